@@ -1,0 +1,176 @@
+"""CPU oracle for the DGQ A8W4 linear layer (test infrastructure, not the product).
+
+Thin numpy/ctypes front end over ``dgq_oracle.c``.  Only the tests, the smoke
+check and the benchmark's ``cpu_baseline`` leg may import this package; it
+imports nothing from the HIP path.
+
+Each function cites the passage of the paper (arXiv 2310.04836) it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dgq_oracle.c")
+_LIB = os.path.join(_HERE, "libdgq_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile dgq_oracle.c with gcc (-O2, OpenMP, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-fno-fast-math",
+             "-ffp-contract=off", "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.dgq_oracle_expand.restype = ctypes.c_long
+        _lib.dgq_oracle_gemm_i32.restype = ctypes.c_long
+        _lib.dgq_oracle_pack.restype = ctypes.c_long
+        _lib.dgq_oracle_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def threads() -> int:
+    return int(_L().dgq_oracle_threads())
+
+
+def quantize_weights_rtn(W, group: int):
+    """RTN dual-grained quantizer (Table 1 "RTN"; Section 3.1 symmetric scale; Eq. 5 decoupling).
+
+    W: fp16/fp32 [K, N].  Returns (w4 int8 [K,N], s2 uint8 [K/group,N], s1 float32 [N]).
+    """
+    Wf = _c(W, np.float32)
+    K, N = Wf.shape
+    assert K % group == 0
+    w4 = np.empty((K, N), np.int8)
+    s2 = np.empty((K // group, N), np.uint8)
+    s1 = np.empty(N, np.float32)
+    _L().dgq_oracle_quantize_rtn(_p(Wf), K, N, group, _p(w4), _p(s2), _p(s1))
+    return w4, s2, s1
+
+
+def quant_act(x):
+    """Per-token dynamic symmetric INT8 quantizer (Section 3.1 symmetric case; Section 4.1).
+
+    x: fp16/fp32 [M, K].  Returns (xq int8 [M,K], sx float32 [M]).
+    """
+    xf = _c(x, np.float32)
+    M, K = xf.shape
+    xq = np.empty((M, K), np.int8)
+    sx = np.empty(M, np.float32)
+    _L().dgq_oracle_quant_act(_p(xf), M, K, _p(xq), _p(sx))
+    return xq, sx
+
+
+def expand(w4, s2, group: int):
+    """W_s8 = S2 * W4 (Eq. 2, second line).  Returns (ws8 int8 [K,N], n_out_of_int8)."""
+    w4 = _c(w4, np.int8)
+    s2 = _c(s2, np.uint8)
+    K, N = w4.shape
+    assert s2.shape == (K // group, N) and K % group == 0
+    ws8 = np.empty((K, N), np.int8)
+    bad = _L().dgq_oracle_expand(_p(w4), _p(s2), K, N, group, _p(ws8))
+    return ws8, int(bad)
+
+
+def gemm_i32(xq, ws8):
+    """acc = Xq @ W_s8 in INT32, one reduction over all of K (Eq. 2, third line).
+
+    Returns (acc int32 [M,N], n_outputs_that_would_wrap_int32).
+    """
+    xq = _c(xq, np.int8)
+    ws8 = _c(ws8, np.int8)
+    M, K = xq.shape
+    K2, N = ws8.shape
+    assert K == K2
+    acc = np.empty((M, N), np.int32)
+    wrapped = _L().dgq_oracle_gemm_i32(_p(xq), _p(ws8), M, N, K, _p(acc))
+    return acc, int(wrapped)
+
+
+def epilogue(acc, sx, s1):
+    """O = (s_X * s1) * acc, rounded once to fp16 (Eq. 2, first and third lines)."""
+    acc = _c(acc, np.int32)
+    sx = _c(sx, np.float32)
+    s1 = _c(s1, np.float32)
+    M, N = acc.shape
+    assert sx.shape == (M,) and s1.shape == (N,)
+    out32 = np.empty((M, N), np.float32)
+    _L().dgq_oracle_epilogue(_p(acc), _p(sx), _p(s1), M, N, _p(out32))
+    with np.errstate(over="ignore"):
+        return out32.astype(np.float16)
+
+
+def linear_a8w4(xq, sx, w4, s2, s1, group: int):
+    """The A8W4 linear of Eq. 2 from already-quantized operands.
+
+    Returns (out fp16 [M,N], acc int32 [M,N]).
+    """
+    ws8, bad = expand(w4, s2, group)
+    if bad:
+        raise ValueError("%d expanded weights fall outside INT8" % bad)
+    acc, wrapped = gemm_i32(xq, ws8)
+    if wrapped:
+        raise OverflowError("%d INT32 accumulators would wrap" % wrapped)
+    return epilogue(acc, sx, s1), acc
+
+
+def forward(x, w4, s2, s1, group: int):
+    """Whole hot path: per-token quantization of fp16 x, then linear_a8w4."""
+    xq, sx = quant_act(x)
+    out, acc = linear_a8w4(xq, sx, w4, s2, s1, group)
+    return out, acc, xq, sx
+
+
+def packed_sizes(K: int, N: int, group: int):
+    ng = K // group
+    return K * N // 2, (N // 16) * ((ng + 3) // 4) * 64
+
+
+def pack(w4, s2, group: int):
+    """Device weight format written from the layout text.  Returns (qweight u8, scales u8, n_bad)."""
+    w4 = _c(w4, np.int8)
+    s2 = _c(s2, np.uint8)
+    K, N = w4.shape
+    assert K % 128 == 0 and N % 16 == 0 and group in (64, 128)
+    assert s2.shape == (K // group, N)
+    qb, sb = packed_sizes(K, N, group)
+    qweight = np.empty(qb, np.uint8)
+    scales = np.empty(sb, np.uint8)
+    bad = _L().dgq_oracle_pack(_p(w4), _p(s2), K, N, group, _p(qweight), _p(scales))
+    return qweight, scales, int(bad)
+
+
+def unpack(qweight, scales, K: int, N: int, group: int):
+    """Inverse of pack.  Returns (w4 int8 [K,N], s2 uint8 [K/group,N])."""
+    qweight = _c(qweight, np.uint8)
+    scales = _c(scales, np.uint8)
+    qb, sb = packed_sizes(K, N, group)
+    assert qweight.size == qb and scales.size == sb
+    w4 = np.empty((K, N), np.int8)
+    s2 = np.empty((K // group, N), np.uint8)
+    _L().dgq_oracle_unpack(_p(qweight), _p(scales), K, N, group, _p(w4), _p(s2))
+    return w4, s2
