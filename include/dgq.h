@@ -1,0 +1,168 @@
+/*
+ * dgq.h - C ABI of the MI355X (gfx950) Dual Grained Quantization A8W4 linear layer.
+ *
+ * The layer is Eq. 2 of the DGQ paper (arXiv 2310.04836, Section 3.2):
+ *
+ *     s     = s_X * s1                       per-token x per-output-channel scale
+ *     W_s8  = S2 * (W_u4 - ZP)               INT4 -> INT8, group-wise integer scale
+ *     O_f16 = s * (X_s8 W_s8)                one INT8 GEMM over all of K, INT32 sums
+ *
+ * with a constant zero point ZP = 8 (signed nibbles w4 = W_u4 - 8 in [-8, 7]) and
+ * integer group scales S2 in [1, 15].
+ *
+ * Orientation (the paper's): X is [M][K] (tokens x input channels), W is [K][N]
+ * (input x output channels, N contiguous), groups are `group` consecutive k.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".
+ *   - The caller owns every buffer; the library allocates nothing and returns no
+ *     handles.  Its only state is the path selector of dgq_force_path().
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and the call returns without synchronising.
+ *   - Dense row-major tensors, no strides.  Device pointers must be 16-byte aligned.
+ *   - Shape rules: M >= 1, K % 128 == 0, 128 <= K <= 131072 (INT32 sums cannot wrap),
+ *     N % 16 == 0, group in {64, 128}.
+ *   - Argument errors are found on the host and returned BEFORE anything is launched.
+ *     A return value < 0 means nothing was enqueued.
+ *   - NaN/Inf activations give unspecified outputs, not an error.
+ *   - Thread-safe; calls on the same buffers must be ordered by the caller.
+ */
+#ifndef DGQ_H
+#define DGQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DGQ_API __attribute__((visibility("default")))
+
+typedef int dgq_status;
+enum {
+    DGQ_OK = 0,
+    DGQ_ERR_NULL = -1,      /* a required pointer is NULL                                  */
+    DGQ_ERR_SHAPE = -2,     /* M, N, K or group breaks a shape rule                        */
+    DGQ_ERR_ALIGN = -3,     /* a device pointer is not 16-byte aligned                     */
+    DGQ_ERR_RANGE = -4,     /* reserved for host-visible value-range errors                */
+    DGQ_ERR_WORKSPACE = -5, /* workspace_bytes is smaller than dgq_linear_workspace_bytes  */
+    DGQ_ERR_HIP = -6        /* a HIP call failed; see dgq_last_hip_error()                 */
+};
+
+/* Version of the packed weight format written by dgq_pack_weights (see below). */
+#define DGQ_LAYOUT_VERSION 1
+
+/* Static, NUL-terminated description of a status code (host). */
+DGQ_API const char *dgq_status_string(dgq_status st);
+
+/* hipError_t (as int) of the most recent DGQ_ERR_HIP on the calling thread; 0 if none. */
+DGQ_API int dgq_last_hip_error(void);
+
+/* Returns DGQ_LAYOUT_VERSION of the loaded library. */
+DGQ_API int dgq_layout_version(void);
+
+/*
+ * Sizes of the packed operands of Eq. 2 for a [K][N] weight (host function, nothing
+ * launched): qweight_bytes = K*N/2 (two nibbles per byte),
+ * scales_bytes = (N/16) * ceil((K/group)/4) * 64 (one byte per group and column,
+ * groups padded to a multiple of four).
+ */
+DGQ_API dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_bytes, size_t *scales_bytes);
+
+/*
+ * Scratch needed by dgq_linear_a8w4 / dgq_linear_a8w4_acc for this problem (host
+ * function).  May be 0, in which case `workspace` may be NULL.
+ */
+DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
+
+/*
+ * Offline packing of the integer operands of Eq. 2 (W_u4 - ZP and S2) into the
+ * device format.
+ *   w4       in  [K][N] int8, signed nibble values in [-8, 7]
+ *   s2       in  [K/group][N] uint8, group scales in [1, 15]
+ *   qweight  out dgq_packed_sizes().qweight_bytes
+ *   scales   out dgq_packed_sizes().scales_bytes
+ *   bad_count in/out, nullable: one int32 the caller has zeroed; the kernel adds the
+ *            number of inputs outside the ranges above (such a nibble is packed as 0,
+ *            such a scale as 1).  Inside the ranges |S2 * w4| <= 120, so the paper's
+ *            constraint W_s8 in [-128, 127] (beside Eq. 4) holds for every packed weight.
+ *
+ * Format, version 1.  Stored nibble u = w4 + 8.  qweight is a sequence of 16-byte cells;
+ * element (k, n) is in cell ((n/16)*(K/128) + k/128)*64 + ((k%128)/32)*16 + n%16, byte
+ * k%16 of the cell, low nibble if k%32 < 16, else high nibble.  The scale of group gi
+ * and column n is byte ((n/16)*ceil(ng/4) + gi/4)*64 + (n%16)*4 + gi%4 of scales;
+ * padding bytes are 0.  One 128-bit load per lane therefore feeds two INT8 MFMA
+ * operands (16 consecutive k each) of one column.
+ */
+DGQ_API dgq_status dgq_pack_weights(const int8_t *w4, const uint8_t *s2, int K, int N, int group,
+                            void *qweight, void *scales, int32_t *bad_count, void *stream);
+
+/*
+ * Test hook: expands packed weights back to W_s8[K][N] = S2 * (W_u4 - 8) (second line
+ * of Eq. 2), the tensor that otherwise only exists in registers.
+ */
+DGQ_API dgq_status dgq_unpack_weights(const void *qweight, const void *scales, int K, int N, int group,
+                              int8_t *w_s8, void *stream);
+
+/*
+ * Round-to-nearest dual-grained weight quantizer (the "RTN" scheme of Table 1; symmetric
+ * scale of Section 3.1; S = s1 * S2 of Eq. 5), used to turn synthetic fp16 weights into
+ * the integer operands:
+ *   S'[j][n] = max_{k in group j}|W[k][n]| / 7,  s1[n] = max_j S'[j][n] / 15,
+ *   s2[j][n] = clamp(round(S'/s1), 1, 15),  w4 = clamp(round(W / (s1*s2)), -8, 7),
+ * fp32 arithmetic, IEEE division, ties to even; a zero column gives s1=1, s2=1, w4=0.
+ *   W   in  [K][N] fp16 (raw bits as uint16_t)
+ *   w4  out [K][N] int8;  s2 out [K/group][N] uint8;  s1 out [N] float
+ */
+DGQ_API dgq_status dgq_quantize_weights_rtn(const uint16_t *W, int K, int N, int group,
+                                    int8_t *w4, uint8_t *s2, float *s1, void *stream);
+
+/*
+ * Per-token dynamic symmetric INT8 activation quantizer (Section 3.1 symmetric case,
+ * "per-token dynamic activation quantization" of Section 4.1):
+ *   a = max_k |x[m][k]|,  sx[m] = a/127,  xq = clamp(round(x * (127/a)), -127, 127),
+ * fp32, ties to even; a zero row gives sx = 0, xq = 0.
+ *   x   in  [M][K] fp16 (raw bits);  xq out [M][K] int8;  sx out [M] float
+ */
+DGQ_API dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, void *stream);
+
+/*
+ * Fused A8W4 linear: in-register INT4->INT8 expansion, INT8 MFMA GEMM with INT32
+ * accumulation over all of K, scale epilogue (all three lines of Eq. 2):
+ *   out[m][n] = fp16( (sx[m] * s1[n]) * (float) sum_k xq[m][k] * (s2[k/group][n] * w4[k][n]) )
+ *   xq, sx            in  as written by dgq_quant_act
+ *   qweight, scales   in  as written by dgq_pack_weights for the same K, N, group
+ *   s1                in  [N] float
+ *   out               out [M][N] fp16 (raw bits)
+ *   workspace         scratch of at least dgq_linear_workspace_bytes(); contents
+ *                     undefined before and after
+ * Small M takes a weight-streaming split-K path, large M a tiled MFMA path; both give
+ * the same INT32 sums.
+ */
+DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight,
+                           const void *scales, const float *s1, uint16_t *out,
+                           int M, int N, int K, int group,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Test hook: same kernels and main loop as dgq_linear_a8w4 but the epilogue stores the
+ * raw INT32 sums X_s8 W_s8 (third line of Eq. 2 before scaling) to acc_out [M][N].
+ */
+DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales,
+                               int32_t *acc_out, int M, int N, int K, int group,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Selects the GEMM path for later dgq_linear_a8w4* calls of this process (host, for
+ * tests and measurements): 0 = choose by M (default), 1 = weight-streaming path,
+ * 2 = tiled path.  Returns the previous value; an unknown value changes nothing and
+ * returns -1.  The weight-streaming path accepts M <= 64 only; forcing it for a larger
+ * M makes the linear calls return DGQ_ERR_SHAPE.
+ */
+DGQ_API int dgq_force_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGQ_H */

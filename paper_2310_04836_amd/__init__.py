@@ -1,0 +1,192 @@
+"""MI355X-native DGQ A8W4 linear layer (arXiv 2310.04836, Eq. 2): thin Python binding.
+
+Every function here only marshals arguments for the C ABI declared in ``include/dgq.h``;
+all arithmetic runs in the HIP kernels of ``libdgq.so``.  PyTorch is used for device
+memory and the current stream, nothing else.  There is no CPU fallback: if the shared
+library cannot be loaded the import of this package raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+__all__ = [
+    "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
+    "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
+    "force_path", "PackedWeight", "STREAM_MAX_M",
+]
+
+STREAM_MAX_M = 64
+
+
+class DGQError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib.dgq_status_string(status).decode()
+        if status == -6:
+            msg += " [hipError %d]" % lib.dgq_last_hip_error()
+        super().__init__("%s: %s (status %d)" % (where, msg, status))
+
+
+def _load() -> ctypes.CDLL:
+    if not _build.is_built():
+        _build.build()
+    L = ctypes.CDLL(_build.LIB)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    psz = ctypes.POINTER(ctypes.c_size_t)
+    L.dgq_status_string.restype = ctypes.c_char_p
+    L.dgq_status_string.argtypes = [i]
+    L.dgq_last_hip_error.restype = i
+    L.dgq_layout_version.restype = i
+    L.dgq_force_path.restype = i
+    L.dgq_force_path.argtypes = [i]
+    L.dgq_packed_sizes.argtypes = [i, i, i, psz, psz]
+    L.dgq_linear_workspace_bytes.argtypes = [i, i, i, i, psz]
+    L.dgq_pack_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp, vp]
+    L.dgq_unpack_weights.argtypes = [vp, vp, i, i, i, vp, vp]
+    L.dgq_quantize_weights_rtn.argtypes = [vp, i, i, i, vp, vp, vp, vp]
+    L.dgq_quant_act.argtypes = [vp, i, i, vp, vp, vp]
+    L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
+                 "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc"):
+        getattr(L, name).restype = i
+    return L
+
+
+lib = _load()
+
+
+def _check(st: int, where: str) -> None:
+    if st != 0:
+        raise DGQError(st, where)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of %s" % (name, dtype))
+    return t
+
+
+def layout_version() -> int:
+    return lib.dgq_layout_version()
+
+
+def force_path(path: int) -> int:
+    """0 = choose by M, 1 = weight-streaming kernel, 2 = tiled kernel.  Returns the old value."""
+    return lib.dgq_force_path(path)
+
+
+def packed_sizes(K: int, N: int, group: int):
+    q, s = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.dgq_packed_sizes(K, N, group, ctypes.byref(q), ctypes.byref(s)), "dgq_packed_sizes")
+    return q.value, s.value
+
+
+def linear_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    b = ctypes.c_size_t()
+    _check(lib.dgq_linear_workspace_bytes(M, N, K, group, ctypes.byref(b)), "dgq_linear_workspace_bytes")
+    return b.value
+
+
+class PackedWeight:
+    """Device buffers of one packed layer: qweight, scales (both uint8), s1 (float32 [N])."""
+
+    def __init__(self, qweight, scales, s1, K, N, group):
+        self.qweight, self.scales, self.s1 = qweight, scales, s1
+        self.K, self.N, self.group = K, N, group
+        self.layout = layout_version()
+
+    @property
+    def nbytes(self) -> int:
+        return self.qweight.numel() + self.scales.numel() + 4 * self.s1.numel()
+
+
+def pack_weights(w4: torch.Tensor, s2: torch.Tensor, s1: torch.Tensor, group: int, return_bad: bool = False):
+    """dgq_pack_weights: w4 int8 [K,N], s2 uint8 [K/group,N], s1 float32 [N] -> PackedWeight."""
+    _dev(w4, torch.int8, "w4"); _dev(s2, torch.uint8, "s2"); _dev(s1, torch.float32, "s1")
+    K, N = w4.shape
+    if tuple(s2.shape) != (K // group, N) or tuple(s1.shape) != (N,):
+        raise ValueError("s2/s1 shapes do not match w4 and group")
+    qb, sb = packed_sizes(K, N, group)
+    qweight = torch.empty(qb, dtype=torch.uint8, device=w4.device)
+    scales = torch.empty(sb, dtype=torch.uint8, device=w4.device)
+    bad = torch.zeros(1, dtype=torch.int32, device=w4.device)
+    _check(lib.dgq_pack_weights(_ptr(w4), _ptr(s2), K, N, group, _ptr(qweight), _ptr(scales), _ptr(bad),
+                                _stream()), "dgq_pack_weights")
+    pw = PackedWeight(qweight, scales, s1, K, N, group)
+    if return_bad:
+        return pw, int(bad.item())
+    return pw
+
+
+def unpack_weights(pw: PackedWeight) -> torch.Tensor:
+    """dgq_unpack_weights: W_s8 int8 [K,N]."""
+    out = torch.empty((pw.K, pw.N), dtype=torch.int8, device=pw.qweight.device)
+    _check(lib.dgq_unpack_weights(_ptr(pw.qweight), _ptr(pw.scales), pw.K, pw.N, pw.group, _ptr(out), _stream()),
+           "dgq_unpack_weights")
+    return out
+
+
+def quantize_weights_rtn(W: torch.Tensor, group: int):
+    """dgq_quantize_weights_rtn: fp16 [K,N] -> (w4 int8 [K,N], s2 uint8 [K/group,N], s1 float32 [N])."""
+    _dev(W, torch.float16, "W")
+    K, N = W.shape
+    w4 = torch.empty((K, N), dtype=torch.int8, device=W.device)
+    s2 = torch.empty((K // group if group else 0, N), dtype=torch.uint8, device=W.device)
+    s1 = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(lib.dgq_quantize_weights_rtn(_ptr(W), K, N, group, _ptr(w4), _ptr(s2), _ptr(s1), _stream()),
+           "dgq_quantize_weights_rtn")
+    return w4, s2, s1
+
+
+def quant_act(x: torch.Tensor, xq: torch.Tensor = None, sx: torch.Tensor = None):
+    """dgq_quant_act: fp16 [M,K] -> (xq int8 [M,K], sx float32 [M])."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if sx is None:
+        sx = torch.empty(M, dtype=torch.float32, device=x.device)
+    _check(lib.dgq_quant_act(_ptr(x), M, K, _ptr(xq), _ptr(sx), _stream()), "dgq_quant_act")
+    return xq, sx
+
+
+def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch.Tensor = None,
+                workspace: torch.Tensor = None) -> torch.Tensor:
+    """dgq_linear_a8w4: fp16 [M,N] = (sx x s1) * (xq @ expand(qweight))."""
+    _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx")
+    M, K = xq.shape
+    if K != pw.K:
+        raise ValueError("xq has K=%d but the packed weight has K=%d" % (K, pw.K))
+    if out is None:
+        out = torch.empty((M, pw.N), dtype=torch.float16, device=xq.device)
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.dgq_linear_a8w4(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
+                               M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
+    return out
+
+
+def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor = None) -> torch.Tensor:
+    """dgq_linear_a8w4_acc: raw INT32 sums [M,N] of the same kernels (test hook)."""
+    _dev(xq, torch.int8, "xq")
+    M, K = xq.shape
+    if K != pw.K:
+        raise ValueError("xq has K=%d but the packed weight has K=%d" % (K, pw.K))
+    acc = torch.empty((M, pw.N), dtype=torch.int32, device=xq.device)
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.dgq_linear_a8w4_acc(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group,
+                                   _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4_acc")
+    return acc

@@ -1,0 +1,159 @@
+// extern "C" boundary of libdgq.so: argument validation on the host, then one launcher.
+// Every check happens before anything is enqueued.
+#include <atomic>
+
+#include "dgq_device.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+std::atomic<int> g_force_path{0};
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+dgq_status check_shape(int N, int K, int group)
+{
+    if (group != 64 && group != 128) return DGQ_ERR_SHAPE;
+    if (K < 128 || K > 131072 || (K % 128) != 0) return DGQ_ERR_SHAPE;
+    if (N < 16 || (N % 16) != 0) return DGQ_ERR_SHAPE;
+    // cell and element indices are computed in 32 bits in places; keep K*N below 2^36
+    if ((long long)K * (long long)N > (1LL << 36)) return DGQ_ERR_SHAPE;
+    return DGQ_OK;
+}
+
+dgq_status hip_result(hipError_t e)
+{
+    if (e == hipSuccess) return DGQ_OK;
+    g_last_hip_error = (int)e;
+    return DGQ_ERR_HIP;
+}
+
+dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    const int forced = g_force_path.load(std::memory_order_relaxed);
+    bool stream_path = a.M <= dgq::kStreamMaxM;
+    if (forced == 1) {
+        if (a.M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
+        stream_path = true;
+    } else if (forced == 2) {
+        stream_path = false;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return hip_result(stream_path ? dgq::launch_linear_stream(a, st) : dgq::launch_linear_tiled(a, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dgq_status_string(dgq_status st)
+{
+    switch (st) {
+    case DGQ_OK: return "ok";
+    case DGQ_ERR_NULL: return "a required pointer is NULL";
+    case DGQ_ERR_SHAPE: return "M, N, K or group breaks a shape rule";
+    case DGQ_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case DGQ_ERR_RANGE: return "value out of range";
+    case DGQ_ERR_WORKSPACE: return "workspace too small";
+    case DGQ_ERR_HIP: return "a HIP call failed (see dgq_last_hip_error)";
+    default: return "unknown dgq status";
+    }
+}
+
+int dgq_last_hip_error(void) { return g_last_hip_error; }
+
+int dgq_layout_version(void) { return DGQ_LAYOUT_VERSION; }
+
+int dgq_force_path(int path)
+{
+    if (path < 0 || path > 2) return -1;
+    return g_force_path.exchange(path);
+}
+
+dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_bytes, size_t *scales_bytes)
+{
+    if (!qweight_bytes || !scales_bytes) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    const size_t ng = (size_t)K / group;
+    *qweight_bytes = (size_t)K * (size_t)N / 2;
+    *scales_bytes = ((size_t)N / 16) * ((ng + 3) / 4) * 64;
+    return DGQ_OK;
+}
+
+dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes)
+{
+    if (!bytes) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    *bytes = 0;  // split-K partial sums are combined in LDS; no global scratch is used
+    return DGQ_OK;
+}
+
+dgq_status dgq_pack_weights(const int8_t *w4, const uint8_t *s2, int K, int N, int group, void *qweight,
+                            void *scales, int32_t *bad_count, void *stream)
+{
+    if (!w4 || !s2 || !qweight || !scales) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(w4) || !aligned16(s2) || !aligned16(qweight) || !aligned16(scales)) return DGQ_ERR_ALIGN;
+    if (bad_count && (reinterpret_cast<uintptr_t>(bad_count) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_pack(w4, s2, K, N, group, qweight, scales, bad_count,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_unpack_weights(const void *qweight, const void *scales, int K, int N, int group, int8_t *w_s8,
+                              void *stream)
+{
+    if (!qweight || !scales || !w_s8) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(qweight) || !aligned16(scales) || !aligned16(w_s8)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_unpack(qweight, scales, K, N, group, w_s8, static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_quantize_weights_rtn(const uint16_t *W, int K, int N, int group, int8_t *w4, uint8_t *s2,
+                                    float *s1, void *stream)
+{
+    if (!W || !w4 || !s2 || !s1) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(W) || !aligned16(w4) || !aligned16(s2) || !aligned16(s1)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_quantize_rtn(W, K, N, group, w4, s2, s1, static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, void *stream)
+{
+    if (!x || !xq || !sx) return DGQ_ERR_NULL;
+    if (M < 1 || K < 128 || K > 131072 || (K % 128) != 0) return DGQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_quant_act(x, M, K, xq, sx, static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight, const void *scales,
+                           const float *s1, uint16_t *out, int M, int N, int K, int group, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    if (!xq || !sx || !qweight || !scales || !s1 || !out) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(xq) || !aligned16(qweight) || !aligned16(scales) || !aligned16(out) ||
+        (reinterpret_cast<uintptr_t>(sx) & 3u) || (reinterpret_cast<uintptr_t>(s1) & 3u))
+        return DGQ_ERR_ALIGN;
+    dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
+                      s1, out, nullptr, M, N, K, group};
+    return run_linear(a, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales, int32_t *acc_out,
+                               int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    if (!xq || !qweight || !scales || !acc_out) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(xq) || !aligned16(qweight) || !aligned16(scales) || !aligned16(acc_out)) return DGQ_ERR_ALIGN;
+    dgq::LinearArgs a{xq, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
+                      nullptr, nullptr, acc_out, M, N, K, group};
+    return run_linear(a, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,87 @@
+// Internal declarations shared by the HIP translation units of libdgq.so.
+// Not part of the public ABI (that is include/dgq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dgq.h"
+
+namespace dgq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned short v2u16 __attribute__((ext_vector_type(2)));
+
+// ---- INT4 -> INT8 expansion in registers (second line of Eq. 2) -------------------
+//
+// A 32-bit word holds eight stored nibbles u = w4 + 8.  The even nibbles (low halves of
+// the four bytes) and the odd nibbles (high halves) are separated into two words of four
+// bytes each; every byte is then turned into the signed INT8 value s2 * (u - 8):
+//
+//   s2*u + (128 - 8*s2)  lies in [8, 233] for s2 in [1, 15], u in [0, 15], so a packed
+//   16-bit multiply-add over byte pairs never carries from one byte into the next, and
+//   flipping bit 7 of each byte subtracts the 128 again in two's complement.
+struct GroupScale {
+    uint32_t mul;  // s2 in both 16-bit halves
+    uint32_t add;  // (128 - 8*s2) in all four bytes
+};
+
+__device__ __forceinline__ GroupScale make_group_scale(uint32_t s2)
+{
+    GroupScale g;
+    g.mul = s2 | (s2 << 16);
+    // 0x8080 - s2*0x0808 per 16-bit half, as one packed multiply-add (mod 2^16)
+    const v2u16 m = __builtin_bit_cast(v2u16, g.mul);
+    const v2u16 r = m * (v2u16){0xF7F8, 0xF7F8} + (v2u16){0x8080, 0x8080};
+    g.add = __builtin_bit_cast(uint32_t, r);
+    return g;
+}
+
+__device__ __forceinline__ uint32_t scale_bytes(uint32_t four_nibbles_in_bytes, const GroupScale &g)
+{
+    v2u16 a = __builtin_bit_cast(v2u16, four_nibbles_in_bytes);
+    v2u16 m = __builtin_bit_cast(v2u16, g.mul);
+    v2u16 c = __builtin_bit_cast(v2u16, g.add);
+    v2u16 r = a * m + c;
+    return __builtin_bit_cast(uint32_t, r) ^ 0x80808080u;
+}
+
+// One 16-byte cell (32 nibbles of one column, 32 consecutive k) -> two MFMA operands:
+// `first` = W_s8 of the cell's k 0..15 (low nibbles), `second` = k 16..31 (high nibbles).
+__device__ __forceinline__ void expand_cell(const uint4 &q, const GroupScale &g, v4i &first, v4i &second)
+{
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        first[v] = (int)scale_bytes(w[v] & 0x0F0F0F0Fu, g);
+        second[v] = (int)scale_bytes((w[v] >> 4) & 0x0F0F0F0Fu, g);
+    }
+}
+
+// ---- kernel launchers (defined one per .hip file) ----------------------------------
+hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
+hipError_t launch_quantize_rtn(const uint16_t *W, int K, int N, int group, int8_t *w4, uint8_t *s2,
+                               float *s1, hipStream_t st);
+hipError_t launch_pack(const int8_t *w4, const uint8_t *s2, int K, int N, int group, void *qweight,
+                       void *scales, int32_t *bad_count, hipStream_t st);
+hipError_t launch_unpack(const void *qweight, const void *scales, int K, int N, int group,
+                         int8_t *w_s8, hipStream_t st);
+
+struct LinearArgs {
+    const int8_t *xq;
+    const float *sx;       // null in acc mode
+    const uint4 *qweight;
+    const uint32_t *scales;
+    const float *s1;       // null in acc mode
+    uint16_t *out;         // fp16 bits, null in acc mode
+    int32_t *acc_out;      // null in fp16 mode
+    int M, N, K, group;
+};
+// Largest M the weight-streaming kernel takes.
+constexpr int kStreamMaxM = 64;
+hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
+hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);
+
+}  // namespace dgq

@@ -1,0 +1,135 @@
+// Per-token dynamic symmetric INT8 activation quantizer (Section 3.1 symmetric case with
+// 8 bits; "per-token dynamic activation quantization", Section 4.1).
+//
+// One 256-thread workgroup per token.  The row is read once as 128-bit vectors of eight
+// fp16 values and kept in registers; the absolute maximum is taken on the raw bit patterns
+// (for non-negative fp16 numbers the integer order of the bits is the numeric order), reduced
+// across the wavefront with lane exchanges and across the four wavefronts through LDS; then
+// every value is scaled, rounded to nearest-even and stored as eight packed bytes.
+#include "dgq_device.hpp"
+
+namespace dgq {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t absmax_bits(const uint4 &v, uint32_t m)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+        m = lo > m ? lo : m;
+        m = hi > m ? hi : m;
+    }
+    return m;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+
+__device__ __forceinline__ uint32_t quant_one(uint32_t hbits, float inv)
+{
+    float q = rintf(half_bits_to_float(hbits) * inv);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (uint32_t)((int)q) & 0xFFu;
+}
+
+__device__ __forceinline__ uint2 quant_vec(const uint4 &v, float inv)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        b[2 * i] = quant_one(w[i] & 0xFFFFu, inv);
+        b[2 * i + 1] = quant_one(w[i] >> 16, inv);
+    }
+    uint2 r;
+    r.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+    r.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
+    return r;
+}
+
+// VPT > 0: each thread caches VPT vectors (K <= 2048 * VPT).  VPT == 0: any K, the row is read
+// twice (the second read hits in cache).
+template <int VPT>
+__global__ __launch_bounds__(kThreads) void quant_act_kernel(const uint16_t *__restrict__ x, int M, int K,
+                                                             int8_t *__restrict__ xq,
+                                                             float *__restrict__ sx)
+{
+    __shared__ uint32_t wave_m[kThreads / 64];
+    const int m = blockIdx.x;
+    const int nvec = K >> 3;
+    const uint4 *row = reinterpret_cast<const uint4 *>(x + (size_t)m * K);
+    uint2 *dst = reinterpret_cast<uint2 *>(xq + (size_t)m * K);
+
+    uint4 cache[VPT > 0 ? VPT : 1];
+    uint32_t mx = 0;
+    if (VPT > 0) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            int idx = threadIdx.x + i * kThreads;
+            cache[i] = idx < nvec ? row[idx] : make_uint4(0, 0, 0, 0);
+            mx = absmax_bits(cache[i], mx);
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < nvec; idx += kThreads) mx = absmax_bits(row[idx], mx);
+    }
+    mx = wave_max_u32(mx);
+    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = wave_m[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) mx = wave_m[w] > mx ? wave_m[w] : mx;
+
+    const float a = half_bits_to_float(mx);
+    float inv = 0.0f, s = 0.0f;
+    if (a != 0.0f) {
+        s = a / 127.0f;
+        inv = 127.0f / a;
+    }
+    if (threadIdx.x == 0) sx[m] = s;
+    // a == 0: inv = 0 makes every product +-0, which rounds to 0.
+    if (VPT > 0) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            int idx = threadIdx.x + i * kThreads;
+            if (idx < nvec) dst[idx] = quant_vec(cache[i], inv);
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < nvec; idx += kThreads) dst[idx] = quant_vec(row[idx], inv);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st)
+{
+    dim3 grid(M), block(kThreads);
+    const int nvec = K / 8;
+    if (nvec <= 2 * kThreads)
+        hipLaunchKernelGGL(quant_act_kernel<2>, grid, block, 0, st, x, M, K, xq, sx);
+    else if (nvec <= 4 * kThreads)
+        hipLaunchKernelGGL(quant_act_kernel<4>, grid, block, 0, st, x, M, K, xq, sx);
+    else if (nvec <= 8 * kThreads)
+        hipLaunchKernelGGL(quant_act_kernel<8>, grid, block, 0, st, x, M, K, xq, sx);
+    else if (nvec <= 12 * kThreads)
+        hipLaunchKernelGGL(quant_act_kernel<12>, grid, block, 0, st, x, M, K, xq, sx);
+    else
+        hipLaunchKernelGGL(quant_act_kernel<0>, grid, block, 0, st, x, M, K, xq, sx);
+    return hipGetLastError();
+}
+
+}  // namespace dgq

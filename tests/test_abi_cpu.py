@@ -1,0 +1,96 @@
+"""The C-ABI library loads without a GPU, exports what include/dgq.h declares, and rejects
+bad arguments on the host before anything could be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dgq():
+    import paper_2310_04836_amd as m
+    return m
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "dgq.h")).read()
+    return re.findall(r"DGQ_API\s+[\w\s\*]+?\b(dgq_\w+)\s*\(", src)
+
+
+def test_header_symbols_are_exported(dgq):
+    names = _declared()
+    assert len(names) == 12 and len(set(names)) == 12
+    for n in names:
+        assert hasattr(dgq.lib, n), n
+
+
+def test_no_internal_symbols_leak(dgq):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", dgq._build.LIB], capture_output=True, text=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if " T " in l}
+    assert exported == set(_declared())
+
+
+def test_status_strings_and_versions(dgq):
+    assert dgq.lib.dgq_status_string(0) == b"ok"
+    for st in range(-6, 0):
+        assert len(dgq.lib.dgq_status_string(st)) > 3
+    assert dgq.layout_version() == 1
+    assert dgq.lib.dgq_last_hip_error() == 0
+
+
+def test_packed_sizes(dgq):
+    assert dgq.packed_sizes(4096, 12288, 128) == (4096 * 12288 // 2, 12288 // 16 * 8 * 64)
+    assert dgq.packed_sizes(11008, 4096, 128) == (11008 * 4096 // 2, 256 * 22 * 64)  # 86 groups -> 22 words
+    assert dgq.packed_sizes(256, 32, 64) == (4096, 2 * 1 * 64)
+    assert dgq.linear_workspace_bytes(16, 4096, 4096, 128) == 0
+
+
+@pytest.mark.parametrize("K,N,g", [(100, 16, 128), (0, 16, 128), (128, 8, 128), (128, 24, 128),
+                                   (128, 16, 32), (128, 16, 0), (131072 + 128, 16, 128), (64, 16, 64)])
+def test_shape_rules(dgq, K, N, g):
+    with pytest.raises(dgq.DGQError) as e:
+        dgq.packed_sizes(K, N, g)
+    assert e.value.status == -2
+
+
+def test_argument_checks_come_before_any_launch(dgq):
+    L = dgq.lib
+    good = 0x10000        # never dereferenced: every call below must fail validation first
+    odd = 0x10008
+    # NULL pointers
+    assert L.dgq_quant_act(None, 1, 128, good, good, None) == -1
+    assert L.dgq_quant_act(good, 1, 128, None, good, None) == -1
+    assert L.dgq_linear_a8w4(good, good, good, good, None, good, 1, 16, 128, 128, None, 0, None) == -1
+    assert L.dgq_linear_a8w4_acc(good, good, good, None, 1, 16, 128, 128, None, 0, None) == -1
+    assert L.dgq_pack_weights(good, None, 128, 16, 128, good, good, None, None) == -1
+    assert L.dgq_unpack_weights(good, good, 128, 16, 128, None, None) == -1
+    assert L.dgq_quantize_weights_rtn(good, 128, 16, 128, good, good, None, None) == -1
+    # shapes
+    assert L.dgq_quant_act(good, 0, 128, good, good, None) == -2
+    assert L.dgq_quant_act(good, 1, 100, good, good, None) == -2
+    assert L.dgq_linear_a8w4(good, good, good, good, good, good, 0, 16, 128, 128, None, 0, None) == -2
+    assert L.dgq_linear_a8w4(good, good, good, good, good, good, 1, 16, 128, 96, None, 0, None) == -2
+    assert L.dgq_linear_a8w4(good, good, good, good, good, good, 1, 20, 128, 128, None, 0, None) == -2
+    assert L.dgq_linear_a8w4_acc(good, good, good, good, 1, 16, 192, 64, None, 0, None) == -2
+    assert L.dgq_pack_weights(good, good, 128, 16, 100, good, good, None, None) == -2
+    # alignment
+    assert L.dgq_quant_act(odd, 1, 128, good, good, None) == -3
+    assert L.dgq_linear_a8w4(good, good, odd, good, good, good, 1, 16, 128, 128, None, 0, None) == -3
+    assert L.dgq_pack_weights(good, good, 128, 16, 128, odd, good, None, None) == -3
+    assert L.dgq_pack_weights(good, good, 128, 16, 128, good, good, 0x10002, None) == -3
+
+
+def test_force_path_selector(dgq):
+    assert dgq.force_path(7) == -1
+    old = dgq.force_path(1)
+    try:
+        # the streaming path refuses M > 64 on the host
+        good = 0x10000
+        assert dgq.lib.dgq_linear_a8w4_acc(good, good, good, good, 65, 16, 128, 128, None, 0, None) == -2
+        assert dgq.force_path(2) == 1
+    finally:
+        dgq.force_path(old)

@@ -1,0 +1,282 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Integers (packed bytes, quantized weights and activations, INT32 sums) must be bit-exact.
+The fp16 output must be within max(1e-3 relative, 1 fp16 ulp) of the oracle's.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dgq():
+    import paper_2310_04836_amd as m
+    return m
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    return t
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def assert_fp16_close(got, ref):
+    """|got - ref| <= max(1e-3 |ref|, 1 ulp of ref in fp16)."""
+    assert got.dtype == np.float16 and ref.dtype == np.float16
+    g = got.astype(np.float64)
+    r = ref.astype(np.float64)
+    ulp = np.spacing(np.abs(ref)).astype(np.float64)
+    bad = ~(np.abs(g - r) <= np.maximum(1e-3 * np.abs(r), ulp))
+    assert not bad.any(), "%d of %d outputs outside tolerance, first at %s" % (
+        bad.sum(), bad.size, np.argwhere(bad)[0])
+
+
+# ----------------------------------------------------------------------------
+# a1: per-token activation quantizer
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("M,K", [(8, 1024), (1, 4096), (16, 11008), (5, 22016), (3, 128),
+                                 (33, 5120), (2, 32768), (4, 24576 + 128)])
+def test_quant_act_bit_exact(dgq, torch, M, K):
+    x = workloads.activations(M, K, seed=M + K)
+    if M > 2:
+        x[1] = 0                      # a zero token
+        x[2, : K // 2] = 0
+    xq, sx = dgq.quant_act(dev(torch, x))
+    oxq, osx = oracle.quant_act(x)
+    assert np.array_equal(host(xq), oxq)
+    assert np.array_equal(host(sx).view(np.uint32), osx.view(np.uint32))
+
+
+def test_quant_act_ties_and_extremes(dgq, torch):
+    K = 128
+    x = np.zeros((3, K), np.float16)
+    x[0, :8] = [127, 0.5, 1.5, 2.5, -0.5, -2.5, 3.5, -126.5]     # inv = 1: halves round to even
+    x[1, :3] = [65504, -65504, 1.0]                               # fp16 max
+    x[2, :3] = [6e-8, -6e-8, 0]                                   # fp16 subnormals
+    xq, sx = dgq.quant_act(dev(torch, x))
+    oxq, osx = oracle.quant_act(x)
+    assert host(xq)[0, :8].tolist() == [127, 0, 2, 2, 0, -2, 4, -126]
+    assert np.array_equal(host(xq), oxq) and np.array_equal(host(sx), osx)
+
+
+# ----------------------------------------------------------------------------
+# weight side: RTN quantizer, pack, unpack
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("K,N,g", [(1024, 1024, 128), (512, 96, 64), (1408, 80, 128)])
+def test_rtn_quantizer_bit_exact(dgq, torch, K, N, g):
+    W = workloads.weights(K, N, seed=K + N)
+    W[:, 3] = 0                       # an all-zero output channel
+    W[: g, 5] = 0                     # an all-zero group
+    w4, s2, s1 = dgq.quantize_weights_rtn(dev(torch, W), g)
+    ow4, os2, os1 = oracle.quantize_weights_rtn(W, g)
+    assert np.array_equal(host(w4), ow4)
+    assert np.array_equal(host(s2), os2)
+    assert np.array_equal(host(s1).view(np.uint32), os1.view(np.uint32))
+
+
+@pytest.mark.parametrize("K,N,g", [(128, 16, 128), (256, 48, 64), (1408, 272, 128), (640, 4096 + 16, 64)])
+def test_pack_bytes_and_unpack(dgq, torch, K, N, g):
+    w4, s2, s1 = workloads.integer_weights(K, N, g, seed=K * 3 + N)
+    pw, bad = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g, return_bad=True)
+    oq, osc, obad = oracle.pack(w4, s2, g)
+    assert bad == 0 and obad == 0
+    assert np.array_equal(host(pw.qweight), oq)
+    assert np.array_equal(host(pw.scales), osc)
+    ws8, nbad = oracle.expand(w4, s2, g)
+    assert nbad == 0
+    assert np.array_equal(host(dgq.unpack_weights(pw)), ws8)
+
+
+def test_pack_counts_out_of_range(dgq, torch):
+    K, N, g = 128, 32, 64
+    w4 = np.zeros((K, N), np.int8)
+    s2 = np.ones((K // g, N), np.uint8)
+    w4[3, 3], w4[4, 4], s2[0, 5], s2[1, 6] = 8, -9, 0, 16
+    pw, bad = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, np.ones(N, np.float32)), g,
+                               return_bad=True)
+    oq, osc, obad = oracle.pack(w4, s2, g)
+    assert bad == obad == 4
+    assert np.array_equal(host(pw.qweight), oq) and np.array_equal(host(pw.scales), osc)
+
+
+# ----------------------------------------------------------------------------
+# a2 + a3: expansion and INT8 GEMM, raw INT32 sums
+# ----------------------------------------------------------------------------
+def _acc_case(dgq, torch, M, K, N, g, seed, path=0, onehot=False):
+    w4, s2, s1 = workloads.integer_weights(K, N, g, seed)
+    if onehot:
+        xq = np.zeros((M, K), np.int8)
+        ks = (np.arange(M) * 37 + 5) % K
+        xq[np.arange(M), ks] = 1
+    else:
+        xq, _ = workloads.integer_activations(M, K, seed)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    old = dgq.force_path(path)
+    try:
+        acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
+    finally:
+        dgq.force_path(old)
+    ws8, _ = oracle.expand(w4, s2, g)
+    if onehot:
+        # closed form: a one-hot token reads out one row of W_s8
+        assert np.array_equal(acc, ws8[ks].astype(np.int32))
+    oacc, wrapped = oracle.gemm_i32(xq, ws8)
+    assert wrapped == 0
+    assert np.array_equal(acc, oacc), "mismatch at %s" % (np.argwhere(acc != oacc)[:4].tolist(),)
+
+
+@pytest.mark.parametrize("g", [128, 64])
+@pytest.mark.parametrize("M", [1, 16, 40])
+def test_onehot_probe_stream_path(dgq, torch, M, g):
+    """Reads single rows of W_s8 through the GEMM: pins nibble order, k pairing and lane maps."""
+    _acc_case(dgq, torch, M, 512, 64, g, seed=M, path=1, onehot=True)
+
+
+@pytest.mark.parametrize("g", [128, 64])
+@pytest.mark.parametrize("M", [1, 130])
+def test_onehot_probe_tiled_path(dgq, torch, M, g):
+    _acc_case(dgq, torch, M, 512, 320, g, seed=M, path=2, onehot=True)
+
+
+@pytest.mark.parametrize("M,K,N,g", [
+    (1, 128, 16, 128), (1, 128, 16, 64), (8, 1024, 1024, 128), (4, 4096, 256, 64), (16, 1408, 80, 128),
+    (17, 2048, 48, 128), (32, 640, 112, 64), (33, 1152, 64, 128), (64, 3072, 32, 64), (3, 11008, 64, 128),
+])
+def test_acc_bit_exact_stream_path(dgq, torch, M, K, N, g):
+    _acc_case(dgq, torch, M, K, N, g, seed=M * 7 + N, path=1)
+
+
+@pytest.mark.parametrize("M,K,N,g", [
+    (1, 128, 16, 128), (65, 256, 256, 64), (128, 1024, 256, 128), (129, 512, 272, 128), (200, 1408, 528, 64),
+    (300, 640, 1040, 128), (512, 1024, 512, 64), (16, 384, 4096 + 48, 128),
+])
+def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
+    _acc_case(dgq, torch, M, K, N, g, seed=M * 5 + N, path=2)
+
+
+def test_both_paths_and_split_factors_agree(dgq, torch):
+    """Integer sums do not depend on how K is split between wavefronts or on the path."""
+    M, N, g = 48, 128, 128
+    for K in (256, 1152, 4096):       # 2, 9 and 32 steps -> different per-wave split patterns
+        w4, s2, s1 = workloads.integer_weights(K, N, g, K)
+        xq, _ = workloads.integer_activations(M, K, K)
+        pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+        res = []
+        for path in (1, 2):
+            old = dgq.force_path(path)
+            try:
+                res.append(host(dgq.linear_a8w4_acc(dev(torch, xq), pw)))
+            finally:
+                dgq.force_path(old)
+        assert np.array_equal(res[0], res[1])
+        assert np.array_equal(res[0].astype(np.int64), xq.astype(np.int64) @ (
+            np.repeat(s2.astype(np.int64), g, axis=0) * w4))
+
+
+def test_extreme_values_no_overflow(dgq, torch):
+    # largest magnitudes everywhere: xq = -127, w4 = -8, s2 = 15 -> acc = 127*120*K
+    M, K, N, g = 2, 22016, 16, 128
+    w4 = np.full((K, N), -8, np.int8)
+    s2 = np.full((K // g, N), 15, np.uint8)
+    xq = np.full((M, K), -127, np.int8)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, np.ones(N, np.float32)), g)
+    acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
+    assert (acc == 127 * 120 * K).all()
+
+
+# ----------------------------------------------------------------------------
+# a4 and the whole path: fp16 output
+# ----------------------------------------------------------------------------
+def _forward_case(dgq, torch, M, K, N, g, seed, frac=0.01, mult=20.0, cols=None):
+    x = workloads.activations(M, K, seed, frac, mult)
+    W = workloads.weights(K, N, seed)
+    w4, s2, s1 = dgq.quantize_weights_rtn(dev(torch, W), g)
+    pw = dgq.pack_weights(w4, s2, s1, g)
+    xq, sx = dgq.quant_act(dev(torch, x))
+    out = host(dgq.linear_a8w4(xq, sx, pw))
+    acc = host(dgq.linear_a8w4_acc(xq, pw))
+    if cols is not None:           # oracle on a sample of output channels
+        W = np.ascontiguousarray(W[:, cols])
+        out, acc = out[:, cols], acc[:, cols]
+        w4, s2, s1 = w4[:, cols], s2[:, cols], s1[cols]
+    ow4, os2, os1 = oracle.quantize_weights_rtn(W, g)
+    assert np.array_equal(host(w4), ow4) and np.array_equal(host(s2), os2) and np.array_equal(host(s1), os1)
+    oout, oacc, oxq, osx = oracle.forward(x, ow4, os2, os1, g)
+    assert np.array_equal(host(xq), oxq) and np.array_equal(host(sx), osx)
+    assert np.array_equal(acc, oacc)
+    assert_fp16_close(out, oout)
+    return out, oout
+
+
+def test_config0_whole_path(dgq, torch):
+    out, oout = _forward_case(dgq, torch, 8, 1024, 1024, 128, seed=0)
+    assert np.isfinite(out).all()
+
+
+@pytest.mark.parametrize("M,K,N,g", [(1, 1024, 256, 64), (16, 2048, 512, 128), (50, 1408, 272, 128),
+                                     (129, 1024, 528, 64), (384, 512, 256, 128)])
+def test_whole_path_small(dgq, torch, M, K, N, g):
+    _forward_case(dgq, torch, M, K, N, g, seed=M + N)
+
+
+def test_epilogue_scales_fp16_rounding(dgq, torch):
+    """Known sums times awkward scales: checks (sx*s1)*acc order, int->float and fp16 rounding."""
+    M, K, N, g = 4, 128, 16, 128
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 9)
+    xq, sx = workloads.integer_activations(M, K, 9)
+    s1 = (s1 * np.float32(3.3)).astype(np.float32)
+    sx[0] = 0.0                                   # zero token scale -> exact zeros
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw))
+    oout, _ = oracle.linear_a8w4(xq, sx, w4, s2, s1, g)
+    assert (out[0] == 0).all()
+    assert_fp16_close(out, oout)
+
+
+# ----------------------------------------------------------------------------
+# full-size LLaMA shapes, in the launch configuration the benchmark times
+# ----------------------------------------------------------------------------
+def _cols(N, n=48, seed=0):
+    rng = np.random.default_rng(seed)
+    c = np.unique(np.concatenate([[0, 15, 16, N - 1], rng.choice(N, n, replace=False)]))
+    return c
+
+
+@pytest.mark.parametrize("shape", ["qkv", "o", "gate_up", "down"])
+def test_llama7b_decode_shapes(dgq, torch, shape):
+    K, N = workloads.LLAMA_SHAPES["7b"][shape]
+    for M in (1, 4, 16):
+        _forward_case(dgq, torch, M, K, N, 128, seed=1, cols=_cols(N, seed=M))
+
+
+@pytest.mark.parametrize("shape", ["qkv", "down"])
+def test_llama7b_prefill_shapes(dgq, torch, shape):
+    K, N = workloads.LLAMA_SHAPES["7b"][shape]
+    for M in (512, 2048):
+        _forward_case(dgq, torch, M, K, N, 128, seed=2, cols=_cols(N, 24, seed=M))
+
+
+def test_llama13b_shapes(dgq, torch):
+    K, N = workloads.LLAMA_SHAPES["13b"]["down"]
+    for M in (1, 16, 1024):
+        _forward_case(dgq, torch, M, K, N, 128, seed=3, cols=_cols(N, 24, seed=M))
+
+
+@pytest.mark.parametrize("g", [64, 128])
+def test_llama65b_shapes(dgq, torch, g):
+    K, N = workloads.LLAMA_SHAPES["65b"]["down"]
+    f, mlt = workloads.OUTLIERS["65b"]
+    for M in (1, 8, 64, 512):
+        _forward_case(dgq, torch, M, K, N, g, seed=4, frac=f, mult=mlt, cols=_cols(N, 16, seed=M))
