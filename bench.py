@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the DGQ A8W4 linear hot path on one MI355X.
+
+A "step" is one pass of the whole hot path (per-token activation quantization, then the
+fused expand + INT8 GEMM + scale epilogue) over one batch of synthetic input, for every
+(M, layer shape) pair of the chosen workload.  Inputs are resident in HBM before the timed
+region.  Packed weights exist in several copies that the steps rotate through, so that the
+weights of a launch are not left in the 256 MB last-level cache by the previous one.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0        # MI355X dense INT8 MFMA, published
+MALL_BYTES = 256 << 20         # last-level cache; rotate over >= 2x this much weight data
+
+# name -> (model size, list of M, group size, dominant (shape, M) for the roofline object)
+WORKLOADS = {
+    "llama7b_decode": ("7b", [1, 4, 16], 128, ("gate_up", 16)),
+    "llama7b_prefill": ("7b", [512, 1024, 2048], 128, ("gate_up", 2048)),
+    "llama13b": ("13b", [1, 16, 1024], 128, ("gate_up", 1024)),
+    "llama65b_g128": ("65b", [1, 8, 64, 512, 2048], 128, ("gate_up", 2048)),
+    "llama65b_g64": ("65b", [1, 8, 64, 512, 2048], 64, ("gate_up", 2048)),
+}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured.
+TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def act_quant_bytes(M, K):
+    """Bytes the activation quantizer must move: fp16 in, int8 + one fp32 scale per token out."""
+    return 2 * M * K + M * K + 4 * M
+
+
+def algorithmic_bytes(M, K, N, g):
+    """Bytes one linear launch must move: packed weights + group scales + channel scales,
+    quantized activations + token scales, fp16 output."""
+    return K * N // 2 + (K // g) * N + 4 * N + M * K + 4 * M + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the path is a single-GPU kernel library); "
+                 "--gpus %d is not supported, use --gpus 1" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import paper_2310_04836_amd as dgq
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    size, Ms, g, dominant = WORKLOADS[args.workload]
+    shapes = workloads.LLAMA_SHAPES[size]
+    frac, mult = workloads.OUTLIERS[size]
+    seed = {"7b": 1, "13b": 3, "65b": 4}[size]
+
+    # ---------------- inputs (untimed) ------------------------------------------------
+    t0 = time.time()
+    layer_bytes = sum(K * N // 2 + (K // g) * N for K, N in shapes.values())
+    ncopies = max(2, -(-2 * MALL_BYTES // layer_bytes))
+    ncopies = -(-ncopies // len(Ms)) * len(Ms)      # a whole number of steps per rotation
+    packed = {}
+    for name, (K, N) in shapes.items():
+        W = torch.from_numpy(workloads.weights(K, N, seed)).to(dev)
+        w4, s2, s1 = dgq.quantize_weights_rtn(W, g)
+        pw = dgq.pack_weights(w4, s2, s1, g)
+        torch.cuda.synchronize()
+        del W, w4, s2
+        copies = [pw]
+        for _ in range(ncopies - 1):
+            copies.append(dgq.PackedWeight(pw.qweight.clone(), pw.scales.clone(), pw.s1.clone(), K, N, g))
+        packed[name] = copies
+    acts, bufs = {}, {}
+    for M in Ms:
+        for name, (K, N) in shapes.items():
+            acts[(M, name)] = torch.from_numpy(workloads.activations(M, K, seed + M, frac, mult)).to(dev)
+            wsb = dgq.linear_workspace_bytes(M, N, K, g)
+            bufs[(M, name)] = (torch.empty((M, K), dtype=torch.int8, device=dev),
+                               torch.empty(M, dtype=torch.float32, device=dev),
+                               torch.empty((M, N), dtype=torch.float16, device=dev),
+                               torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None)
+    torch.cuda.synchronize()
+    log("inputs ready in %.1fs: %s, M=%s, g=%d, %d weight copies of %.1f MB" %
+        (time.time() - t0, size, Ms, g, ncopies, layer_bytes / 1e6))
+
+    def one_pair(M, name, copy):
+        xq, sx, out, ws = bufs[(M, name)]
+        dgq.quant_act(acts[(M, name)], xq, sx)
+        dgq.linear_a8w4(xq, sx, packed[name][copy % ncopies], out, ws)
+
+    def step_body(i):
+        for mi, M in enumerate(Ms):
+            for name in shapes:
+                one_pair(M, name, i * len(Ms) + mi)
+
+    # number of distinct steps before the copy rotation repeats
+    import math
+    period = ncopies // math.gcd(ncopies, len(Ms))
+
+    def make_graph(fn):
+        gr = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()                      # warm-up outside capture
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(gr):
+            fn()
+        return gr
+
+    if args.no_graph:
+        run_step = step_body
+    else:
+        graphs = [make_graph(lambda i=i: step_body(i)) for i in range(period)]
+        run_step = lambda i: graphs[i % period].replay()
+
+    # ---------------- timed region ----------------------------------------------------
+    for i in range(args.warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run_step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    step_bytes = sum(algorithmic_bytes(M, K, N, g) + act_quant_bytes(M, K) for M in Ms for K, N in shapes.values())
+    step_ops = sum(2 * M * K * N for M in Ms for K, N in shapes.values())
+    value = step_bytes / (elapsed / args.steps) / 1e9
+    log("step: %.3f ms, %.1f GB/s algorithmic, %.2f TOP/s" % (ms_per_step, value, step_ops / (elapsed / args.steps) / 1e12))
+
+    # ---------------- dominant kernel, HIP events on the launch stream -----------------
+    def time_linear(M, name, reps):
+        """Average duration of the linear kernel alone for (M, shape), weights rotating."""
+        xq, sx, out, ws = bufs[(M, name)]
+        launches = ncopies
+
+        def body():
+            for c in range(launches):
+                dgq.linear_a8w4(xq, sx, packed[name][c], out, ws)
+        if args.no_graph:
+            run = body
+        else:
+            gr = make_graph(body)
+            run = gr.replay
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return 1e-3 * e0.elapsed_time(e1) / (reps * launches)   # seconds per launch
+
+    dname, dM = dominant
+    dK, dN = shapes[dname]
+    hbm_bound = dM <= 64
+    dsec = time_linear(dM, dname, max(3, min(50, int(0.2 / max(1e-6, ms_per_step * 1e-3)))))
+    dbytes = algorithmic_bytes(dM, dK, dN, g)
+    dops = 2 * dM * dK * dN
+    kernel_name = ("linear_decode_kernel" if dM <= 16 else "linear_stream_kernel") if hbm_bound else "linear_tiled_kernel"
+    if hbm_bound:
+        roofline = {"bound": "hbm", "achieved": dbytes / dsec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roofline = {"bound": "mfma", "achieved": dops / dsec / 1e12, "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = TRAFFIC_BYTES.get((args.workload, dname, dM))
+    roofline.update({"kernel": kernel_name, "shape": "%s K=%d N=%d M=%d g=%d" % (dname, dK, dN, dM, g),
+                     "avg_us": dsec * 1e6, "algorithmic_bytes": dbytes, "ops": dops})
+    log("dominant kernel %s %s: %.2f us, %.1f %s (%.1f%% of peak)" %
+        (kernel_name, roofline["shape"], dsec * 1e6, roofline["achieved"], roofline["unit"], 100 * roofline["frac"]))
+
+    # ---------------- per (shape, M) table + fp16 GEMM (A16) baseline -------------------
+    breakdown = []
+    a16_ms = 0.0
+    if not args.no_breakdown:
+        for M in Ms:
+            for name, (K, N) in shapes.items():
+                sec = time_linear(M, name, 5 if M > 64 else 20)
+                xh = acts[(M, name)]
+                wh = torch.empty((K, N), dtype=torch.float16, device=dev).normal_(0, 0.02)
+                torch.matmul(xh, wh)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps = 5 if M > 64 else 20
+                e0.record()
+                for _ in range(reps):
+                    torch.matmul(xh, wh)
+                e1.record()
+                torch.cuda.synchronize()
+                fsec = 1e-3 * e0.elapsed_time(e1) / reps
+                del wh
+                a16_ms += fsec * 1e3
+                b = algorithmic_bytes(M, K, N, g)
+                row = {"shape": name, "M": M, "K": K, "N": N, "us": round(sec * 1e6, 2),
+                       "GBps": round(b / sec / 1e9, 1), "hbm_frac": round(b / sec / 1e9 / HBM_PEAK_GBS, 4),
+                       "TOPS": round(2 * M * K * N / sec / 1e12, 2),
+                       "mfma_frac": round(2 * M * K * N / sec / 1e12 / INT8_PEAK_TOPS, 4),
+                       "fp16_gemm_us": round(fsec * 1e6, 2), "speedup_vs_fp16_gemm": round(fsec / sec, 2)}
+                breakdown.append(row)
+                log("  %-8s M=%-5d %9.2f us  %7.1f GB/s (%5.1f%% HBM)  %8.2f TOP/s (%5.1f%% MFMA)  fp16 GEMM %9.2f us  x%.2f" %
+                    (name, M, row["us"], row["GBps"], 100 * row["hbm_frac"], row["TOPS"], 100 * row["mfma_frac"],
+                     row["fp16_gemm_us"], row["speedup_vs_fp16_gemm"]))
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("calibration copy of %d bytes done" % src.numel())
+
+    # ---------------- CPU baseline: the oracle on the same workload ---------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        qcache = {}
+        t_cpu, n_steps, done_bytes = 0.0, 0, 0
+        while t_cpu < 10.0 and n_steps < 3:
+            for M in Ms:
+                for name, (K, N) in shapes.items():
+                    # bounded sample for large layers: a contiguous slice of output channels
+                    ncol = N
+                    if 2 * M * K * N > 4e9:
+                        ncol = max(256, int(4e9 / (2 * M * K)) // 256 * 256)
+                    if (name, ncol) not in qcache:
+                        Wn = workloads.weights(K, N, seed)[:, :ncol]
+                        qcache[(name, ncol)] = oracle.quantize_weights_rtn(Wn, g)
+                    w4, s2, s1 = qcache[(name, ncol)]
+                    x = acts[(M, name)].cpu().numpy()
+                    t1 = time.perf_counter()
+                    oracle.forward(x, w4, s2, s1, g)
+                    t_cpu += time.perf_counter() - t1
+                    done_bytes += algorithmic_bytes(M, K, ncol, g) + act_quant_bytes(M, K)
+            n_steps += 1
+        cpu = {"value": done_bytes / t_cpu / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": "%d whole step(s) of the same workload%s, %.1f s of CPU time" %
+                         (n_steps, "" if max(Ms) <= 64 else " (output channels of large layers cut to a contiguous slice)", t_cpu)}
+        log("cpu oracle: %.3f GB/s on %d threads" % (cpu["value"], cpu["cores"]))
+
+    result = {
+        "metric": "A8W4 linear TOPS and weight GB/s (% of roofline) at M=1..2048, LLaMA shapes",
+        "value": value, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
+                   "layers_per_step": list(shapes), "weight_copies": ncopies,
+                   "launch": "eager" if args.no_graph else "hip_graph"},
+        "tops": step_ops / (elapsed / args.steps) / 1e12,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "a16_fp16_gemm_ms_per_step": a16_ms if breakdown else None,
+        "breakdown": breakdown,
+        "paper_context": "paper reports 3.24x vs A16W4 and 1.12x memory, end to end on one A100-80G (abstract, Section 4.3)",
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

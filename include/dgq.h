@@ -72,7 +72,8 @@ DGQ_API dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_byt
 
 /*
  * Scratch needed by dgq_linear_a8w4 / dgq_linear_a8w4_acc for this problem (host
- * function).  May be 0, in which case `workspace` may be NULL.
+ * function).  May be 0, in which case `workspace` may be NULL.  Non-zero only for small M
+ * with very long K, where several workgroups split K and exchange INT32 partial sums.
  */
 DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
 
@@ -154,11 +155,13 @@ DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, co
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Selects the GEMM path for later dgq_linear_a8w4* calls of this process (host, for
- * tests and measurements): 0 = choose by M (default), 1 = weight-streaming path,
- * 2 = tiled path.  Returns the previous value; an unknown value changes nothing and
- * returns -1.  The weight-streaming path accepts M <= 64 only; forcing it for a larger
- * M makes the linear calls return DGQ_ERR_SHAPE.
+ * Selects the GEMM path for later dgq_linear_a8w4* and dgq_linear_workspace_bytes calls of
+ * this process (host, for tests and measurements): 0 = choose by M (default), 1 = the
+ * weight-streaming kernels, 2 = the tiled kernel, 3 = the weight-streaming kernel that
+ * re-reads activations every step (by default used for 16 < M <= 64 only).  Returns the
+ * previous value; an unknown value changes nothing and returns -1.  The weight-streaming
+ * kernels accept M <= 64 only; forcing them for a larger M makes the linear calls return
+ * DGQ_ERR_SHAPE.
  */
 DGQ_API int dgq_force_path(int path);
 

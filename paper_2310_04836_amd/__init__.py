@@ -85,7 +85,8 @@ def layout_version() -> int:
 
 
 def force_path(path: int) -> int:
-    """0 = choose by M, 1 = weight-streaming kernel, 2 = tiled kernel.  Returns the old value."""
+    """0 = choose by M, 1 = weight-streaming kernels, 2 = tiled kernel, 3 = streaming kernel that
+    re-reads activations every step.  Returns the old value."""
     return lib.dgq_force_path(path)
 
 
@@ -164,6 +165,12 @@ def quant_act(x: torch.Tensor, xq: torch.Tensor = None, sx: torch.Tensor = None)
     return xq, sx
 
 
+def _workspace(M, N, K, group, device):
+    """Scratch of the size the library asks for (None when it needs none)."""
+    nbytes = linear_workspace_bytes(M, N, K, group)
+    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
 def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch.Tensor = None,
                 workspace: torch.Tensor = None) -> torch.Tensor:
     """dgq_linear_a8w4: fp16 [M,N] = (sx x s1) * (xq @ expand(qweight))."""
@@ -173,6 +180,8 @@ def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch
         raise ValueError("xq has K=%d but the packed weight has K=%d" % (K, pw.K))
     if out is None:
         out = torch.empty((M, pw.N), dtype=torch.float16, device=xq.device)
+    if workspace is None:
+        workspace = _workspace(M, pw.N, K, pw.group, xq.device)
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.dgq_linear_a8w4(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
                                M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
@@ -186,6 +195,8 @@ def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor 
     if K != pw.K:
         raise ValueError("xq has K=%d but the packed weight has K=%d" % (K, pw.K))
     acc = torch.empty((M, pw.N), dtype=torch.int32, device=xq.device)
+    if workspace is None:
+        workspace = _workspace(M, pw.N, K, pw.group, xq.device)
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.dgq_linear_a8w4_acc(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group,
                                    _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4_acc")

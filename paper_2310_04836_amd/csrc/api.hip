@@ -28,20 +28,39 @@ dgq_status hip_result(hipError_t e)
     return DGQ_ERR_HIP;
 }
 
+// 0 = by M, 1 = weight-streaming kernels, 2 = tiled kernel, 3 = the streaming kernel that
+// re-reads activations every step (normally only used for 16 < M <= 64).
+enum { kPathAuto = 0, kPathStream = 1, kPathTiled = 2, kPathStreamGeneric = 3 };
+
+int pick_path(int M, int forced)
+{
+    if (forced == kPathTiled) return kPathTiled;
+    if (forced == kPathStreamGeneric) return kPathStreamGeneric;
+    if (forced == kPathStream || M <= dgq::kStreamMaxM) return M <= dgq::kDecodeMaxM ? kPathStream : kPathStreamGeneric;
+    return kPathTiled;
+}
+
+size_t workspace_needed(int path, int M, int N, int K)
+{
+    return path == kPathStream ? dgq::decode_workspace_bytes(M, N, K) : 0;
+}
+
 dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_bytes, void *stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     const int forced = g_force_path.load(std::memory_order_relaxed);
-    bool stream_path = a.M <= dgq::kStreamMaxM;
-    if (forced == 1) {
-        if (a.M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
-        stream_path = true;
-    } else if (forced == 2) {
-        stream_path = false;
+    if ((forced == kPathStream || forced == kPathStreamGeneric) && a.M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
+    const int path = pick_path(a.M, forced);
+    const size_t need = workspace_needed(path, a.M, a.N, a.K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return DGQ_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return DGQ_ERR_ALIGN;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    return hip_result(stream_path ? dgq::launch_linear_stream(a, st) : dgq::launch_linear_tiled(a, st));
+    switch (path) {
+    case kPathStream: return hip_result(dgq::launch_linear_decode(a, workspace, st));
+    case kPathStreamGeneric: return hip_result(dgq::launch_linear_stream(a, st));
+    default: return hip_result(dgq::launch_linear_tiled(a, st));
+    }
 }
 
 }  // namespace
@@ -68,7 +87,7 @@ int dgq_layout_version(void) { return DGQ_LAYOUT_VERSION; }
 
 int dgq_force_path(int path)
 {
-    if (path < 0 || path > 2) return -1;
+    if (path < 0 || path > 3) return -1;
     return g_force_path.exchange(path);
 }
 
@@ -87,7 +106,9 @@ dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *by
     if (!bytes) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
-    *bytes = 0;  // split-K partial sums are combined in LDS; no global scratch is used
+    // Only the decode kernel with a K too long for one workgroup keeps partial sums in
+    // global memory; every other split of K is combined in LDS.
+    *bytes = workspace_needed(pick_path(M, g_force_path.load(std::memory_order_relaxed)), M, N, K);
     return DGQ_OK;
 }
 

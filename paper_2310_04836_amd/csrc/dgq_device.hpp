@@ -79,8 +79,14 @@ struct LinearArgs {
     int32_t *acc_out;      // null in fp16 mode
     int M, N, K, group;
 };
-// Largest M the weight-streaming kernel takes.
+// Largest M the weight-streaming kernels take.
 constexpr int kStreamMaxM = 64;
+// Decode kernel (one 16-token tile, activations resident in registers).
+constexpr int kDecodeMaxM = 16;
+constexpr int kDecodeMaxStepsPerWave = 6;  // 8 would spill at 128 VGPRs
+int decode_ksplit(int K);
+size_t decode_workspace_bytes(int M, int N, int K);
+hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st);
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
 hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);
 

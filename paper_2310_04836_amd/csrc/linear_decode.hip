@@ -1,0 +1,276 @@
+// Decode A8W4 linear for M <= 16 tokens: one 16-token MFMA tile, weights streamed once.
+//
+// The layer reads K*N/2 bytes of packed weights and almost nothing else, so everything is
+// arranged to keep that stream dense and to take the activations off it:
+//
+//   - One workgroup of 16 wavefronts per CU (a persistent grid).  Wavefront w owns a fixed
+//     slice of K (at most SPW steps of 128 k) for the whole kernel and loads its slice of
+//     the INT8 activations into registers ONCE; after that the only global loads in the
+//     loop are 1 KiB weight chunks (one 128-bit load per lane) and their group scales.
+//   - The workgroup walks over 16-column tiles.  For each tile every wavefront expands its
+//     chunks in registers (second line of Eq. 2), issues two v_mfma_i32_16x16x64_i8 per
+//     chunk (third line of Eq. 2; tokens beyond M repeat the last row and are never stored)
+//     and refills each register slot with the same step of the next tile right away, so a
+//     wavefront always has SPW KiB of loads in flight.
+//   - The 16 partial INT32 tiles are added through LDS (double buffered, one barrier per
+//     tile; integer addition is associative, so the split changes no bit).  The first four
+//     wavefronts apply sx[m]*s1[n] (first line of Eq. 2) and store fp16.
+//   - If K is too long for 16 wavefronts x SPW steps, several workgroups split K and write
+//     raw INT32 partial tiles to the workspace; a small second kernel adds them and runs
+//     the epilogue.
+#include "dgq_device.hpp"
+
+namespace dgq {
+namespace {
+
+constexpr int kWaves = 16;
+// A workgroup keeps the finished INT32 tiles of all its column tiles in LDS and stores
+// them after the weight loop, so that the loop itself contains no global stores.
+constexpr int kMaxTilesPerWg = 32;
+
+template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, int ksplit, int32_t *partial)
+{
+    __shared__ int red[2][kWaves][256];
+    __shared__ int sums[kMaxTilesPerWg][256];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = lane & 15;
+    const int kb = lane >> 4;
+    const int steps = a.K >> 7;
+    const int tiles = a.N >> 4;
+    const int gqn = ((a.K / G) + 3) >> 2;
+
+    // This workgroup's part of K; wavefront w takes steps [p0 + w*SPW, p0 + (w+1)*SPW) of it.
+    // Only the last active wavefront can be short; wavefronts past the end only help reduce.
+    const int kpart = blockIdx.x % ksplit;
+    const int wg = blockIdx.x / ksplit;
+    const int wg_stride = gridDim.x / ksplit;
+    const int p0 = (steps * kpart) / ksplit;
+    const int p1 = (steps * (kpart + 1)) / ksplit;
+    const int active_waves = (p1 - p0 + SPW - 1) / SPW;  // <= kWaves, checked on the host
+    const int sb = p0 + wave * SPW;
+    const int nst = sb < p1 ? (p1 - sb < SPW ? p1 - sb : SPW) : 0;
+    const int my_tiles = wg < tiles ? (tiles - wg + wg_stride - 1) / wg_stride : 0;
+
+    if (nst > 0) {
+        // activations of this slice: loaded once, kept in registers; slots past the end of
+        // a short slice hold zeros, so whatever weights they are multiplied with add nothing
+        uint4 xa[SPW][2];
+        const int m = j < a.M ? j : a.M - 1;
+        const uint4 *ap = reinterpret_cast<const uint4 *>(a.xq + (size_t)m * a.K + kb * 32);
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+            const int s = i < nst ? sb + i : sb;
+            xa[i][0] = ap[(size_t)s * 8];
+            xa[i][1] = ap[(size_t)s * 8 + 1];
+            if (i >= nst) xa[i][0] = xa[i][1] = make_uint4(0, 0, 0, 0);
+        }
+
+        // per-slot element offsets inside one column tile (a short slice re-reads step sb)
+        int qoff[SPW], soff[SPW], ssh[SPW];
+#pragma unroll
+        for (int i = 0; i < SPW; ++i) {
+            const int s = i < nst ? sb + i : sb;
+            const int gi = (G == 128) ? s : 2 * s + (kb >> 1);
+            qoff[i] = s * 64 + lane;
+            soff[i] = (gi >> 2) * 16 + j;
+            ssh[i] = 8 * (gi & 3);
+        }
+
+        uint4 q[PF][SPW];
+        uint32_t sw[PF][SPW];
+#define DGQ_LOAD_SLOT(P, I, TILE)                                              \
+    do {                                                                       \
+        q[P][I] = a.qweight[(size_t)(TILE) * steps * 64 + qoff[I]];            \
+        sw[P][I] = a.scales[(size_t)(TILE) * gqn * 16 + soff[I]];              \
+    } while (0)
+
+        // prologue: PF tiles in flight (tiles past the end re-read the first tile, unused)
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int t = p < my_tiles ? wg + p * wg_stride : wg;
+#pragma unroll
+            for (int i = 0; i < SPW; ++i) {
+                DGQ_LOAD_SLOT(p, i, t);
+                // issue order = consumption order, so that waiting for the oldest slot
+                // leaves all younger loads in flight
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+#define DGQ_TILE(P, IT)                                                                              \
+    do {                                                                                             \
+        const int it_ = (IT);                                                                        \
+        const int tn_ = it_ + PF < my_tiles ? wg + (it_ + PF) * wg_stride : wg;                      \
+        v4i acc = v4i{0, 0, 0, 0};                                                                   \
+        _Pragma("unroll") for (int i = 0; i < SPW; ++i)                                              \
+        {                                                                                            \
+            const GroupScale gs = make_group_scale((sw[P][i] >> ssh[i]) & 0xFFu);                    \
+            v4i b0, b1;                                                                              \
+            expand_cell(q[P][i], gs, b0, b1);                                                        \
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, xa[i][0]), b0, acc, 0, 0, 0); \
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, xa[i][1]), b1, acc, 0, 0, 0); \
+            DGQ_LOAD_SLOT(P, i, tn_);                                                                \
+            __builtin_amdgcn_sched_barrier(0); /* keep each refill right behind its use */           \
+        }                                                                                            \
+        /* acc[r] of lane l: token 4*(l/16) + r, column tile*16 + l%16 */                            \
+        int *mine = &red[it_ & 1][wave][0];                                                          \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) mine[r * 64 + lane] = acc[r];                  \
+        __syncthreads();                                                                             \
+        if (threadIdx.x < 256) {                                                                     \
+            int sum = 0;                                                                             \
+            for (int w = 0; w < active_waves; ++w) sum += red[it_ & 1][w][threadIdx.x];              \
+            sums[it_][threadIdx.x] = sum;                                                            \
+        }                                                                                            \
+        /* No second barrier: the next tile writes the other buffer, and that buffer's readers */    \
+        /* passed the barrier above only after their reads. */                                       \
+    } while (0)
+
+        // Main loop: whole rounds of PF tiles, straight-line, so every wait for a slot leaves
+        // the younger PF*SPW - 1 slots in flight.  Then the last my_tiles % PF tiles.
+        int it0 = 0;
+        for (; it0 + PF <= my_tiles; it0 += PF) {
+#pragma unroll
+            for (int p = 0; p < PF; ++p) DGQ_TILE(p, it0 + p);
+        }
+#pragma unroll
+        for (int p = 0; p < PF - 1; ++p)
+            if (it0 + p < my_tiles) DGQ_TILE(p, it0 + p);
+#undef DGQ_TILE
+#undef DGQ_LOAD_SLOT
+    } else {
+        // wavefronts without a slice of K: keep the barrier count and help with the reduction
+        for (int it = 0; it < my_tiles; ++it) {
+            __syncthreads();
+            if (threadIdx.x < 256) {
+                int sum = 0;
+                for (int w = 0; w < active_waves; ++w) sum += red[it & 1][w][threadIdx.x];
+                sums[it][threadIdx.x] = sum;
+            }
+        }
+    }
+    __syncthreads();
+
+    // Epilogue for all tiles of this workgroup.  Element x of a tile: token 4*((x%64)/16) + x/64,
+    // column tile*16 + x%16.
+    for (int idx = threadIdx.x; idx < my_tiles * 256; idx += kWaves * 64) {
+        const int ti = idx >> 8;
+        const int x = idx & 255;
+        const int sum = sums[ti][x];
+        const int m = 4 * ((x & 63) >> 4) + (x >> 6);
+        const int n = (wg + ti * wg_stride) * 16 + (x & 15);
+        if (m < a.M) {
+            if (PARTIAL) {
+                partial[((size_t)kpart * a.M + m) * a.N + n] = sum;
+            } else if (ACC) {
+                a.acc_out[(size_t)m * a.N + n] = sum;
+            } else {
+                const float sc = a.sx[m] * a.s1[n];
+                const _Float16 h = (_Float16)(sc * (float)sum);
+                a.out[(size_t)m * a.N + n] = __builtin_bit_cast(unsigned short, h);
+            }
+        }
+    }
+}
+
+// Adds the K-split partial tiles and runs the epilogue.
+template <bool ACC>
+__global__ __launch_bounds__(256) void splitk_finalize_kernel(LinearArgs a, int ksplit, const int32_t *partial)
+{
+    const size_t total = (size_t)a.M * a.N;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    int sum = 0;
+    for (int p = 0; p < ksplit; ++p) sum += partial[(size_t)p * total + idx];
+    if (ACC) {
+        a.acc_out[idx] = sum;
+    } else {
+        const int m = (int)(idx / a.N);
+        const int n = (int)(idx % a.N);
+        const float sc = a.sx[m] * a.s1[n];
+        const _Float16 h = (_Float16)(sc * (float)sum);
+        a.out[idx] = __builtin_bit_cast(unsigned short, h);
+    }
+}
+
+int cu_count()
+{
+    static int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
+template <int SPW, int PF, int G>
+hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
+{
+    const int tiles = a.N / 16;
+    int cols = cu_count() / ksplit;
+    if (cols < 1) cols = 1;
+    if (cols * kMaxTilesPerWg < tiles) cols = (tiles + kMaxTilesPerWg - 1) / kMaxTilesPerWg;
+    if (cols > tiles) cols = tiles;
+    dim3 grid(cols * ksplit), block(kWaves * 64);
+    int32_t *partial = static_cast<int32_t *>(workspace);
+    const bool acc = a.acc_out != nullptr;
+    if (ksplit > 1) {
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
+        const size_t total = (size_t)a.M * a.N;
+        dim3 fgrid((unsigned)((total + 255) / 256));
+        if (acc)
+            hipLaunchKernelGGL(splitk_finalize_kernel<true>, fgrid, dim3(256), 0, st, a, ksplit, partial);
+        else
+            hipLaunchKernelGGL(splitk_finalize_kernel<false>, fgrid, dim3(256), 0, st, a, ksplit, partial);
+    } else if (acc) {
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, 1, partial);
+    } else {
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, 1, partial);
+    }
+    return hipGetLastError();
+}
+
+template <int G>
+hipError_t launch_g(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
+{
+    const int steps = a.K / 128;
+    const int per_part = (steps + ksplit - 1) / ksplit;
+    const int spw = (per_part + kWaves - 1) / kWaves;
+    // SPW steps per wavefront x PF tiles ahead = KiB of weight loads in flight per wavefront
+    if (spw <= 1) return launch_spw<1, 4, G>(a, ksplit, workspace, st);
+    if (spw <= 2) return launch_spw<2, 2, G>(a, ksplit, workspace, st);
+    if (spw <= 3) return launch_spw<3, 2, G>(a, ksplit, workspace, st);
+    if (spw <= 4) return launch_spw<4, 1, G>(a, ksplit, workspace, st);
+    if (spw <= 5) return launch_spw<5, 1, G>(a, ksplit, workspace, st);
+    if (spw <= 6) return launch_spw<6, 1, G>(a, ksplit, workspace, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int decode_ksplit(int K)
+{
+    const int steps = K / 128;
+    int s = 1;
+    while (((steps + s - 1) / s + kWaves - 1) / kWaves > kDecodeMaxStepsPerWave) s *= 2;
+    return s;
+}
+
+size_t decode_workspace_bytes(int M, int N, int K)
+{
+    const int s = decode_ksplit(K);
+    return s > 1 ? (size_t)s * M * N * sizeof(int32_t) : 0;
+}
+
+hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st)
+{
+    if (a.M > kDecodeMaxM) return hipErrorInvalidValue;
+    const int ksplit = decode_ksplit(a.K);
+    return a.group == 128 ? launch_g<128>(a, ksplit, workspace, st) : launch_g<64>(a, ksplit, workspace, st);
+}
+
+}  // namespace dgq

@@ -156,6 +156,42 @@ def test_onehot_probe_tiled_path(dgq, torch, M, g):
 ])
 def test_acc_bit_exact_stream_path(dgq, torch, M, K, N, g):
     _acc_case(dgq, torch, M, K, N, g, seed=M * 7 + N, path=1)
+    _acc_case(dgq, torch, M, K, N, g, seed=M * 7 + N, path=3)
+
+
+# Decode kernel (M <= 16): every steps-per-wavefront variant, short last slices, idle
+# wavefronts, several column tiles per workgroup with a ragged count, K split over
+# workgroups through the workspace (K/128 > 96), and more tiles than one workgroup buffers.
+@pytest.mark.parametrize("M,K,N,g", [
+    (1, 1024, 48, 128),        # 8 steps: 8 active wavefronts of 1 step
+    (16, 2176, 8240, 64),      # 17 steps: 2 per wavefront, last one short; 515 tiles on 256 workgroups
+    (5, 5120, 4112, 128),      # 40 steps: 3 per wavefront, 14 active
+    (16, 8192, 272, 64),       # 64 steps: 4 per wavefront
+    (7, 10240, 64, 128),       # 80 steps: 5 per wavefront
+    (16, 11008, 4096, 128),    # 86 steps: 6 per wavefront, 15 active, last one short
+    (9, 13824, 528, 128),      # 108 steps: split in 2 parts of 54 -> 4 per wavefront
+    (16, 22016, 1040, 64),     # 172 steps: split in 2 parts of 86
+    (2, 128, 131200, 128),     # 8200 tiles: more than 32 per workgroup on 256 CUs
+])
+def test_acc_bit_exact_decode_kernel(dgq, torch, M, K, N, g):
+    _acc_case(dgq, torch, M, K, N, g, seed=M + K, path=1)
+
+
+def test_decode_workspace_contract(dgq, torch):
+    M, K, N, g = 4, 22016, 64, 128
+    need = dgq.linear_workspace_bytes(M, N, K, g)
+    assert need == 2 * M * N * 4
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 1)
+    xq, sx = workloads.integer_activations(M, K, 1)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dgq.DGQError) as e:
+        dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=small)
+    assert e.value.status == -5
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")   # contents undefined on entry
+    out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=ws))
+    oout, _ = oracle.linear_a8w4(xq, sx, w4, s2, s1, g)
+    assert_fp16_close(out, oout)
 
 
 @pytest.mark.parametrize("M,K,N,g", [
@@ -168,19 +204,19 @@ def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
 
 def test_both_paths_and_split_factors_agree(dgq, torch):
     """Integer sums do not depend on how K is split between wavefronts or on the path."""
-    M, N, g = 48, 128, 128
-    for K in (256, 1152, 4096):       # 2, 9 and 32 steps -> different per-wave split patterns
+    N, g = 128, 128
+    for M, K in ((48, 256), (48, 1152), (48, 4096), (12, 1152), (16, 4096)):   # 2, 9, 32 steps
         w4, s2, s1 = workloads.integer_weights(K, N, g, K)
         xq, _ = workloads.integer_activations(M, K, K)
         pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
         res = []
-        for path in (1, 2):
+        for path in (1, 2, 3):
             old = dgq.force_path(path)
             try:
                 res.append(host(dgq.linear_a8w4_acc(dev(torch, xq), pw)))
             finally:
                 dgq.force_path(old)
-        assert np.array_equal(res[0], res[1])
+        assert np.array_equal(res[0], res[1]) and np.array_equal(res[0], res[2])
         assert np.array_equal(res[0].astype(np.int64), xq.astype(np.int64) @ (
             np.repeat(s2.astype(np.int64), g, axis=0) * w4))
 
