@@ -234,6 +234,37 @@ def main():
                     (name, M, row["us"], row["GBps"], 100 * row["hbm_frac"], row["TOPS"], 100 * row["mfma_frac"],
                      row["fp16_gemm_us"], row["speedup_vs_fp16_gemm"]))
 
+    # ---------------- measured achievable read bandwidth (plain streaming read) -----------
+    probe = None
+    try:
+        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+        big.zero_()
+        probe = {}
+        for label, nbytes in (("1GiB", 1 << 30), ("dominant_launch", (dbytes // 16) * 16)):
+            ncp = max(1, (1 << 30) // nbytes)
+            reps = 3 if nbytes > (256 << 20) else 10
+
+            def body(nbytes=nbytes, ncp=ncp):
+                for c in range(ncp):
+                    dgq.lib.dgq_probe_read(big.data_ptr() + c * ((nbytes + 255) // 256 * 256) % ((1 << 30) - nbytes + 1) // 256 * 256,
+                                           nbytes, sink.data_ptr(), 256, torch.cuda.current_stream().cuda_stream)
+            gr = make_graph(body)
+            gr.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                gr.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            sec = 1e-3 * e0.elapsed_time(e1) / (reps * ncp)
+            probe[label] = {"bytes": nbytes, "us": sec * 1e6, "GBps": nbytes / sec / 1e9}
+            log("plain streaming read of %s (%d bytes): %.2f us, %.1f GB/s" % (label, nbytes, sec * 1e6, nbytes / sec / 1e9))
+        del big
+    except Exception as e:  # measurement aid only
+        log("probe_read failed: %r" % (e,))
+
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -282,6 +313,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "a16_fp16_gemm_ms_per_step": a16_ms if breakdown else None,
+        "measured_read_bandwidth": probe,
         "breakdown": breakdown,
         "paper_context": "paper reports 3.24x vs A16W4 and 1.12x memory, end to end on one A100-80G (abstract, Section 4.3)",
     }

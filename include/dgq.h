@@ -165,6 +165,16 @@ DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, co
  */
 DGQ_API int dgq_force_path(int path);
 
+/*
+ * Measurement aid (not part of Eq. 2): reads `bytes` (a multiple of 16 is read, the rest is
+ * ignored) of a device buffer once with `workgroups` 1024-thread workgroups and 128-bit
+ * loads, the access pattern of the weight stream.  `sink` is a device array of `workgroups`
+ * uint32 that is written only in the unlikely case a checksum matches; it exists so that the
+ * loads cannot be optimised away.  Timing this call gives the read bandwidth a
+ * weight-streaming kernel could at best reach for a buffer of that size.
+ */
+DGQ_API dgq_status dgq_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -177,4 +177,12 @@ dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void
     return run_linear(a, workspace, workspace_bytes, stream);
 }
 
+dgq_status dgq_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, void *stream)
+{
+    if (!src || !sink) return DGQ_ERR_NULL;
+    if (bytes < 16 || workgroups < 1 || workgroups > 65536) return DGQ_ERR_SHAPE;
+    if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_probe_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -90,4 +90,6 @@ hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
 hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);
 
+hipError_t launch_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t st);
+
 }  // namespace dgq

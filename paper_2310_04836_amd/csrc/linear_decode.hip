@@ -54,6 +54,22 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
     const int nst = sb < p1 ? (p1 - sb < SPW ? p1 - sb : SPW) : 0;
     const int my_tiles = wg < tiles ? (tiles - wg + wg_stride - 1) / wg_stride : 0;
 
+    // Epilogue operands, fetched now so that the end of the kernel does not wait on memory.
+    // In the epilogue thread x handles element x%256 of tiles x/256, x/256 + 4, ...: a fixed
+    // token, and one output channel per tile.
+    constexpr int kEarly = 3;
+    const int ep_x = threadIdx.x & 255;
+    const int ep_m = 4 * ((ep_x & 63) >> 4) + (ep_x >> 6);
+    float ep_sx = 0.0f, ep_s1[kEarly] = {0.0f, 0.0f, 0.0f};
+    if (!ACC && !PARTIAL && ep_m < a.M) {
+        ep_sx = a.sx[ep_m];
+#pragma unroll
+        for (int k = 0; k < kEarly; ++k) {
+            const int ti = (threadIdx.x >> 8) + 4 * k;
+            if (ti < my_tiles) ep_s1[k] = a.s1[(wg + ti * wg_stride) * 16 + (ep_x & 15)];
+        }
+    }
+
     if (nst > 0) {
         // activations of this slice: loaded once, kept in registers; slots past the end of
         // a short slice hold zeros, so whatever weights they are multiplied with add nothing
@@ -155,21 +171,24 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
 
     // Epilogue for all tiles of this workgroup.  Element x of a tile: token 4*((x%64)/16) + x/64,
     // column tile*16 + x%16.
-    for (int idx = threadIdx.x; idx < my_tiles * 256; idx += kWaves * 64) {
-        const int ti = idx >> 8;
-        const int x = idx & 255;
-        const int sum = sums[ti][x];
-        const int m = 4 * ((x & 63) >> 4) + (x >> 6);
-        const int n = (wg + ti * wg_stride) * 16 + (x & 15);
-        if (m < a.M) {
+    if (ep_m < a.M) {
+        int k = 0;
+        for (int ti = threadIdx.x >> 8; ti < my_tiles; ti += 4, ++k) {
+            const int sum = sums[ti][ep_x];
+            const int n = (wg + ti * wg_stride) * 16 + (ep_x & 15);
             if (PARTIAL) {
-                partial[((size_t)kpart * a.M + m) * a.N + n] = sum;
+                partial[((size_t)kpart * a.M + ep_m) * a.N + n] = sum;
             } else if (ACC) {
-                a.acc_out[(size_t)m * a.N + n] = sum;
+                a.acc_out[(size_t)ep_m * a.N + n] = sum;
             } else {
-                const float sc = a.sx[m] * a.s1[n];
+                float s1n;
+                if (k == 0) s1n = ep_s1[0];
+                else if (k == 1) s1n = ep_s1[1];
+                else if (k == 2) s1n = ep_s1[2];
+                else s1n = a.s1[n];
+                const float sc = ep_sx * s1n;
                 const _Float16 h = (_Float16)(sc * (float)sum);
-                a.out[(size_t)m * a.N + n] = __builtin_bit_cast(unsigned short, h);
+                a.out[(size_t)ep_m * a.N + n] = __builtin_bit_cast(unsigned short, h);
             }
         }
     }

@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 12 and len(set(names)) == 12
+    assert len(names) == 13 and len(set(names)) == 13
     for n in names:
         assert hasattr(dgq.lib, n), n
 
