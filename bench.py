@@ -25,13 +25,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0        # MI355X dense INT8 MFMA, published
 MALL_BYTES = 256 << 20         # last-level cache; rotate over >= 2x this much weight data
 
-# name -> (model size, list of M, group size, dominant (shape, M) for the roofline object)
+# name -> (model size, list of M, group size)
 WORKLOADS = {
-    "llama7b_decode": ("7b", [1, 4, 16], 128, ("gate_up", 16)),
-    "llama7b_prefill": ("7b", [512, 1024, 2048], 128, ("gate_up", 2048)),
-    "llama13b": ("13b", [1, 16, 1024], 128, ("gate_up", 1024)),
-    "llama65b_g128": ("65b", [1, 8, 64, 512, 2048], 128, ("gate_up", 2048)),
-    "llama65b_g64": ("65b", [1, 8, 64, 512, 2048], 64, ("gate_up", 2048)),
+    "llama7b_decode": ("7b", [1, 4, 16], 128),
+    "llama7b_prefill": ("7b", [512, 1024, 2048], 128),
+    "llama13b": ("13b", [1, 16, 1024], 128),
+    "llama65b_g128": ("65b", [1, 8, 64, 512, 2048], 128),
+    "llama65b_g64": ("65b", [1, 8, 64, 512, 2048], 64),
 }
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
@@ -78,7 +78,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    size, Ms, g, dominant = WORKLOADS[args.workload]
+    size, Ms, g = WORKLOADS[args.workload]
     shapes = workloads.LLAMA_SHAPES[size]
     frac, mult = workloads.OUTLIERS[size]
     seed = {"7b": 1, "13b": 3, "65b": 4}[size]
@@ -184,23 +184,34 @@ def main():
         torch.cuda.synchronize()
         return 1e-3 * e0.elapsed_time(e1) / (reps * launches)   # seconds per launch
 
-    dname, dM = dominant
-    dK, dN = shapes[dname]
-    hbm_bound = dM <= 64
-    dsec = time_linear(dM, dname, max(3, min(50, int(0.2 / max(1e-6, ms_per_step * 1e-3)))))
-    dbytes = algorithmic_bytes(dM, dK, dN, g)
-    dops = 2 * dM * dK * dN
-    kernel_name = ("linear_decode_kernel" if dM <= 16 else "linear_stream_kernel") if hbm_bound else "linear_tiled_kernel"
+    # Every (M, shape) pair alone, same number of launches each, then grouped by the kernel
+    # symbol the library picks: the dominant kernel is the symbol with the largest share of
+    # the step.  Its figures are means over its launches, which is also what a profiler's
+    # per-kernel average over this run shows.
+    reps_pair = 20 if max(Ms) <= 64 else 5
+    pair_sec, groups = {}, {}
+    for M in Ms:
+        for name, (K, N) in shapes.items():
+            pair_sec[(M, name)] = time_linear(M, name, reps_pair)
+            groups.setdefault(dgq.linear_plan(M, N, K, g), []).append((M, name))
+    kernel_name = max(groups, key=lambda k: sum(pair_sec[p] for p in groups[k]))
+    dpairs = groups[kernel_name]
+    dsec = sum(pair_sec[p] for p in dpairs) / len(dpairs)
+    dbytes = sum(algorithmic_bytes(M, *shapes[name], g) for M, name in dpairs) / len(dpairs)
+    dops = sum(2 * M * shapes[name][0] * shapes[name][1] for M, name in dpairs) / len(dpairs)
+    hbm_bound = not kernel_name.startswith("linear_tiled")
     if hbm_bound:
         roofline = {"bound": "hbm", "achieved": dbytes / dsec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
         roofline = {"bound": "mfma", "achieved": dops / dsec / 1e12, "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = TRAFFIC_BYTES.get((args.workload, dname, dM))
-    roofline.update({"kernel": kernel_name, "shape": "%s K=%d N=%d M=%d g=%d" % (dname, dK, dN, dM, g),
-                     "avg_us": dsec * 1e6, "algorithmic_bytes": dbytes, "ops": dops})
-    log("dominant kernel %s %s: %.2f us, %.1f %s (%.1f%% of peak)" %
-        (kernel_name, roofline["shape"], dsec * 1e6, roofline["achieved"], roofline["unit"], 100 * roofline["frac"]))
+    roofline["traffic"] = TRAFFIC_BYTES.get((args.workload, kernel_name))
+    roofline.update({"kernel": kernel_name,
+                     "launches": ["%s M=%d" % (name, M) for M, name in dpairs],
+                     "avg_us": dsec * 1e6, "algorithmic_bytes_per_launch": dbytes, "ops_per_launch": dops,
+                     "share_of_linear_time": sum(pair_sec[p] for p in dpairs) / sum(pair_sec.values())})
+    log("dominant kernel %s over %d (M, shape) pairs: avg %.2f us, %.1f %s (%.1f%% of peak)" %
+        (kernel_name, len(dpairs), dsec * 1e6, roofline["achieved"], roofline["unit"], 100 * roofline["frac"]))
 
     # ---------------- per (shape, M) table + fp16 GEMM (A16) baseline -------------------
     breakdown = []
@@ -208,7 +219,7 @@ def main():
     if not args.no_breakdown:
         for M in Ms:
             for name, (K, N) in shapes.items():
-                sec = time_linear(M, name, 5 if M > 64 else 20)
+                sec = pair_sec[(M, name)]
                 xh = acts[(M, name)]
                 wh = torch.empty((K, N), dtype=torch.float16, device=dev).normal_(0, 0.02)
                 torch.matmul(xh, wh)
@@ -241,7 +252,7 @@ def main():
         sink = torch.zeros(4096, dtype=torch.int32, device=dev)
         big.zero_()
         probe = {}
-        for label, nbytes in (("1GiB", 1 << 30), ("dominant_launch", (dbytes // 16) * 16)):
+        for label, nbytes in (("1GiB", 1 << 30), ("dominant_launch", (int(dbytes) // 16) * 16)):
             ncp = max(1, (1 << 30) // nbytes)
             reps = 3 if nbytes > (256 << 20) else 10
 

@@ -166,6 +166,14 @@ DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, co
 DGQ_API int dgq_force_path(int path);
 
 /*
+ * Measurement aid (host function, nothing launched): writes into buf (at least 96 bytes)
+ * the name, with template arguments, of the GEMM kernel that dgq_linear_a8w4 would launch
+ * for this problem under the current dgq_force_path() setting, e.g.
+ * "linear_decode_kernel<2, 2, 128, false, false>".  Profiler output can be matched to it.
+ */
+DGQ_API dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes);
+
+/*
  * Measurement aid (not part of Eq. 2): reads `bytes` (a multiple of 16 is read, the rest is
  * ignored) of a device buffer once with `workgroups` 1024-thread workgroups and 128-bit
  * loads, the access pattern of the weight stream.  `sink` is a device array of `workgroups`

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "probe_read", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -53,9 +53,10 @@ def _load() -> ctypes.CDLL:
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_probe_read.argtypes = [vp, sz, vp, i, vp]
+    L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
-                 "dgq_probe_read"):
+                 "dgq_probe_read", "dgq_linear_plan"):
         getattr(L, name).restype = i
     return L
 
@@ -188,6 +189,13 @@ def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch
     _check(lib.dgq_linear_a8w4(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
                                M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
     return out
+
+
+def linear_plan(M: int, N: int, K: int, group: int) -> str:
+    """dgq_linear_plan: name of the GEMM kernel dgq_linear_a8w4 would launch for this problem."""
+    buf = ctypes.create_string_buffer(128)
+    _check(lib.dgq_linear_plan(M, N, K, group, buf, 128), "dgq_linear_plan")
+    return buf.value.decode()
 
 
 def probe_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int = 256, nbytes: int = None) -> None:

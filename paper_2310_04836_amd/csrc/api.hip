@@ -1,6 +1,7 @@
 // extern "C" boundary of libdgq.so: argument validation on the host, then one launcher.
 // Every check happens before anything is enqueued.
 #include <atomic>
+#include <cstdio>
 
 #include "dgq_device.hpp"
 
@@ -175,6 +176,31 @@ dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void
     dgq::LinearArgs a{xq, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
                       nullptr, nullptr, acc_out, M, N, K, group};
     return run_linear(a, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes)
+{
+    if (!buf) return DGQ_ERR_NULL;
+    if (M < 1 || buf_bytes < 96) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    const int forced = g_force_path.load(std::memory_order_relaxed);
+    if ((forced == kPathStream || forced == kPathStreamGeneric) && M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
+    switch (pick_path(M, forced)) {
+    case kPathStream: {
+        const dgq::DecodePlan p = dgq::decode_plan(K);
+        std::snprintf(buf, buf_bytes, "linear_decode_kernel<%d, %d, %d, false, %s>", p.spw, p.pf, group,
+                      p.ksplit > 1 ? "true" : "false");
+        break;
+    }
+    case kPathStreamGeneric: {
+        const dgq::StreamPlan p = dgq::stream_plan(M, N, K);
+        std::snprintf(buf, buf_bytes, "linear_stream_kernel<%d, %d, %d, %d, false>", p.mtiles, group, p.waves, p.depth);
+        break;
+    }
+    default:
+        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, false>", group);
+    }
+    return DGQ_OK;
 }
 
 dgq_status dgq_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, void *stream)

@@ -84,8 +84,19 @@ constexpr int kStreamMaxM = 64;
 // Decode kernel (one 16-token tile, activations resident in registers).
 constexpr int kDecodeMaxM = 16;
 constexpr int kDecodeMaxStepsPerWave = 6;  // 8 would spill at 128 VGPRs
-int decode_ksplit(int K);
+struct DecodePlan {
+    int spw;     // steps of 128 k per wavefront (template SPW)
+    int pf;      // column tiles prefetched ahead (template PF)
+    int ksplit;  // workgroups sharing one column tile's K
+};
+DecodePlan decode_plan(int K);
 size_t decode_workspace_bytes(int M, int N, int K);
+struct StreamPlan {
+    int mtiles;  // 16-token tiles (template MT)
+    int waves;   // wavefronts per workgroup = K split (template W)
+    int depth;   // steps of loads in flight (template D)
+};
+StreamPlan stream_plan(int M, int N, int K);
 hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st);
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
 hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);

@@ -254,42 +254,44 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
 }
 
 template <int G>
-hipError_t launch_g(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
+hipError_t launch_g(const LinearArgs &a, const DecodePlan &p, void *workspace, hipStream_t st)
 {
-    const int steps = a.K / 128;
-    const int per_part = (steps + ksplit - 1) / ksplit;
-    const int spw = (per_part + kWaves - 1) / kWaves;
-    // SPW steps per wavefront x PF tiles ahead = KiB of weight loads in flight per wavefront
-    if (spw <= 1) return launch_spw<1, 4, G>(a, ksplit, workspace, st);
-    if (spw <= 2) return launch_spw<2, 2, G>(a, ksplit, workspace, st);
-    if (spw <= 3) return launch_spw<3, 2, G>(a, ksplit, workspace, st);
-    if (spw <= 4) return launch_spw<4, 1, G>(a, ksplit, workspace, st);
-    if (spw <= 5) return launch_spw<5, 1, G>(a, ksplit, workspace, st);
-    if (spw <= 6) return launch_spw<6, 1, G>(a, ksplit, workspace, st);
-    return hipErrorInvalidValue;
+    switch (p.spw) {
+    case 1: return launch_spw<1, 4, G>(a, p.ksplit, workspace, st);
+    case 2: return launch_spw<2, 2, G>(a, p.ksplit, workspace, st);
+    case 3: return launch_spw<3, 2, G>(a, p.ksplit, workspace, st);
+    case 4: return launch_spw<4, 1, G>(a, p.ksplit, workspace, st);
+    case 5: return launch_spw<5, 1, G>(a, p.ksplit, workspace, st);
+    case 6: return launch_spw<6, 1, G>(a, p.ksplit, workspace, st);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
 
-int decode_ksplit(int K)
+DecodePlan decode_plan(int K)
 {
     const int steps = K / 128;
-    int s = 1;
-    while (((steps + s - 1) / s + kWaves - 1) / kWaves > kDecodeMaxStepsPerWave) s *= 2;
-    return s;
+    DecodePlan p;
+    p.ksplit = 1;
+    while (((steps + p.ksplit - 1) / p.ksplit + kWaves - 1) / kWaves > kDecodeMaxStepsPerWave) p.ksplit *= 2;
+    p.spw = ((steps + p.ksplit - 1) / p.ksplit + kWaves - 1) / kWaves;
+    // spw steps per wavefront x pf tiles ahead = KiB of weight loads in flight per wavefront
+    p.pf = p.spw <= 1 ? 4 : (p.spw <= 3 ? 2 : 1);
+    return p;
 }
 
 size_t decode_workspace_bytes(int M, int N, int K)
 {
-    const int s = decode_ksplit(K);
+    const int s = decode_plan(K).ksplit;
     return s > 1 ? (size_t)s * M * N * sizeof(int32_t) : 0;
 }
 
 hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st)
 {
     if (a.M > kDecodeMaxM) return hipErrorInvalidValue;
-    const int ksplit = decode_ksplit(a.K);
-    return a.group == 128 ? launch_g<128>(a, ksplit, workspace, st) : launch_g<64>(a, ksplit, workspace, st);
+    const DecodePlan p = decode_plan(a.K);
+    return a.group == 128 ? launch_g<128>(a, p, workspace, st) : launch_g<64>(a, p, workspace, st);
 }
 
 }  // namespace dgq

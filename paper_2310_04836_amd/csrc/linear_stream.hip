@@ -136,45 +136,56 @@ hipError_t launch_wd(const LinearArgs &a, hipStream_t st)
 }
 
 template <int MT, int G, int W>
-hipError_t launch_w(const LinearArgs &a, hipStream_t st)
+hipError_t launch_w(const LinearArgs &a, int d, hipStream_t st)
 {
-    // loads in flight per wavefront: as many steps as it has, up to 4 (2 for wide token tiles)
-    const int per_wave = (a.K / 128) / W;
-    if (MT <= 2 && per_wave >= 4) return launch_wd<MT, G, W, 4>(a, st);
-    if (per_wave >= 2) return launch_wd<MT, G, W, 2>(a, st);
+    if constexpr (MT <= 2)
+        if (d == 4) return launch_wd<MT, G, W, 4>(a, st);
+    if (d >= 2) return launch_wd<MT, G, W, 2>(a, st);
     return launch_wd<MT, G, W, 1>(a, st);
 }
 
 template <int MT, int G>
-hipError_t launch_mt(const LinearArgs &a, hipStream_t st)
+hipError_t launch_mt(const LinearArgs &a, const StreamPlan &p, hipStream_t st)
 {
-    // Enough wavefronts to keep every CU streaming (256 CUs x 16 wavefront slots); more
-    // K-splitting only while each wavefront still has a couple of steps.
-    const int tiles = a.N / 16;
-    const int steps = a.K / 128;
-    int w = 16;
-    while (w > 4 && (tiles * w > 8192 || steps / w < 2)) w >>= 1;
-    if (MT == 4 && w > 8) w = 8;  // LDS reduction buffer is W * MT KiB
     if constexpr (MT < 4)
-        if (w == 16) return launch_w<MT, G, 16>(a, st);
-    if (w >= 8) return launch_w<MT, G, 8>(a, st);
-    return launch_w<MT, G, 4>(a, st);
+        if (p.waves == 16) return launch_w<MT, G, 16>(a, p.depth, st);
+    if (p.waves == 8) return launch_w<MT, G, 8>(a, p.depth, st);
+    return launch_w<MT, G, 4>(a, p.depth, st);
 }
 
 template <int G>
-hipError_t launch_g(const LinearArgs &a, hipStream_t st)
+hipError_t launch_g(const LinearArgs &a, const StreamPlan &p, hipStream_t st)
 {
-    if (a.M <= 16) return launch_mt<1, G>(a, st);
-    if (a.M <= 32) return launch_mt<2, G>(a, st);
-    return launch_mt<4, G>(a, st);
+    if (p.mtiles == 1) return launch_mt<1, G>(a, p, st);
+    if (p.mtiles == 2) return launch_mt<2, G>(a, p, st);
+    return launch_mt<4, G>(a, p, st);
 }
 
 }  // namespace
 
+StreamPlan stream_plan(int M, int N, int K)
+{
+    StreamPlan p;
+    p.mtiles = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
+    // Enough wavefronts to keep every CU streaming (256 CUs x 16 wavefront slots); more
+    // K-splitting only while each wavefront still has a couple of steps.
+    const int tiles = N / 16;
+    const int steps = K / 128;
+    int w = 16;
+    while (w > 4 && (tiles * w > 8192 || steps / w < 2)) w >>= 1;
+    if (p.mtiles == 4 && w > 8) w = 8;  // LDS reduction buffer is waves * mtiles KiB
+    p.waves = w;
+    // loads in flight per wavefront: as many steps as it has, up to 4 (2 for wide token tiles)
+    const int per_wave = steps / w;
+    p.depth = (p.mtiles <= 2 && per_wave >= 4) ? 4 : (per_wave >= 2 ? 2 : 1);
+    return p;
+}
+
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st)
 {
     if (a.M > kStreamMaxM) return hipErrorInvalidValue;
-    return a.group == 128 ? launch_g<128>(a, st) : launch_g<64>(a, st);
+    const StreamPlan p = stream_plan(a.M, a.N, a.K);
+    return a.group == 128 ? launch_g<128>(a, p, st) : launch_g<64>(a, p, st);
 }
 
 }  // namespace dgq

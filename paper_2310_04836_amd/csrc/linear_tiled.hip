@@ -1,16 +1,19 @@
 // Tiled A8W4 linear for prefill-size M, bound by the INT8 matrix cores.
 //
-//   - Workgroup tile 128 tokens x 256 output channels, K walked in stages of 128.
-//     The four wavefronts split the output channels (64 each), so every packed weight is
-//     expanded to INT8 exactly once per workgroup.
+//   - Workgroup tile 128 tokens x 256 output channels, K walked in stages of 128; two
+//     workgroups share a CU.  The four wavefronts split the output channels (64 each), so
+//     every packed weight is expanded to INT8 exactly once per workgroup.
 //   - Weights never touch LDS: each lane loads 16-byte cells of qweight straight into VGPRs
-//     (a cell = 32 consecutive k of one column), expands them with the group scale
-//     (second line of Eq. 2) and feeds them as the B operand of v_mfma_i32_32x32x32_i8.
-//   - The INT8 activation tile is staged through LDS (double buffered, rows padded by 16
-//     bytes so that 128-bit reads of 8 consecutive rows hit distinct banks) and read as the
-//     A operand; lane (kb, i) reads the same k the weight cell of lane (kb, j) holds.
-//   - INT32 accumulation over all of K (third line of Eq. 2), then the scale epilogue
-//     (first line of Eq. 2) and one rounding to fp16.
+//     (a cell = 32 consecutive k of one column) two stages ahead of their use, expands them
+//     with the group scale (second line of Eq. 2) and feeds them as the B operand of
+//     v_mfma_i32_32x32x32_i8.
+//   - The INT8 activation tile goes from global memory directly into a three-stage LDS ring
+//     (global_load_lds_dwordx4, no registers in between), two stages ahead.  A row is 128
+//     bytes = eight 16-byte units; unit u of row r is stored at unit u ^ (r % 8), so that the
+//     128-bit reads of eight consecutive rows hit all 32 banks.  Lane (kb, i) reads as the A
+//     operand the same k that the weight cell of lane (kb, j) holds.
+//   - INT32 accumulation over all of K in AGPRs (third line of Eq. 2), then the scale
+//     epilogue (first line of Eq. 2) and one rounding to fp16.
 //   - Workgroups are numbered so that each XCD (workgroup id modulo 8) walks a contiguous
 //     range of tiles, M fastest: the tiles resident on one XCD share weight columns in
 //     that XCD's L2.
@@ -22,13 +25,64 @@ namespace {
 constexpr int BM = 128;
 constexpr int BN = 256;
 constexpr int BK = 128;
-constexpr int LDA = BK + 16;
+constexpr int kStages = 3;
 constexpr int kThreads = 256;
 
-template <int G, bool ACC>
-__global__ __launch_bounds__(kThreads) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n)
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// All global loads of the main loop are written as inline assembly, and all waiting for them
+// is explicit (one s_waitcnt vmcnt(N) + barrier at the top of each stage).
+//
+// Why: the stage prefetch runs two stages ahead, both for weights (into registers) and for
+// activations (straight into LDS).  The compiler makes every LDS read that follows a
+// direct-to-LDS load it knows about wait for ALL outstanding vector loads (vmcnt(0)), which
+// would serialise the prefetch behind the current stage.  With the loads invisible to its
+// bookkeeping, the only waits are the ones written here, and they rely on vector loads
+// completing in issue order: "at most N outstanding" means everything but the N youngest
+// has landed.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+// One wavefront copies 1 KiB from global memory straight into LDS: lane l's 16 bytes at `src`
+// land at LDS byte address lds_base + 16*l (lds_base is wavefront-uniform and goes through M0).
+__device__ __forceinline__ void lds_dma_1k(const void *src, uint32_t lds_base)
 {
-    __shared__ __attribute__((aligned(16))) int8_t lds_a[2][BM * LDA];
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(lds_base)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ v4u load_b128_async(const void *src)
+{
+    v4u r;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(src) : "memory");
+    return r;
+}
+__device__ __forceinline__ v4u load_b128_async_512(const void *src)
+{
+    v4u r;
+    asm volatile("global_load_dwordx4 %0, %1, off offset:512" : "=v"(r) : "v"(src) : "memory");
+    return r;
+}
+__device__ __forceinline__ uint32_t load_b32_async(const void *src)
+{
+    uint32_t r;
+    asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(src) : "memory");
+    return r;
+}
+// After the explicit wait: ties the registers of an asynchronously loaded set to this point, so
+// that nothing that uses them can be scheduled above the wait and the registers stay reserved
+// for the load until then.  EVERY register written by load_*_async must pass through here after
+// the wait that covers it, also when its value is never used.
+__device__ __forceinline__ void arrive(v4u &a, v4u &b, v4u &c, v4u &d, uint32_t &e, uint32_t &f)
+{
+    asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e), "+v"(f));
+}
+
+template <int G, bool ACC>
+__global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n)
+{
+    __shared__ __attribute__((aligned(1024))) int8_t lds_a[kStages][BM * BK];
+#define DGQ_LDS(P) (lds_a[P])
 
     const int T = tiles_m * tiles_n;
     const int per_xcd = (T + 7) >> 3;
@@ -39,12 +93,11 @@ __global__ __launch_bounds__(kThreads) void linear_tiled_kernel(LinearArgs a, in
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = lane >> 5;
     const int li = lane & 31;
     const int steps = a.K >> 7;
-    const int ng = a.K / G;
-    const int gqn = (ng + 3) >> 2;
+    const int gqn = ((a.K / G) + 3) >> 2;
 
     // ---- weight stream: two 32-column tiles per wavefront -------------------------------
     const uint4 *bp[2];
@@ -58,18 +111,20 @@ __global__ __launch_bounds__(kThreads) void linear_tiled_kernel(LinearArgs a, in
         bp[nj] = a.qweight + (size_t)(n >> 4) * steps * 64 + kb * 16 + (n & 15);
         sp[nj] = a.scales + (size_t)(n >> 4) * gqn * 16 + (n & 15);
     }
-    // ---- activation tile: thread copies four 16-byte units per stage ----------------------
-    const int unit = tid & 7;
-    const uint4 *gp[4];
-    int lds_off[4];
+    // ---- activation tile: each wavefront moves four 1 KiB pieces (8 rows) per stage --------
+    // lane l of piece q lands at LDS row r = (wave*4+q)*8 + l/8, stored unit l%8, which is
+    // the place of global unit (l%8) ^ (r%8) = (l%8) ^ (l/8).
+    const int8_t *gp[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int r = (tid >> 3) + 32 * q;
+        const int r = (wave * 4 + q) * 8 + (lane >> 3);
         int m = m0 + r;
         if (m >= a.M) m = a.M - 1;  // ragged M: duplicate the last row, never store it
-        gp[q] = reinterpret_cast<const uint4 *>(a.xq + (size_t)m * a.K + unit * 16);
-        lds_off[q] = r * LDA + unit * 16;
+        gp[q] = a.xq + (size_t)m * a.K + (((lane & 7) ^ (lane >> 3)) << 4);
     }
+
+    // LDS byte address of this wavefront's first piece in stage buffer 0
+    const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[0][0] + wave * 4096;
 
     v16i acc[4][2];
 #pragma unroll
@@ -79,74 +134,97 @@ __global__ __launch_bounds__(kThreads) void linear_tiled_kernel(LinearArgs a, in
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0;
 
-    uint4 ga[4];     // activation units in flight from global memory to LDS
-    uint4 bq[2][2];  // weight cells of the next stage: [column tile][k half]
-    uint32_t sw[2];  // four group scales of each of this lane's two columns
+    v4u bq[kStages][2][2];    // [stage % 3][column tile][k half]
+    uint32_t sw[kStages][2];  // [stage % 3][column tile]: four group scales of this lane's column
 
-#define DGQ_LOAD_STAGE(S)                                                                   \
-    do {                                                                                    \
-        const int s_ = (S);                                                                 \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q) ga[q] = gp[q][(size_t)s_ * (BK / 16)]; \
-        const int gq_ = ((G == 128) ? s_ : 2 * s_) >> 2;                                    \
-        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                    \
-        {                                                                                   \
-            bq[nj][0] = bp[nj][(size_t)s_ * 64];                                            \
-            bq[nj][1] = bp[nj][(size_t)s_ * 64 + 32];                                       \
-            sw[nj] = sp[nj][(size_t)gq_ * 16];                                              \
-        }                                                                                   \
+#define DGQ_LOAD_B(P, S)                                                   \
+    do {                                                                   \
+        const int s_ = (S);                                                \
+        const int gq_ = ((G == 128) ? s_ : 2 * s_) >> 2;                   \
+        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                   \
+        {                                                                  \
+            bq[P][nj][0] = load_b128_async(bp[nj] + (size_t)s_ * 64);      \
+            bq[P][nj][1] = load_b128_async_512(bp[nj] + (size_t)s_ * 64);  \
+            sw[P][nj] = load_b32_async(sp[nj] + (size_t)gq_ * 16);         \
+        }                                                                  \
     } while (0)
-#define DGQ_STORE_A(BUF)                                                                   \
-    do {                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                       \
-            *reinterpret_cast<uint4 *>(&lds_a[(BUF)][lds_off[q]]) = ga[q];                  \
+#define DGQ_LOAD_A(BUF, S)                                                                          \
+    do {                                                                                            \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                               \
+            lds_dma_1k(gp[q] + (size_t)(S) * BK, lds_base + (BUF) * (BM * BK) + q * 1024);          \
     } while (0)
 
-    DGQ_LOAD_STAGE(0);
-    DGQ_STORE_A(0);
-    __syncthreads();
+    // per-lane LDS read offsets: row li of each 32-row block, units 2*kb + {0,1} (+4 for h=1)
+    int a_off[2][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) a_off[h][t] = li * BK + (((4 * h + 2 * kb + t) ^ (li & 7)) << 4);
 
-    const int a_lane_off = li * LDA + kb * 32;
-    for (int s = 0; s < steps; ++s) {
-        const int cur = s & 1;
-        uint4 cq[2][2];
-        uint32_t csw[2];
-#pragma unroll
-        for (int nj = 0; nj < 2; ++nj) {
-            cq[nj][0] = bq[nj][0];
-            cq[nj][1] = bq[nj][1];
-            csw[nj] = sw[nj];
-        }
-        // Prefetch the next stage; the last iteration re-reads its own stage (unused).
-        DGQ_LOAD_STAGE(s + 1 < steps ? s + 1 : s);
+    const int last = steps - 1;
+    // prologue: stages 0 and 1 in flight
+    DGQ_LOAD_B(0, 0);
+    DGQ_LOAD_A(0, 0);
+    DGQ_LOAD_B(1, last < 1 ? last : 1);
+    DGQ_LOAD_A(1, last < 1 ? last : 1);
 
-        const int8_t *la = &lds_a[cur][a_lane_off];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int gi = (G == 128) ? s : 2 * s + h;
-            v4i bf[2][2];
-#pragma unroll
-            for (int nj = 0; nj < 2; ++nj) {
-                const GroupScale gs = make_group_scale((csw[nj] >> (8 * (gi & 3))) & 0xFFu);
-                expand_cell(cq[nj][h], gs, bf[nj][0], bf[nj][1]);
-            }
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                for (int mi = 0; mi < 4; ++mi) {
-                    const v4i af = *reinterpret_cast<const v4i *>(la + mi * 32 * LDA + h * 64 + t * 16);
-#pragma unroll
-                    for (int nj = 0; nj < 2; ++nj)
-                        acc[mi][nj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[nj][t], acc[mi][nj], 0, 0, 0);
-                }
-            }
-        }
-        // The other buffer was last read before the barrier that ended the previous
-        // iteration, so it can be overwritten now.
-        DGQ_STORE_A(cur ^ 1);
-        __syncthreads();
+    // Stage s uses register set and LDS buffer s % 3 and refills set/buffer (s + 2) % 3, which
+    // stage s - 1 used; the barrier at the top of stage s guarantees that every wavefront has
+    // finished reading that buffer.
+#define DGQ_STAGE(P, S)                                                                                 \
+    do {                                                                                                \
+        const int s_ = (S);                                                                             \
+        /* stage s_ has landed once only the 10 loads of stage s_+1 (6 weight/scale loads and 4 */      \
+        /* LDS copies per lane) are still outstanding                                          */      \
+        __builtin_amdgcn_s_waitcnt(0x0F70 | 10);                                                        \
+        __syncthreads();                                                                                \
+        arrive(bq[P][0][0], bq[P][0][1], bq[P][1][0], bq[P][1][1], sw[P][0], sw[P][1]);                 \
+        /* refill: stage s_+2 (past the end: re-read the last stage, unused) */                         \
+        const int sn_ = s_ + 2 < steps ? s_ + 2 : last;                                                 \
+        DGQ_LOAD_B((P + 2) % kStages, sn_);                                                             \
+        DGQ_LOAD_A((P + 2) % kStages, sn_);                                                             \
+        __builtin_amdgcn_sched_barrier(0); /* keep the prefetch at the top of the stage */              \
+        const int8_t *la = &DGQ_LDS(P)[0];                                                                    \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                   \
+        {                                                                                               \
+            const int gi = (G == 128) ? s_ : 2 * s_ + h;                                                \
+            v4i bf[2][2];                                                                               \
+            _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                            \
+            {                                                                                           \
+                const GroupScale gs = make_group_scale((sw[P][nj] >> (8 * (gi & 3))) & 0xFFu);          \
+                expand_cell(__builtin_bit_cast(uint4, bq[P][nj][h]), gs, bf[nj][0], bf[nj][1]);                                 \
+            }                                                                                           \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t)                                               \
+            {                                                                                           \
+                _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                        \
+                {                                                                                       \
+                    const v4i af = *reinterpret_cast<const v4i *>(la + mi * 32 * BK + a_off[h][t]);     \
+                    _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) acc[mi][nj] =                      \
+                        __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[nj][t], acc[mi][nj], 0, 0, 0);     \
+                }                                                                                       \
+            }                                                                                           \
+        }                                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+    } while (0)
+
+    int s = 0;
+    for (; s + 3 <= steps; s += 3) {
+        DGQ_STAGE(0, s);
+        DGQ_STAGE(1, s + 1);
+        DGQ_STAGE(2, s + 2);
     }
-#undef DGQ_LOAD_STAGE
-#undef DGQ_STORE_A
+    if (s < steps) DGQ_STAGE(0, s);
+    if (s + 1 < steps) DGQ_STAGE(1, s + 1);
+    // The re-reads issued by the last two stages are unused but still in flight.  Their
+    // destination registers must stay reserved until they have landed: a register the compiler
+    // considers dead could be handed to another value and then be overwritten by the late load.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+    for (int p = 0; p < kStages; ++p) arrive(bq[p][0][0], bq[p][0][1], bq[p][1][0], bq[p][1][1], sw[p][0], sw[p][1]);
+#undef DGQ_STAGE
+#undef DGQ_LDS
+#undef DGQ_LOAD_A
+#undef DGQ_LOAD_B
 
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
 #pragma unroll

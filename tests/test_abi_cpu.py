@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 13 and len(set(names)) == 13
+    assert len(names) == 14 and len(set(names)) == 14
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -82,6 +82,14 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4(good, good, odd, good, good, good, 1, 16, 128, 128, None, 0, None) == -3
     assert L.dgq_pack_weights(good, good, 128, 16, 128, odd, good, None, None) == -3
     assert L.dgq_pack_weights(good, good, 128, 16, 128, good, good, 0x10002, None) == -3
+
+
+def test_linear_plan_names(dgq):
+    assert dgq.linear_plan(16, 22016, 4096, 128) == "linear_decode_kernel<2, 2, 128, false, false>"
+    assert dgq.linear_plan(1, 4096, 11008, 128) == "linear_decode_kernel<6, 1, 128, false, false>"
+    assert dgq.linear_plan(8, 8192, 22016, 64) == "linear_decode_kernel<6, 1, 64, false, true>"
+    assert dgq.linear_plan(64, 8192, 8192, 128).startswith("linear_stream_kernel<4, 128, ")
+    assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, false>"
 
 
 def test_force_path_selector(dgq):
