@@ -9,8 +9,9 @@
 //     v_mfma_i32_32x32x32_i8.
 //   - The INT8 activation tile goes from global memory directly into a three-stage LDS ring
 //     (global_load_lds_dwordx4, no registers in between), two stages ahead.  A row is 128
-//     bytes = eight 16-byte units; unit u of row r is stored at unit u ^ (r % 8), so that the
-//     128-bit reads of eight consecutive rows hit all 32 banks.  Lane (kb, i) reads as the A
+//     bytes = eight 16-byte units; unit u of row r is stored at unit u ^ ((r/2) % 8), so that
+//     the 128-bit reads of sixteen consecutive rows (one read phase) fall on sixteen different
+//     16-byte slots of the 256-byte bank line.  Lane (kb, i) reads as the A
 //     operand the same k that the weight cell of lane (kb, j) holds.
 //   - INT32 accumulation over all of K in AGPRs (third line of Eq. 2), then the scale
 //     epilogue (first line of Eq. 2) and one rounding to fp16.
@@ -113,14 +114,14 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
     }
     // ---- activation tile: each wavefront moves four 1 KiB pieces (8 rows) per stage --------
     // lane l of piece q lands at LDS row r = (wave*4+q)*8 + l/8, stored unit l%8, which is
-    // the place of global unit (l%8) ^ (r%8) = (l%8) ^ (l/8).
+    // the place of global unit (l%8) ^ ((r/2)%8).
     const int8_t *gp[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int r = (wave * 4 + q) * 8 + (lane >> 3);
         int m = m0 + r;
         if (m >= a.M) m = a.M - 1;  // ragged M: duplicate the last row, never store it
-        gp[q] = a.xq + (size_t)m * a.K + (((lane & 7) ^ (lane >> 3)) << 4);
+        gp[q] = a.xq + (size_t)m * a.K + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
     }
 
     // LDS byte address of this wavefront's first piece in stage buffer 0
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) a_off[h][t] = li * BK + (((4 * h + 2 * kb + t) ^ (li & 7)) << 4);
+        for (int t = 0; t < 2; ++t) a_off[h][t] = li * BK + (((4 * h + 2 * kb + t) ^ ((li >> 1) & 7)) << 4);
 
     const int last = steps - 1;
     // prologue: stages 0 and 1 in flight
