@@ -227,28 +227,59 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
 #undef DGQ_LOAD_A
 #undef DGQ_LOAD_B
 
+    // ---- epilogue ---------------------------------------------------------------------------
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
+    __syncthreads();  // every wavefront is done with the LDS ring
+    if (ACC) {
 #pragma unroll
-    for (int nj = 0; nj < 2; ++nj) {
-        const int n = ncol[nj];
-        if (n >= a.N) continue;
-        float s1n = 0.0f;
-        if (!ACC) s1n = a.s1[n];
+        for (int nj = 0; nj < 2; ++nj) {
+            const int n = ncol[nj];
+            if (n >= a.N) continue;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
+            for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + mi * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
-                if (m < a.M) {
-                    if (ACC) {
-                        a.acc_out[(size_t)m * a.N + n] = acc[mi][nj][r];
-                    } else {
-                        const float sc = a.sx[m] * s1n;
-                        const _Float16 hv = (_Float16)(sc * (float)acc[mi][nj][r]);
-                        a.out[(size_t)m * a.N + n] = __builtin_bit_cast(unsigned short, hv);
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + mi * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
+                    if (m < a.M) a.acc_out[(size_t)m * a.N + n] = acc[mi][nj][r];
                 }
-            }
+        }
+        return;
+    }
+    // fp16 path.  The token scales of the tile go through LDS, so that scaling 128 accumulators
+    // per lane does not wait on global memory.  The scaled fp16 values are then transposed
+    // through a per-wavefront LDS region (64 tokens x 64 channels at a time) so that every lane
+    // stores 16 contiguous bytes and eight lanes cover a whole 128-byte line of the output.
+    float *lds_sx = reinterpret_cast<float *>(&lds_a[0][0]);
+    unsigned short *lds_t = reinterpret_cast<unsigned short *>(&lds_a[0][0] + 1024 + wave * 8192);
+    if (tid < BM) lds_sx[tid] = (m0 + tid < a.M) ? a.sx[m0 + tid] : 0.0f;
+    float s1n[2];
+#pragma unroll
+    for (int nj = 0; nj < 2; ++nj) s1n[nj] = ncol[nj] < a.N ? a.s1[ncol[nj]] : 0.0f;
+    __syncthreads();
+    const int nw0 = n0 + wave * 64;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) {
+            const int mi = half * 2 + mh;
+#pragma unroll
+            for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = mh * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
+                    const float sc = lds_sx[half * 64 + row] * s1n[nj];
+                    const _Float16 hv = (_Float16)(sc * (float)acc[mi][nj][r]);
+                    lds_t[row * 64 + nj * 32 + li] = __builtin_bit_cast(unsigned short, hv);
+                }
+        }
+        // 64 rows x 128 bytes: lane l takes 16-byte chunk l%8 of rows l/8, l/8 + 8, ...
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int row = j * 8 + (lane >> 3);
+            const int m = m0 + half * 64 + row;
+            const int n = nw0 + (lane & 7) * 8;
+            const uint4 v = *reinterpret_cast<const uint4 *>(&lds_t[row * 64 + (lane & 7) * 8]);
+            if (m < a.M && n < a.N) *reinterpret_cast<uint4 *>(&a.out[(size_t)m * a.N + n]) = v;
         }
     }
 }
