@@ -34,9 +34,13 @@ WORKLOADS = {
     "llama65b_g64": ("65b", [1, 8, 64, 512, 2048], 64),
 }
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured.
-TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter shows for a 1 GiB copy
+# (FETCH_SIZE reads 0.5 GiB per GiB read: x2.0; WRITE_SIZE x1.0).  Figures and commands are in
+# profiles/; a workload that has not been profiled reports null.
+TRAFFIC_BYTES = {
+    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14147.0 + 175.0) * 1024,
+}
 
 
 def log(*a):
