@@ -198,7 +198,7 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
         break;
     }
     default:
-        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, false>", group);
+        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, %d, false>", group, dgq::tiled_waves(M, N));
     }
     return DGQ_OK;
 }

@@ -99,6 +99,7 @@ struct StreamPlan {
 StreamPlan stream_plan(int M, int N, int K);
 hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st);
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
+int tiled_waves(int M, int N);  // wavefronts per workgroup the tiled kernel uses (template NW)
 hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);
 
 hipError_t launch_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t st);

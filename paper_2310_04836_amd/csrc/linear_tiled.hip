@@ -1,8 +1,8 @@
 // Tiled A8W4 linear for prefill-size M, bound by the INT8 matrix cores.
 //
-//   - Workgroup tile 128 tokens x 256 output channels, K walked in stages of 128; two
-//     workgroups share a CU.  The four wavefronts split the output channels (64 each), so
-//     every packed weight is expanded to INT8 exactly once per workgroup.
+//   - Workgroup tile 128 tokens x 256 or 512 output channels (4 or 8 wavefronts, two per
+//     SIMD), K walked in stages of 128.  The wavefronts split the output channels (64 each),
+//     so every packed weight is expanded to INT8 exactly once per workgroup.
 //   - Weights never touch LDS: each lane loads 16-byte cells of qweight straight into VGPRs
 //     (a cell = 32 consecutive k of one column) two stages ahead of their use, expands them
 //     with the group scale (second line of Eq. 2) and feeds them as the B operand of
@@ -24,10 +24,8 @@ namespace dgq {
 namespace {
 
 constexpr int BM = 128;
-constexpr int BN = 256;
 constexpr int BK = 128;
 constexpr int kStages = 3;
-constexpr int kThreads = 256;
 
 typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -43,31 +41,44 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 // has landed.
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
-// One wavefront copies 1 KiB from global memory straight into LDS: lane l's 16 bytes at `src`
-// land at LDS byte address lds_base + 16*l (lds_base is wavefront-uniform and goes through M0).
-__device__ __forceinline__ void lds_dma_1k(const void *src, uint32_t lds_base)
+// Addresses are a wavefront-uniform 64-bit base (SGPR pair, advanced per stage with scalar
+// arithmetic) plus a per-lane 32-bit byte offset that never changes, so the main loop computes
+// no vector addresses at all.
+
+// One wavefront copies 1 KiB from global memory straight into LDS: lane l's 16 bytes at
+// base + off land at LDS byte address lds_base + 16*l (lds_base is uniform and goes through M0).
+__device__ __forceinline__ void lds_dma_1k(const void *base, uint32_t off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(src), "s"(lds_base)
+                 : "v"(off), "s"(base), "s"(lds_base)
                  : "memory", "m0");
 }
-__device__ __forceinline__ v4u load_b128_async(const void *src)
+__device__ __forceinline__ v4u load_b128_async(const void *base, uint32_t off)
 {
     v4u r;
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(src) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(r) : "v"(off), "s"(base) : "memory");
     return r;
 }
-__device__ __forceinline__ v4u load_b128_async_512(const void *src)
+__device__ __forceinline__ v4u load_b128_async_512(const void *base, uint32_t off)
 {
     v4u r;
-    asm volatile("global_load_dwordx4 %0, %1, off offset:512" : "=v"(r) : "v"(src) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:512" : "=v"(r) : "v"(off), "s"(base) : "memory");
     return r;
 }
-__device__ __forceinline__ uint32_t load_b32_async(const void *src)
+__device__ __forceinline__ uint32_t load_b32_async(const void *base, uint32_t off)
 {
     uint32_t r;
-    asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(src) : "memory");
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(r) : "v"(off), "s"(base) : "memory");
+    return r;
+}
+// One MFMA operand (16 consecutive k of one column) from half of a weight cell: the low
+// nibbles (hi = 0, k 0..15 of the cell) or the high nibbles (hi = 1, k 16..31).
+__device__ __forceinline__ v4i expand_half(const v4u &q, const GroupScale &g, int hi)
+{
+    v4i r;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) r[v] = (int)scale_bytes((hi ? (q[v] >> 4) : q[v]) & 0x0F0F0F0Fu, g);
     return r;
 }
 // After the explicit wait: ties the registers of an asynchronously loaded set to this point, so
@@ -79,11 +90,15 @@ __device__ __forceinline__ void arrive(v4u &a, v4u &b, v4u &c, v4u &d, uint32_t 
     asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e), "+v"(f));
 }
 
-template <int G, bool ACC>
-__global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n)
+// NW wavefronts per workgroup, each owning 64 output channels of the 128 x (64*NW) tile.
+template <int G, int NW, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n)
 {
+    constexpr int BN = 64 * NW;
+    constexpr int PPW = 16 / NW;  // 1 KiB pieces of the activation tile each wavefront copies per stage
+    constexpr int kLoadsPerStage = 6 + PPW;
+
     __shared__ __attribute__((aligned(1024))) int8_t lds_a[kStages][BM * BK];
-#define DGQ_LDS(P) (lds_a[P])
 
     const int T = tiles_m * tiles_n;
     const int per_xcd = (T + 7) >> 3;
@@ -100,32 +115,31 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
     const int steps = a.K >> 7;
     const int gqn = ((a.K / G) + 3) >> 2;
 
-    // ---- weight stream: two 32-column tiles per wavefront -------------------------------
-    const uint4 *bp[2];
-    const uint32_t *sp[2];
+    // ---- weight stream: two 32-column tiles per wavefront; per-lane byte offsets ------------
+    uint32_t boff[2], soff[2];
     int ncol[2];
 #pragma unroll
     for (int nj = 0; nj < 2; ++nj) {
         int n = n0 + wave * 64 + nj * 32 + li;
         ncol[nj] = n;
         if (n >= a.N) n = a.N - 1;  // ragged N: read a valid column, never store it
-        bp[nj] = a.qweight + (size_t)(n >> 4) * steps * 64 + kb * 16 + (n & 15);
-        sp[nj] = a.scales + (size_t)(n >> 4) * gqn * 16 + (n & 15);
+        boff[nj] = ((uint32_t)(n >> 4) * steps * 64 + kb * 16 + (n & 15)) * 16u;
+        soff[nj] = ((uint32_t)(n >> 4) * gqn * 16 + (n & 15)) * 4u;
     }
-    // ---- activation tile: each wavefront moves four 1 KiB pieces (8 rows) per stage --------
-    // lane l of piece q lands at LDS row r = (wave*4+q)*8 + l/8, stored unit l%8, which is
+    // ---- activation tile: each wavefront moves PPW 1 KiB pieces (8 rows each) per stage ------
+    // lane l of piece q lands at LDS row r = (wave*PPW+q)*8 + l/8, stored unit l%8, which is
     // the place of global unit (l%8) ^ ((r/2)%8).
-    const int8_t *gp[4];
+    uint32_t goff[PPW];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int r = (wave * 4 + q) * 8 + (lane >> 3);
+    for (int q = 0; q < PPW; ++q) {
+        const int r = (wave * PPW + q) * 8 + (lane >> 3);
         int m = m0 + r;
         if (m >= a.M) m = a.M - 1;  // ragged M: duplicate the last row, never store it
-        gp[q] = a.xq + (size_t)m * a.K + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
+        goff[q] = (uint32_t)m * a.K + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
     }
 
     // LDS byte address of this wavefront's first piece in stage buffer 0
-    const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[0][0] + wave * 4096;
+    const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[0][0] + wave * PPW * 1024;
 
     v16i acc[4][2];
 #pragma unroll
@@ -138,74 +152,98 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
     v4u bq[kStages][2][2];    // [stage % 3][column tile][k half]
     uint32_t sw[kStages][2];  // [stage % 3][column tile]: four group scales of this lane's column
 
-#define DGQ_LOAD_B(P, S)                                                   \
-    do {                                                                   \
-        const int s_ = (S);                                                \
-        const int gq_ = ((G == 128) ? s_ : 2 * s_) >> 2;                   \
-        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                   \
-        {                                                                  \
-            bq[P][nj][0] = load_b128_async(bp[nj] + (size_t)s_ * 64);      \
-            bq[P][nj][1] = load_b128_async_512(bp[nj] + (size_t)s_ * 64);  \
-            sw[P][nj] = load_b32_async(sp[nj] + (size_t)gq_ * 16);         \
-        }                                                                  \
+    // Loads of one stage, weights first: "weights of stage s have landed" can then be waited for
+    // separately from (and earlier than) "activations of stage s have landed".
+#define DGQ_LOAD_STAGE(P, S)                                                                         \
+    do {                                                                                             \
+        const int ls_ = (S);                                                                          \
+        const char *qb_ = reinterpret_cast<const char *>(a.qweight) + (size_t)ls_ * 1024;             \
+        const char *sb_ = reinterpret_cast<const char *>(a.scales) +                                 \
+                          (size_t)(((G == 128) ? ls_ : 2 * ls_) >> 2) * 64;                            \
+        const char *xb_ = reinterpret_cast<const char *>(a.xq) + (size_t)ls_ * BK;                    \
+        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                             \
+        {                                                                                            \
+            bq[P][nj][0] = load_b128_async(qb_, boff[nj]);                                           \
+            bq[P][nj][1] = load_b128_async_512(qb_, boff[nj]);                                       \
+            sw[P][nj] = load_b32_async(sb_, soff[nj]);                                               \
+        }                                                                                            \
+        _Pragma("unroll") for (int q = 0; q < PPW; ++q)                                              \
+            lds_dma_1k(xb_, goff[q], lds_base + (P) * (BM * BK) + q * 1024);                         \
     } while (0)
-#define DGQ_LOAD_A(BUF, S)                                                                          \
-    do {                                                                                            \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                               \
-            lds_dma_1k(gp[q] + (size_t)(S) * BK, lds_base + (BUF) * (BM * BK) + q * 1024);          \
-    } while (0)
+#define DGQ_ARRIVE(P) arrive(bq[P][0][0], bq[P][0][1], bq[P][1][0], bq[P][1][1], sw[P][0], sw[P][1])
 
-    // per-lane LDS read offsets: row li of each 32-row block, units 2*kb + {0,1} (+4 for h=1)
-    int a_off[2][2];
+    // per-lane LDS read offsets: row li of each 32-row block, units 2*kb + t (+4 for h = 1)
+    int a_off[4];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) a_off[h][t] = li * BK + (((4 * h + 2 * kb + t) ^ ((li >> 1) & 7)) << 4);
+    for (int g4 = 0; g4 < 4; ++g4) a_off[g4] = li * BK + (((2 * g4 - (g4 & 1) + 2 * kb) ^ ((li >> 1) & 7)) << 4);
+
+    // The 128 k of a stage are consumed in four groups (h, t) = (0,0), (0,1), (1,0), (1,1) of
+    // eight MFMAs each.  While the MFMAs of one group run, the operands of the next group are
+    // prepared: its four activation fragments are read from LDS and its two weight operands
+    // are expanded, both into the other half of a two-deep register buffer.
+    v4i af[2][4];  // [group parity][mi]
+    v4i bf[2][2];  // [group parity][nj]
+#define DGQ_READ_A(PAR, P, GRP)                                                                      \
+    do {                                                                                             \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) af[PAR][mi] =                               \
+            *reinterpret_cast<const v4i *>(&lds_a[P][mi * 32 * BK + a_off[GRP]]);                    \
+    } while (0)
+#define DGQ_EXPAND(PAR, P, S, GRP)                                                                   \
+    do {                                                                                             \
+        const int gi_ = (G == 128) ? (S) : 2 * (S) + ((GRP) >> 1);                                   \
+        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                             \
+        {                                                                                            \
+            const GroupScale gs_ = make_group_scale((sw[P][nj] >> (8 * (gi_ & 3))) & 0xFFu);         \
+            bf[PAR][nj] = expand_half(bq[P][nj][(GRP) >> 1], gs_, (GRP) & 1);                        \
+        }                                                                                            \
+    } while (0)
+#define DGQ_MFMA(PAR)                                                                                \
+    do {                                                                                             \
+        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                             \
+        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) acc[mi][nj] =                               \
+            __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][mi], bf[PAR][nj], acc[mi][nj], 0, 0, 0);   \
+    } while (0)
 
     const int last = steps - 1;
-    // prologue: stages 0 and 1 in flight
-    DGQ_LOAD_B(0, 0);
-    DGQ_LOAD_A(0, 0);
-    DGQ_LOAD_B(1, last < 1 ? last : 1);
-    DGQ_LOAD_A(1, last < 1 ? last : 1);
+    // prologue: stages 0 and 1 in flight; first weight operands expanded
+    DGQ_LOAD_STAGE(0, 0);
+    DGQ_LOAD_STAGE(1, last < 1 ? last : 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (PPW + kLoadsPerStage));  // weights of stage 0
+    DGQ_ARRIVE(0);
+    DGQ_EXPAND(0, 0, 0, 0);
 
     // Stage s uses register set and LDS buffer s % 3 and refills set/buffer (s + 2) % 3, which
     // stage s - 1 used; the barrier at the top of stage s guarantees that every wavefront has
-    // finished reading that buffer.
-#define DGQ_STAGE(P, S)                                                                                 \
-    do {                                                                                                \
-        const int s_ = (S);                                                                             \
-        /* stage s_ has landed once only the 10 loads of stage s_+1 (6 weight/scale loads and 4 */      \
-        /* LDS copies per lane) are still outstanding                                          */      \
-        __builtin_amdgcn_s_waitcnt(0x0F70 | 10);                                                        \
-        __syncthreads();                                                                                \
-        arrive(bq[P][0][0], bq[P][0][1], bq[P][1][0], bq[P][1][1], sw[P][0], sw[P][1]);                 \
-        /* refill: stage s_+2 (past the end: re-read the last stage, unused) */                         \
-        const int sn_ = s_ + 2 < steps ? s_ + 2 : last;                                                 \
-        DGQ_LOAD_B((P + 2) % kStages, sn_);                                                             \
-        DGQ_LOAD_A((P + 2) % kStages, sn_);                                                             \
-        __builtin_amdgcn_sched_barrier(0); /* keep the prefetch at the top of the stage */              \
-        const int8_t *la = &DGQ_LDS(P)[0];                                                                    \
-        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                   \
-        {                                                                                               \
-            const int gi = (G == 128) ? s_ : 2 * s_ + h;                                                \
-            v4i bf[2][2];                                                                               \
-            _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                            \
-            {                                                                                           \
-                const GroupScale gs = make_group_scale((sw[P][nj] >> (8 * (gi & 3))) & 0xFFu);          \
-                expand_cell(__builtin_bit_cast(uint4, bq[P][nj][h]), gs, bf[nj][0], bf[nj][1]);                                 \
-            }                                                                                           \
-            _Pragma("unroll") for (int t = 0; t < 2; ++t)                                               \
-            {                                                                                           \
-                _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                        \
-                {                                                                                       \
-                    const v4i af = *reinterpret_cast<const v4i *>(la + mi * 32 * BK + a_off[h][t]);     \
-                    _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) acc[mi][nj] =                      \
-                        __builtin_amdgcn_mfma_i32_32x32x32_i8(af, bf[nj][t], acc[mi][nj], 0, 0, 0);     \
-                }                                                                                       \
-            }                                                                                           \
-        }                                                                                               \
-        __builtin_amdgcn_sched_barrier(0);                                                              \
+    // finished reading that buffer.  On entry bf[0] already holds group 0 of this stage.
+#define DGQ_STAGE(P, S)                                                                              \
+    do {                                                                                             \
+        const int s_ = (S);                                                                          \
+        /* stage s_ has landed once only the loads of stage s_+1 are still outstanding */            \
+        __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStage);                                         \
+        __syncthreads();                                                                             \
+        DGQ_ARRIVE(P);                                                                               \
+        DGQ_READ_A(0, P, 0);                                                                         \
+        /* refill: stage s_+2 (past the end: re-read the last stage, unused) */                      \
+        DGQ_LOAD_STAGE((P + 2) % kStages, s_ + 2 < steps ? s_ + 2 : last);                           \
+        __builtin_amdgcn_sched_barrier(0); /* keep the prefetch at the top of the stage */           \
+        DGQ_READ_A(1, P, 1);                                                                         \
+        DGQ_EXPAND(1, P, s_, 1);                                                                     \
+        DGQ_MFMA(0);                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+        DGQ_READ_A(0, P, 2);                                                                         \
+        DGQ_EXPAND(0, P, s_, 2);                                                                     \
+        DGQ_MFMA(1);                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+        DGQ_READ_A(1, P, 3);                                                                         \
+        DGQ_EXPAND(1, P, s_, 3);                                                                     \
+        DGQ_MFMA(0);                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
+        /* weights of stage s_+1: everything but its LDS copies and the loads of stage s_+2 */       \
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (PPW + kLoadsPerStage));                                 \
+        DGQ_ARRIVE((P + 1) % kStages);                                                               \
+        DGQ_EXPAND(0, (P + 1) % kStages, s_ + 1, 0);                                                 \
+        DGQ_MFMA(1);                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                           \
     } while (0)
 
     int s = 0;
@@ -221,11 +259,13 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
     // considers dead could be handed to another value and then be overwritten by the late load.
     __builtin_amdgcn_s_waitcnt(0x0F70);
 #pragma unroll
-    for (int p = 0; p < kStages; ++p) arrive(bq[p][0][0], bq[p][0][1], bq[p][1][0], bq[p][1][1], sw[p][0], sw[p][1]);
+    for (int p = 0; p < kStages; ++p) DGQ_ARRIVE(p);
 #undef DGQ_STAGE
-#undef DGQ_LDS
-#undef DGQ_LOAD_A
-#undef DGQ_LOAD_B
+#undef DGQ_MFMA
+#undef DGQ_EXPAND
+#undef DGQ_READ_A
+#undef DGQ_ARRIVE
+#undef DGQ_LOAD_STAGE
 
     // ---- epilogue ---------------------------------------------------------------------------
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
@@ -247,10 +287,10 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
     }
     // fp16 path.  The token scales of the tile go through LDS, so that scaling 128 accumulators
     // per lane does not wait on global memory.  The scaled fp16 values are then transposed
-    // through a per-wavefront LDS region (64 tokens x 64 channels at a time) so that every lane
+    // through a per-wavefront LDS region (32 tokens x 64 channels at a time) so that every lane
     // stores 16 contiguous bytes and eight lanes cover a whole 128-byte line of the output.
     float *lds_sx = reinterpret_cast<float *>(&lds_a[0][0]);
-    unsigned short *lds_t = reinterpret_cast<unsigned short *>(&lds_a[0][0] + 1024 + wave * 8192);
+    unsigned short *lds_t = reinterpret_cast<unsigned short *>(&lds_a[0][0] + 1024 + wave * 4096);
     if (tid < BM) lds_sx[tid] = (m0 + tid < a.M) ? a.sx[m0 + tid] : 0.0f;
     float s1n[2];
 #pragma unroll
@@ -258,25 +298,21 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
     __syncthreads();
     const int nw0 = n0 + wave * 64;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+    for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh) {
-            const int mi = half * 2 + mh;
+        for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
-            for (int nj = 0; nj < 2; ++nj)
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * kb + (r & 3);
+                const float sc = lds_sx[mi * 32 + row] * s1n[nj];
+                const _Float16 hv = (_Float16)(sc * (float)acc[mi][nj][r]);
+                lds_t[row * 64 + nj * 32 + li] = __builtin_bit_cast(unsigned short, hv);
+            }
+        // 32 rows x 128 bytes: lane l takes 16-byte chunk l%8 of rows l/8, l/8 + 8, ...
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = mh * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
-                    const float sc = lds_sx[half * 64 + row] * s1n[nj];
-                    const _Float16 hv = (_Float16)(sc * (float)acc[mi][nj][r]);
-                    lds_t[row * 64 + nj * 32 + li] = __builtin_bit_cast(unsigned short, hv);
-                }
-        }
-        // 64 rows x 128 bytes: lane l takes 16-byte chunk l%8 of rows l/8, l/8 + 8, ...
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < 4; ++j) {
             const int row = j * 8 + (lane >> 3);
-            const int m = m0 + half * 64 + row;
+            const int m = m0 + mi * 32 + row;
             const int n = nw0 + (lane & 7) * 8;
             const uint4 v = *reinterpret_cast<const uint4 *>(&lds_t[row * 64 + (lane & 7) * 8]);
             if (m < a.M && n < a.N) *reinterpret_cast<uint4 *>(&a.out[(size_t)m * a.N + n]) = v;
@@ -286,26 +322,38 @@ __global__ __launch_bounds__(kThreads, 2) void linear_tiled_kernel(LinearArgs a,
 
 }  // namespace
 
-hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st)
+int tiled_waves(int M, int N)
+{
+    // The wide tile (128 x 512, eight wavefronts) moves a quarter less operand data per MAC than
+    // the narrow one (128 x 256); it is used whenever it still yields at least one workgroup
+    // per CU.
+    const long long wide = (long long)((M + BM - 1) / BM) * ((N + 511) / 512);
+    return wide >= 256 ? 8 : 4;
+}
+
+template <int G, int NW>
+static hipError_t launch_tiled_nw(const LinearArgs &a, hipStream_t st)
 {
     const int tiles_m = (a.M + BM - 1) / BM;
-    const int tiles_n = (a.N + BN - 1) / BN;
+    const int tiles_n = (a.N + 64 * NW - 1) / (64 * NW);
     const long long T = (long long)tiles_m * tiles_n;
     const long long blocks = ((T + 7) / 8) * 8;
     if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)blocks), block(kThreads);
-    if (a.group == 128) {
-        if (a.acc_out)
-            hipLaunchKernelGGL((linear_tiled_kernel<128, true>), grid, block, 0, st, a, tiles_m, tiles_n);
-        else
-            hipLaunchKernelGGL((linear_tiled_kernel<128, false>), grid, block, 0, st, a, tiles_m, tiles_n);
-    } else {
-        if (a.acc_out)
-            hipLaunchKernelGGL((linear_tiled_kernel<64, true>), grid, block, 0, st, a, tiles_m, tiles_n);
-        else
-            hipLaunchKernelGGL((linear_tiled_kernel<64, false>), grid, block, 0, st, a, tiles_m, tiles_n);
-    }
+    dim3 grid((unsigned)blocks), block(64 * NW);
+    if (a.acc_out)
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, true>), grid, block, 0, st, a, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, false>), grid, block, 0, st, a, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st)
+{
+    // the activation tile is addressed with 32-bit offsets inside the kernel's copies
+    const int nw = tiled_waves(a.M, a.N);
+    if (a.group == 128)
+        return nw == 8 ? launch_tiled_nw<128, 8>(a, st) : launch_tiled_nw<128, 4>(a, st);
+    return nw == 8 ? launch_tiled_nw<64, 8>(a, st) : launch_tiled_nw<64, 4>(a, st);
 }
 
 }  // namespace dgq

@@ -98,7 +98,7 @@ def tiled_asm(tmp_path_factory):
 
 def test_no_register_is_touched_while_an_async_load_into_it_is_in_flight(tiled_asm):
     kernels, problems = check_asm(tiled_asm, "linear_tiled_kernel")
-    assert kernels == 4
+    assert kernels == 8
     assert not problems, "\n".join(problems[:10])
 
 
