@@ -205,24 +205,24 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     } while (0)
 
     const int last = steps - 1;
-    // prologue: stages 0 and 1 in flight; first weight operands expanded
+    // prologue: stages 0 and 1 in flight; operands of the first group prepared
     DGQ_LOAD_STAGE(0, 0);
     DGQ_LOAD_STAGE(1, last < 1 ? last : 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (PPW + kLoadsPerStage));  // weights of stage 0
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStage);  // stage 0 has landed
+    __syncthreads();
     DGQ_ARRIVE(0);
+    DGQ_READ_A(0, 0, 0);
     DGQ_EXPAND(0, 0, 0, 0);
 
-    // Stage s uses register set and LDS buffer s % 3 and refills set/buffer (s + 2) % 3, which
-    // stage s - 1 used; the barrier at the top of stage s guarantees that every wavefront has
-    // finished reading that buffer.  On entry bf[0] already holds group 0 of this stage.
+    // Stage s uses register set and LDS buffer s % 3.  On entry af[0] / bf[0] already hold the
+    // operands of its group 0: they were prepared during the last group of stage s - 1, after
+    // that stage's mid-way barrier.  The barrier before group 3 says two things at once: the
+    // data of stage s + 1 (loaded two stages ahead) have landed for every wavefront, and every
+    // wavefront has finished its LDS reads of stage s (lgkmcnt(0) precedes the barrier), so the
+    // refill issued at the top of stage s + 1 into that buffer cannot overtake a reader.
 #define DGQ_STAGE(P, S)                                                                              \
     do {                                                                                             \
         const int s_ = (S);                                                                          \
-        /* stage s_ has landed once only the loads of stage s_+1 are still outstanding */            \
-        __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStage);                                         \
-        __syncthreads();                                                                             \
-        DGQ_ARRIVE(P);                                                                               \
-        DGQ_READ_A(0, P, 0);                                                                         \
         /* refill: stage s_+2 (past the end: re-read the last stage, unused) */                      \
         DGQ_LOAD_STAGE((P + 2) % kStages, s_ + 2 < steps ? s_ + 2 : last);                           \
         __builtin_amdgcn_sched_barrier(0); /* keep the prefetch at the top of the stage */           \
@@ -238,9 +238,12 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
         DGQ_EXPAND(1, P, s_, 3);                                                                     \
         DGQ_MFMA(0);                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                           \
-        /* weights of stage s_+1: everything but its LDS copies and the loads of stage s_+2 */       \
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (PPW + kLoadsPerStage));                                 \
+        /* stage s_+1 has landed once only the loads of stage s_+2 are outstanding; own LDS */       \
+        /* reads of stage s_ are complete                                                   */       \
+        __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerStage);                                         \
+        __syncthreads();                                                                             \
         DGQ_ARRIVE((P + 1) % kStages);                                                               \
+        DGQ_READ_A(0, (P + 1) % kStages, 0);                                                         \
         DGQ_EXPAND(0, (P + 1) % kStages, s_ + 1, 0);                                                 \
         DGQ_MFMA(1);                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                           \
