@@ -72,15 +72,6 @@ __device__ __forceinline__ uint32_t load_b32_async(const void *base, uint32_t of
     asm volatile("global_load_dword %0, %1, %2" : "=v"(r) : "v"(off), "s"(base) : "memory");
     return r;
 }
-// One MFMA operand (16 consecutive k of one column) from half of a weight cell: the low
-// nibbles (hi = 0, k 0..15 of the cell) or the high nibbles (hi = 1, k 16..31).
-__device__ __forceinline__ v4i expand_half(const v4u &q, const GroupScale &g, int hi)
-{
-    v4i r;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) r[v] = (int)scale_bytes((hi ? (q[v] >> 4) : q[v]) & 0x0F0F0F0Fu, g);
-    return r;
-}
 // After the explicit wait: ties the registers of an asynchronously loaded set to this point, so
 // that nothing that uses them can be scheduled above the wait and the registers stay reserved
 // for the load until then.  EVERY register written by load_*_async must pass through here after
@@ -152,23 +143,28 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     v4u bq[kStages][2][2];    // [stage % 3][column tile][k half]
     uint32_t sw[kStages][2];  // [stage % 3][column tile]: four group scales of this lane's column
 
-    // Loads of one stage, weights first: "weights of stage s have landed" can then be waited for
-    // separately from (and earlier than) "activations of stage s have landed".
-#define DGQ_LOAD_STAGE(P, S)                                                                         \
-    do {                                                                                             \
+    // The loads of one stage are ten (NW = 4) or eight (NW = 8) instructions per lane, always in
+    // this order: weight cells and scales of the two column tiles, then the LDS copies.  Item I of
+    // stage S, into register set / LDS buffer P:
+#define DGQ_LOAD_ITEM(I, P, S)                                                                        \
+    do {                                                                                              \
         const int ls_ = (S);                                                                          \
         const char *qb_ = reinterpret_cast<const char *>(a.qweight) + (size_t)ls_ * 1024;             \
-        const char *sb_ = reinterpret_cast<const char *>(a.scales) +                                 \
-                          (size_t)(((G == 128) ? ls_ : 2 * ls_) >> 2) * 64;                            \
+        const char *sb_ = reinterpret_cast<const char *>(a.scales) +                                  \
+                          (size_t)(((G == 128) ? ls_ : 2 * ls_) >> 2) * 64;                           \
         const char *xb_ = reinterpret_cast<const char *>(a.xq) + (size_t)ls_ * BK;                    \
-        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                             \
-        {                                                                                            \
-            bq[P][nj][0] = load_b128_async(qb_, boff[nj]);                                           \
-            bq[P][nj][1] = load_b128_async_512(qb_, boff[nj]);                                       \
-            sw[P][nj] = load_b32_async(sb_, soff[nj]);                                               \
-        }                                                                                            \
-        _Pragma("unroll") for (int q = 0; q < PPW; ++q)                                              \
-            lds_dma_1k(xb_, goff[q], lds_base + (P) * (BM * BK) + q * 1024);                         \
+        if ((I) == 0) bq[P][0][0] = load_b128_async(qb_, boff[0]);                                    \
+        else if ((I) == 1) bq[P][0][1] = load_b128_async_512(qb_, boff[0]);                           \
+        else if ((I) == 2) sw[P][0] = load_b32_async(sb_, soff[0]);                                   \
+        else if ((I) == 3) bq[P][1][0] = load_b128_async(qb_, boff[1]);                               \
+        else if ((I) == 4) bq[P][1][1] = load_b128_async_512(qb_, boff[1]);                           \
+        else if ((I) == 5) sw[P][1] = load_b32_async(sb_, soff[1]);                                   \
+        else if ((I) < kLoadsPerStage)                                                                \
+            lds_dma_1k(xb_, goff[((I) - 6) % PPW], lds_base + (P) * (BM * BK) + (((I) - 6) % PPW) * 1024); \
+    } while (0)
+#define DGQ_LOAD_STAGE(P, S)                                                                          \
+    do {                                                                                              \
+        _Pragma("unroll") for (int i_ = 0; i_ < kLoadsPerStage; ++i_) DGQ_LOAD_ITEM(i_, P, S);        \
     } while (0)
 #define DGQ_ARRIVE(P) arrive(bq[P][0][0], bq[P][0][1], bq[P][1][0], bq[P][1][1], sw[P][0], sw[P][1])
 
@@ -178,30 +174,49 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     for (int g4 = 0; g4 < 4; ++g4) a_off[g4] = li * BK + (((2 * g4 - (g4 & 1) + 2 * kb) ^ ((li >> 1) & 7)) << 4);
 
     // The 128 k of a stage are consumed in four groups (h, t) = (0,0), (0,1), (1,0), (1,1) of
-    // eight MFMAs each.  While the MFMAs of one group run, the operands of the next group are
-    // prepared: its four activation fragments are read from LDS and its two weight operands
-    // are expanded, both into the other half of a two-deep register buffer.
+    // eight MFMAs each, and a group in four sub-chunks of two MFMAs (one 32-token block, both
+    // column tiles).  A wavefront issues in order, so anything that sits between two MFMAs for
+    // longer than an MFMA runs (32 cycles) drains the matrix pipe.  Every sub-chunk therefore
+    // carries an even share of the other work, all of it for LATER use: one LDS read and one
+    // word (2 x 4 weights) of expansion for the same sub-chunk of the next group, into the
+    // other half of two-deep register buffers, and at most one of the stage's global loads.
     v4i af[2][4];  // [group parity][mi]
     v4i bf[2][2];  // [group parity][nj]
-#define DGQ_READ_A(PAR, P, GRP)                                                                      \
-    do {                                                                                             \
-        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) af[PAR][mi] =                               \
-            *reinterpret_cast<const v4i *>(&lds_a[P][mi * 32 * BK + a_off[GRP]]);                    \
+    GroupScale gsn[2];
+#define DGQ_SCALES(PN, SN, GRPN)                                                                      \
+    do {                                                                                              \
+        const int gi_ = (G == 128) ? (SN) : 2 * (SN) + ((GRPN) >> 1);                                 \
+        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) gsn[nj] =                                    \
+            make_group_scale((sw[PN][nj] >> (8 * (gi_ & 3))) & 0xFFu);                                \
     } while (0)
-#define DGQ_EXPAND(PAR, P, S, GRP)                                                                   \
-    do {                                                                                             \
-        const int gi_ = (G == 128) ? (S) : 2 * (S) + ((GRP) >> 1);                                   \
-        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                             \
-        {                                                                                            \
-            const GroupScale gs_ = make_group_scale((sw[P][nj] >> (8 * (gi_ & 3))) & 0xFFu);         \
-            bf[PAR][nj] = expand_half(bq[P][nj][(GRP) >> 1], gs_, (GRP) & 1);                        \
-        }                                                                                            \
+    // prepares piece C of group GRPN (stage set PN) into parity PARN
+#define DGQ_PREP(PARN, C, PN, GRPN)                                                                   \
+    do {                                                                                              \
+        af[PARN][C] = *reinterpret_cast<const v4i *>(&lds_a[PN][(C) * 32 * BK + a_off[GRPN]]);        \
+        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                              \
+        {                                                                                             \
+            const uint32_t w_ = bq[PN][nj][(GRPN) >> 1][C];                                           \
+            bf[PARN][nj][C] = (int)scale_bytes((((GRPN) & 1) ? (w_ >> 4) : w_) & 0x0F0F0F0Fu, gsn[nj]); \
+        }                                                                                             \
     } while (0)
-#define DGQ_MFMA(PAR)                                                                                \
-    do {                                                                                             \
-        _Pragma("unroll") for (int mi = 0; mi < 4; ++mi)                                             \
-        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) acc[mi][nj] =                               \
-            __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][mi], bf[PAR][nj], acc[mi][nj], 0, 0, 0);   \
+    // sub-chunk C of a group with operand parity PAR: prepare piece C of the next group, two
+    // MFMAs, optionally load item LI of stage LS into set LP
+#define DGQ_SUB(PAR, C, PN, GRPN, LI, LP, LS)                                                         \
+    do {                                                                                              \
+        DGQ_PREP((PAR) ^ 1, C, PN, GRPN);                                                             \
+        acc[C][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][C], bf[PAR][0], acc[C][0], 0, 0, 0); \
+        acc[C][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][C], bf[PAR][1], acc[C][1], 0, 0, 0); \
+        DGQ_LOAD_ITEM(LI, LP, LS);                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+    } while (0)
+    // group with operand parity PAR whose sub-chunks carry load items LI0 .. LI0+3
+#define DGQ_GROUP(PAR, PN, SN, GRPN, LI0, LP, LS)                                                     \
+    do {                                                                                              \
+        DGQ_SCALES(PN, SN, GRPN);                                                                     \
+        DGQ_SUB(PAR, 0, PN, GRPN, (LI0) + 0, LP, LS);                                                 \
+        DGQ_SUB(PAR, 1, PN, GRPN, (LI0) + 1, LP, LS);                                                 \
+        DGQ_SUB(PAR, 2, PN, GRPN, (LI0) + 2, LP, LS);                                                 \
+        DGQ_SUB(PAR, 3, PN, GRPN, (LI0) + 3, LP, LS);                                                 \
     } while (0)
 
     const int last = steps - 1;
@@ -211,42 +226,30 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStage);  // stage 0 has landed
     __syncthreads();
     DGQ_ARRIVE(0);
-    DGQ_READ_A(0, 0, 0);
-    DGQ_EXPAND(0, 0, 0, 0);
+    DGQ_SCALES(0, 0, 0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) DGQ_PREP(0, c, 0, 0);
 
     // Stage s uses register set and LDS buffer s % 3.  On entry af[0] / bf[0] already hold the
     // operands of its group 0: they were prepared during the last group of stage s - 1, after
-    // that stage's mid-way barrier.  The barrier before group 3 says two things at once: the
-    // data of stage s + 1 (loaded two stages ahead) have landed for every wavefront, and every
-    // wavefront has finished its LDS reads of stage s (lgkmcnt(0) precedes the barrier), so the
-    // refill issued at the top of stage s + 1 into that buffer cannot overtake a reader.
-#define DGQ_STAGE(P, S)                                                                              \
-    do {                                                                                             \
-        const int s_ = (S);                                                                          \
-        /* refill: stage s_+2 (past the end: re-read the last stage, unused) */                      \
-        DGQ_LOAD_STAGE((P + 2) % kStages, s_ + 2 < steps ? s_ + 2 : last);                           \
-        __builtin_amdgcn_sched_barrier(0); /* keep the prefetch at the top of the stage */           \
-        DGQ_READ_A(1, P, 1);                                                                         \
-        DGQ_EXPAND(1, P, s_, 1);                                                                     \
-        DGQ_MFMA(0);                                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                           \
-        DGQ_READ_A(0, P, 2);                                                                         \
-        DGQ_EXPAND(0, P, s_, 2);                                                                     \
-        DGQ_MFMA(1);                                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                           \
-        DGQ_READ_A(1, P, 3);                                                                         \
-        DGQ_EXPAND(1, P, s_, 3);                                                                     \
-        DGQ_MFMA(0);                                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                           \
-        /* stage s_+1 has landed once only the loads of stage s_+2 are outstanding; own LDS */       \
-        /* reads of stage s_ are complete                                                   */       \
-        __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerStage);                                         \
-        __syncthreads();                                                                             \
-        DGQ_ARRIVE((P + 1) % kStages);                                                               \
-        DGQ_READ_A(0, (P + 1) % kStages, 0);                                                         \
-        DGQ_EXPAND(0, (P + 1) % kStages, s_ + 1, 0);                                                 \
-        DGQ_MFMA(1);                                                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                           \
+    // that stage's barrier.  Groups 0-2 also issue the loads of stage s + 2, one per sub-chunk.
+    // The barrier before group 3 says two things at once: the data of stage s + 1 (loaded two
+    // stages ahead) have landed for every wavefront, and every wavefront has finished its LDS
+    // reads of stage s (lgkmcnt(0) precedes the barrier), so the copies that stage s + 1 issues
+    // into that buffer cannot overtake a reader.
+#define DGQ_STAGE(P, S)                                                                               \
+    do {                                                                                              \
+        const int s_ = (S);                                                                           \
+        const int s2_ = s_ + 2 < steps ? s_ + 2 : last; /* past the end: re-read, unused */           \
+        DGQ_GROUP(0, P, s_, 1, 0, (P + 2) % kStages, s2_);                                            \
+        DGQ_GROUP(1, P, s_, 2, 4, (P + 2) % kStages, s2_);                                            \
+        DGQ_GROUP(0, P, s_, 3, 8, (P + 2) % kStages, s2_);                                            \
+        /* stage s_+1 has landed once only the loads of stage s_+2 are outstanding; own LDS */        \
+        /* reads of stage s_ are complete                                                   */        \
+        __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerStage);                                          \
+        __syncthreads();                                                                              \
+        DGQ_ARRIVE((P + 1) % kStages);                                                                \
+        DGQ_GROUP(1, (P + 1) % kStages, s_ + 1, 0, 12, (P + 2) % kStages, s2_);                       \
     } while (0)
 
     int s = 0;
@@ -264,11 +267,13 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
 #pragma unroll
     for (int p = 0; p < kStages; ++p) DGQ_ARRIVE(p);
 #undef DGQ_STAGE
-#undef DGQ_MFMA
-#undef DGQ_EXPAND
-#undef DGQ_READ_A
+#undef DGQ_GROUP
+#undef DGQ_SUB
+#undef DGQ_PREP
+#undef DGQ_SCALES
 #undef DGQ_ARRIVE
 #undef DGQ_LOAD_STAGE
+#undef DGQ_LOAD_ITEM
 
     // ---- epilogue ---------------------------------------------------------------------------
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
@@ -327,11 +332,12 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
 
 int tiled_waves(int M, int N)
 {
-    // The wide tile (128 x 512, eight wavefronts) moves a quarter less operand data per MAC than
-    // the narrow one (128 x 256); it is used whenever it still yields at least one workgroup
-    // per CU.
+    // Two workgroups of four wavefronts per CU overlap better than one of eight: the two
+    // wavefronts that share a SIMD then wait at different barriers.  The wide tile (128 x 512,
+    // eight wavefronts) moves a quarter less operand data per MAC, which only pays when its grid
+    // fills every CU in whole rounds (one workgroup per CU and round).
     const long long wide = (long long)((M + BM - 1) / BM) * ((N + 511) / 512);
-    return wide >= 256 ? 8 : 4;
+    return (wide >= 256 && wide % 256 == 0) ? 8 : 4;
 }
 
 template <int G, int NW>

@@ -90,7 +90,8 @@ def test_linear_plan_names(dgq):
     assert dgq.linear_plan(8, 8192, 22016, 64) == "linear_decode_kernel<6, 1, 64, false, true>"
     assert dgq.linear_plan(64, 8192, 8192, 128).startswith("linear_stream_kernel<4, 128, ")
     assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, false>"
-    assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 8, false>"
+    assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, false>"
+    assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, false>"   # 16 x 16 wide tiles
 
 
 def test_force_path_selector(dgq):

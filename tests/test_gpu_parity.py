@@ -197,8 +197,9 @@ def test_decode_workspace_contract(dgq, torch):
 @pytest.mark.parametrize("M,K,N,g", [
     (1, 128, 16, 128), (65, 256, 256, 64), (128, 1024, 256, 128), (129, 512, 272, 128), (200, 1408, 528, 64),
     (300, 640, 1040, 128), (512, 1024, 512, 64), (16, 384, 4096 + 48, 128),
-    (4000, 256, 4096 + 16, 64),      # >= 256 wide tiles: the eight-wavefront 128 x 512 variant, ragged M and N
-    (2100, 384, 8192 - 64, 128),
+    (4000, 256, 4096 + 16, 64),      # 32 x 17 narrow tiles, ragged M and N
+    (4000, 256, 4096 - 48, 64),      # 32 x 8 = 256 wide tiles: the eight-wavefront 128 x 512 variant, ragged M and N
+    (2000, 384, 8192 - 64, 128),     # 16 x 16 wide tiles
 ])
 def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
     _acc_case(dgq, torch, M, K, N, g, seed=M * 5 + N, path=2)
