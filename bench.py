@@ -40,6 +40,7 @@ WORKLOADS = {
 # profiles/; a workload that has not been profiled reports null.
 TRAFFIC_BYTES = {
     ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14147.0 + 175.0) * 1024,
+    ("llama7b_prefill", "linear_tiled_kernel<128, 4, false>"): (2.0 * 60679.2 + 24789.3) * 1024,
 }
 
 
@@ -280,6 +281,39 @@ def main():
     except Exception as e:  # measurement aid only
         log("probe_read failed: %r" % (e,))
 
+    # ---------------- measured matrix-core rate on this workload's operand data ------------
+    mfma_probe = None
+    try:
+        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+        M0 = max(Ms)
+        name0 = list(shapes)[0]
+        K0, N0 = shapes[name0]
+        xq0 = bufs[(M0, name0)][0]                           # X_s8 as the timed steps left it
+        w_s8 = dgq.unpack_weights(packed[name0][0])          # W_s8 of Eq. 2, the B operand's data
+        nrec = 1 << 19                                       # 96-byte records: 64 B of X_s8, 32 B of W_s8
+        xa = xq0.reshape(-1).view(torch.uint8)
+        xa = xa.repeat(-(-nrec * 64 // xa.numel()))[: nrec * 64].view(nrec, 64)
+        wb = w_s8.reshape(-1).view(torch.uint8)[: nrec * 32].view(nrec, 32)
+        real = torch.cat([xa, wb], dim=1).contiguous()
+        mfma_probe = {}
+        for label, buf in (("zero_operands", torch.zeros(1 << 20, dtype=torch.uint8, device=dev)),
+                           ("workload_operands", real)):
+            iters = 20000
+            ops = dgq.probe_mfma(buf, iters, sink)            # warm-up
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                dgq.probe_mfma(buf, iters, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            sec = 1e-3 * e0.elapsed_time(e1) / 3
+            mfma_probe[label] = {"TOPS": ops / sec / 1e12, "ms": sec * 1e3}
+            log("MFMA-only loop, %s: %.1f TOP/s" % (label, ops / sec / 1e12))
+        del real, w_s8, xa, wb
+    except Exception as e:  # measurement aid only
+        log("probe_mfma failed: %r" % (e,))
+
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -329,6 +363,7 @@ def main():
         "cpu_baseline": cpu,
         "a16_fp16_gemm_ms_per_step": a16_ms if breakdown else None,
         "measured_read_bandwidth": probe,
+        "measured_mfma_rate": mfma_probe,
         "breakdown": breakdown,
         "paper_context": "paper reports 3.24x vs A16W4 and 1.12x memory, end to end on one A100-80G (abstract, Section 4.3)",
     }

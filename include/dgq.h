@@ -183,6 +183,19 @@ DGQ_API dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, si
  */
 DGQ_API dgq_status dgq_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, void *stream);
 
+/*
+ * Measurement aid (not part of Eq. 2): every lane of `workgroups` 256-thread workgroups takes
+ * six 16-byte MFMA operands from `operands` (`bytes` >= 96; lane l reads 96 bytes at offset
+ * 96*l, wrapping around) and issues 8*iters v_mfma_i32_32x32x32_i8 on them with no memory
+ * access in the loop: 2*32*32*32 * 8 * iters * 4 * workgroups integer operations in all.  The
+ * matrix-core rate depends on the operand data (the chip lowers its clock with switching
+ * activity), so timing this call on a buffer of real INT8 activations or expanded weights
+ * gives the ceiling that applies to the GEMM of Eq. 2 on such data; a zeroed buffer gives
+ * the data-independent peak.  `sink`: as for dgq_probe_read.
+ */
+DGQ_API dgq_status dgq_probe_mfma(const void *operands, size_t bytes, int iters, uint32_t *sink,
+                          int workgroups, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "probe_mfma", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -53,10 +53,11 @@ def _load() -> ctypes.CDLL:
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_probe_read.argtypes = [vp, sz, vp, i, vp]
+    L.dgq_probe_mfma.argtypes = [vp, sz, i, vp, i, vp]
     L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
-                 "dgq_probe_read", "dgq_linear_plan"):
+                 "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan"):
         getattr(L, name).restype = i
     return L
 
@@ -202,6 +203,13 @@ def probe_read(buf: torch.Tensor, sink: torch.Tensor, workgroups: int = 256, nby
     """dgq_probe_read: stream `nbytes` (default: all) of `buf` once; measurement aid."""
     n = buf.numel() * buf.element_size() if nbytes is None else nbytes
     _check(lib.dgq_probe_read(_ptr(buf), n, _ptr(sink), workgroups, _stream()), "dgq_probe_read")
+
+
+def probe_mfma(operands: torch.Tensor, iters: int, sink: torch.Tensor, workgroups: int = 512) -> int:
+    """dgq_probe_mfma: MFMA-only loop on operands from `operands`; returns the integer operations issued."""
+    n = operands.numel() * operands.element_size()
+    _check(lib.dgq_probe_mfma(_ptr(operands), n, iters, _ptr(sink), workgroups, _stream()), "dgq_probe_mfma")
+    return 2 * 32 * 32 * 32 * 8 * iters * 4 * workgroups
 
 
 def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor = None) -> torch.Tensor:

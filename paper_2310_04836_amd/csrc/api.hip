@@ -211,4 +211,12 @@ dgq_status dgq_probe_read(const void *src, size_t bytes, uint32_t *sink, int wor
     return hip_result(dgq::launch_probe_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream)));
 }
 
+dgq_status dgq_probe_mfma(const void *operands, size_t bytes, int iters, uint32_t *sink, int workgroups, void *stream)
+{
+    if (!operands || !sink) return DGQ_ERR_NULL;
+    if (bytes < 96 || iters < 1 || iters > (1 << 24) || workgroups < 1 || workgroups > 65536) return DGQ_ERR_SHAPE;
+    if (!aligned16(operands) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_probe_mfma(operands, bytes, iters, sink, workgroups, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -103,5 +103,6 @@ int tiled_waves(int M, int N);  // wavefronts per workgroup the tiled kernel use
 hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);
 
 hipError_t launch_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t st);
+hipError_t launch_probe_mfma(const void *operands, size_t bytes, int iters, uint32_t *sink, int workgroups, hipStream_t st);
 
 }  // namespace dgq

@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 14 and len(set(names)) == 14
+    assert len(names) == 15 and len(set(names)) == 15
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -82,6 +82,11 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4(good, good, odd, good, good, good, 1, 16, 128, 128, None, 0, None) == -3
     assert L.dgq_pack_weights(good, good, 128, 16, 128, odd, good, None, None) == -3
     assert L.dgq_pack_weights(good, good, 128, 16, 128, good, good, 0x10002, None) == -3
+    # measurement aids
+    assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
+    assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2
+    assert L.dgq_probe_mfma(good, 4096, 0, good, 1, None) == -2
+    assert L.dgq_probe_mfma(odd, 4096, 1, good, 1, None) == -3
 
 
 def test_linear_plan_names(dgq):
