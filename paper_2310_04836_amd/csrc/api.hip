@@ -30,20 +30,22 @@ dgq_status hip_result(hipError_t e)
 }
 
 // 0 = by M, 1 = weight-streaming kernels, 2 = tiled kernel, 3 = the streaming kernel that
-// re-reads activations every step (normally only used for 16 < M <= 64).
+// re-reads activations every step (never chosen by M).
 enum { kPathAuto = 0, kPathStream = 1, kPathTiled = 2, kPathStreamGeneric = 3 };
 
 int pick_path(int M, int forced)
 {
     if (forced == kPathTiled) return kPathTiled;
     if (forced == kPathStreamGeneric) return kPathStreamGeneric;
-    if (forced == kPathStream || M <= dgq::kStreamMaxM) return M <= dgq::kDecodeMaxM ? kPathStream : kPathStreamGeneric;
-    return kPathTiled;
+    if (forced == kPathStream) return M <= dgq::kDecodeMaxM ? kPathStream : kPathStreamGeneric;
+    return M <= dgq::kDecodeMaxM ? kPathStream : kPathTiled;
 }
 
 size_t workspace_needed(int path, int M, int N, int K)
 {
-    return path == kPathStream ? dgq::decode_workspace_bytes(M, N, K) : 0;
+    if (path == kPathStream) return dgq::decode_workspace_bytes(M, N, K);
+    if (path == kPathTiled) return dgq::tiled_workspace_bytes(M, N, K);
+    return 0;
 }
 
 dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_bytes, void *stream)
@@ -60,7 +62,7 @@ dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_byte
     switch (path) {
     case kPathStream: return hip_result(dgq::launch_linear_decode(a, workspace, st));
     case kPathStreamGeneric: return hip_result(dgq::launch_linear_stream(a, st));
-    default: return hip_result(dgq::launch_linear_tiled(a, st));
+    default: return hip_result(dgq::launch_linear_tiled(a, workspace, st));
     }
 }
 
@@ -107,8 +109,8 @@ dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *by
     if (!bytes) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
-    // Only the decode kernel with a K too long for one workgroup keeps partial sums in
-    // global memory; every other split of K is combined in LDS.
+    // Partial sums go through global memory when several workgroups split K: the decode kernel
+    // with a K too long for one workgroup, and the tiled kernel for M <= 64.
     *bytes = workspace_needed(pick_path(M, g_force_path.load(std::memory_order_relaxed)), M, N, K);
     return DGQ_OK;
 }
@@ -197,8 +199,11 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
         std::snprintf(buf, buf_bytes, "linear_stream_kernel<%d, %d, %d, %d, false>", p.mtiles, group, p.waves, p.depth);
         break;
     }
-    default:
-        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, %d, false>", group, dgq::tiled_waves(M, N));
+    default: {
+        const dgq::TiledPlan p = dgq::tiled_plan(M, N, K);
+        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, %d, %d, %d, %s>", group, p.nw, p.mi, p.st,
+                      p.ksplit > 1 ? "true" : "false");
+    }
     }
     return DGQ_OK;
 }

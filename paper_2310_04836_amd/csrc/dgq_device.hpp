@@ -99,8 +99,17 @@ struct StreamPlan {
 StreamPlan stream_plan(int M, int N, int K);
 hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st);
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
-int tiled_waves(int M, int N);  // wavefronts per workgroup the tiled kernel uses (template NW)
-hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st);
+// Adds ksplit slices [M][N] of INT32 partial sums and runs the epilogue (or stores the sums).
+hipError_t launch_splitk_finalize(const LinearArgs &a, int ksplit, const int32_t *partial, hipStream_t st);
+struct TiledPlan {
+    int nw;      // wavefronts per workgroup, 64 output channels each (template NW)
+    int mi;      // 32-token blocks per tile (template MI)
+    int st;      // stages of operands in flight or in use (template ST)
+    int ksplit;  // workgroups that share one tile, each taking a part of K
+};
+TiledPlan tiled_plan(int M, int N, int K);
+size_t tiled_workspace_bytes(int M, int N, int K);
+hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st);
 
 hipError_t launch_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t st);
 hipError_t launch_probe_mfma(const void *operands, size_t bytes, int iters, uint32_t *sink, int workgroups, hipStream_t st);

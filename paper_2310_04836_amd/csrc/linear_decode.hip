@@ -239,12 +239,7 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
     const bool acc = a.acc_out != nullptr;
     if (ksplit > 1) {
         hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
-        const size_t total = (size_t)a.M * a.N;
-        dim3 fgrid((unsigned)((total + 255) / 256));
-        if (acc)
-            hipLaunchKernelGGL(splitk_finalize_kernel<true>, fgrid, dim3(256), 0, st, a, ksplit, partial);
-        else
-            hipLaunchKernelGGL(splitk_finalize_kernel<false>, fgrid, dim3(256), 0, st, a, ksplit, partial);
+        return launch_splitk_finalize(a, ksplit, partial, st);
     } else if (acc) {
         hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, 1, partial);
     } else {
@@ -268,6 +263,17 @@ hipError_t launch_g(const LinearArgs &a, const DecodePlan &p, void *workspace, h
 }
 
 }  // namespace
+
+hipError_t launch_splitk_finalize(const LinearArgs &a, int ksplit, const int32_t *partial, hipStream_t st)
+{
+    const size_t total = (size_t)a.M * a.N;
+    dim3 fgrid((unsigned)((total + 255) / 256));
+    if (a.acc_out)
+        hipLaunchKernelGGL(splitk_finalize_kernel<true>, fgrid, dim3(256), 0, st, a, ksplit, partial);
+    else
+        hipLaunchKernelGGL(splitk_finalize_kernel<false>, fgrid, dim3(256), 0, st, a, ksplit, partial);
+    return hipGetLastError();
+}
 
 DecodePlan decode_plan(int K)
 {

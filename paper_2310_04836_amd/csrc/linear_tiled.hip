@@ -23,9 +23,11 @@
 namespace dgq {
 namespace {
 
-constexpr int BM = 128;
 constexpr int BK = 128;
-constexpr int kStages = 3;
+
+// s_waitcnt immediate: at most n vector loads outstanding; LDS/scalar counter either ignored or
+// waited down to zero.  (vmcnt is split over bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8.)
+constexpr int wait_vm(int n, bool lgkm0) { return (n & 15) | ((n >> 4) << 14) | 0x0070 | (lgkm0 ? 0 : 0x0F00); }
 
 typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -81,20 +83,30 @@ __device__ __forceinline__ void arrive(v4u &a, v4u &b, v4u &c, v4u &d, uint32_t 
     asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e), "+v"(f));
 }
 
-// NW wavefronts per workgroup, each owning 64 output channels of the 128 x (64*NW) tile.
-template <int G, int NW, bool ACC>
-__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n)
+// NW wavefronts per workgroup, each owning 64 output channels of the (32*MI) x (64*NW) tile;
+// ST stages of operands in flight or in use.  ksplit workgroups share one tile, each walking its
+// own part of K; then (and in the test hook) the raw INT32 sums go to a.acc_out, slice kpart.
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
 {
+    constexpr int kStages = ST;
+    constexpr int BM = 32 * MI;
     constexpr int BN = 64 * NW;
-    constexpr int PPW = 16 / NW;  // 1 KiB pieces of the activation tile each wavefront copies per stage
+    constexpr int PPW = BM / (8 * NW);  // 1 KiB pieces of the activation tile each wavefront copies per stage
     constexpr int kLoadsPerStage = 6 + PPW;
+    static_assert(MI == 2 || MI == 4, "two or four 32-token blocks");
+    static_assert(ST >= 3 && ST <= 6 && PPW >= 1 && kLoadsPerStage <= 12, "loads are spread over 12 sub-chunks");
+    static_assert((ST - 1) * kLoadsPerStage <= 63, "vmcnt counts to 63");
+    static_assert(1024 + NW * 4096 <= ST * BM * BK, "the epilogue reuses the ring");
 
     __shared__ __attribute__((aligned(1024))) int8_t lds_a[kStages][BM * BK];
 
-    const int T = tiles_m * tiles_n;
+    const int T = tiles_m * tiles_n * ksplit;
     const int per_xcd = (T + 7) >> 3;
-    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= T) return;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= T) return;
+    const int tile = work / ksplit;
+    const int kpart = work - tile * ksplit;
     const int m0 = (tile % tiles_m) * BM;
     const int n0 = (tile / tiles_m) * BN;
 
@@ -132,18 +144,22 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     // LDS byte address of this wavefront's first piece in stage buffer 0
     const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[0][0] + wave * PPW * 1024;
 
-    v16i acc[4][2];
+    // this workgroup's stages of K
+    const int p0 = (steps * kpart) / ksplit;
+    const int p1 = (steps * (kpart + 1)) / ksplit;
+
+    v16i acc[MI][2];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0;
 
-    v4u bq[kStages][2][2];    // [stage % 3][column tile][k half]
-    uint32_t sw[kStages][2];  // [stage % 3][column tile]: four group scales of this lane's column
+    v4u bq[kStages][2][2];    // [stage % ST][column tile][k half]
+    uint32_t sw[kStages][2];  // [stage % ST][column tile]: four group scales of this lane's column
 
-    // The loads of one stage are ten (NW = 4) or eight (NW = 8) instructions per lane, always in
+    // The loads of one stage are 6 + PPW instructions per lane, always in
     // this order: weight cells and scales of the two column tiles, then the LDS copies.  Item I of
     // stage S, into register set / LDS buffer P:
 #define DGQ_LOAD_ITEM(I, P, S)                                                                        \
@@ -174,13 +190,13 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     for (int g4 = 0; g4 < 4; ++g4) a_off[g4] = li * BK + (((2 * g4 - (g4 & 1) + 2 * kb) ^ ((li >> 1) & 7)) << 4);
 
     // The 128 k of a stage are consumed in four groups (h, t) = (0,0), (0,1), (1,0), (1,1) of
-    // eight MFMAs each, and a group in four sub-chunks of two MFMAs (one 32-token block, both
-    // column tiles).  A wavefront issues in order, so anything that sits between two MFMAs for
+    // 2*MI MFMAs each, and a group in four sub-chunks: two MFMAs (one 32-token block, both
+    // column tiles) for MI = 4, one MFMA for MI = 2.  A wavefront issues in order, so anything that sits between two MFMAs for
     // longer than an MFMA runs (32 cycles) drains the matrix pipe.  Every sub-chunk therefore
     // carries an even share of the other work, all of it for LATER use: one LDS read and one
     // word (2 x 4 weights) of expansion for the same sub-chunk of the next group, into the
     // other half of two-deep register buffers, and at most one of the stage's global loads.
-    v4i af[2][4];  // [group parity][mi]
+    v4i af[2][MI];  // [group parity][mi]
     v4i bf[2][2];  // [group parity][nj]
     GroupScale gsn[2];
 #define DGQ_SCALES(PN, SN, GRPN)                                                                      \
@@ -192,20 +208,28 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     // prepares piece C of group GRPN (stage set PN) into parity PARN
 #define DGQ_PREP(PARN, C, PN, GRPN)                                                                   \
     do {                                                                                              \
-        af[PARN][C] = *reinterpret_cast<const v4i *>(&lds_a[PN][(C) * 32 * BK + a_off[GRPN]]);        \
+        if ((C) < MI)                                                                                 \
+            af[PARN][(C) % MI] = *reinterpret_cast<const v4i *>(&lds_a[PN][((C) % MI) * 32 * BK + a_off[GRPN]]); \
         _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                              \
         {                                                                                             \
             const uint32_t w_ = bq[PN][nj][(GRPN) >> 1][C];                                           \
             bf[PARN][nj][C] = (int)scale_bytes((((GRPN) & 1) ? (w_ >> 4) : w_) & 0x0F0F0F0Fu, gsn[nj]); \
         }                                                                                             \
     } while (0)
-    // sub-chunk C of a group with operand parity PAR: prepare piece C of the next group, two
+    // sub-chunk C of a group with operand parity PAR: prepare piece C of the next group, the
     // MFMAs, optionally load item LI of stage LS into set LP
 #define DGQ_SUB(PAR, C, PN, GRPN, LI, LP, LS)                                                         \
     do {                                                                                              \
         DGQ_PREP((PAR) ^ 1, C, PN, GRPN);                                                             \
-        acc[C][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][C], bf[PAR][0], acc[C][0], 0, 0, 0); \
-        acc[C][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][C], bf[PAR][1], acc[C][1], 0, 0, 0); \
+        if (MI == 4) {                                                                                \
+            acc[(C) % MI][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][(C) % MI], bf[PAR][0],   \
+                                                                     acc[(C) % MI][0], 0, 0, 0);     \
+            acc[(C) % MI][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[PAR][(C) % MI], bf[PAR][1],   \
+                                                                     acc[(C) % MI][1], 0, 0, 0);     \
+        } else {                                                                                      \
+            acc[((C) >> 1) % MI][(C) & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                    \
+                af[PAR][((C) >> 1) % MI], bf[PAR][(C) & 1], acc[((C) >> 1) % MI][(C) & 1], 0, 0, 0);  \
+        }                                                                                             \
         DGQ_LOAD_ITEM(LI, LP, LS);                                                                    \
         __builtin_amdgcn_sched_barrier(0);                                                            \
     } while (0)
@@ -219,51 +243,72 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
         DGQ_SUB(PAR, 3, PN, GRPN, (LI0) + 3, LP, LS);                                                 \
     } while (0)
 
-    const int last = steps - 1;
-    // prologue: stages 0 and 1 in flight; operands of the first group prepared
-    DGQ_LOAD_STAGE(0, 0);
-    DGQ_LOAD_STAGE(1, last < 1 ? last : 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoadsPerStage);  // stage 0 has landed
+    const int last = p1 - 1;
+    // prologue: the first ST - 1 stages in flight (stages past the end re-read the last one,
+    // unused); operands of the first group prepared
+#pragma unroll
+    for (int p = 0; p < kStages - 1; ++p) DGQ_LOAD_STAGE(p, p0 + p < last ? p0 + p : last);
+    __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 2) * kLoadsPerStage, false));  // the first stage has landed
     __syncthreads();
     DGQ_ARRIVE(0);
-    DGQ_SCALES(0, 0, 0);
+    DGQ_SCALES(0, p0, 0);
 #pragma unroll
     for (int c = 0; c < 4; ++c) DGQ_PREP(0, c, 0, 0);
 
-    // Stage s uses register set and LDS buffer s % 3.  On entry af[0] / bf[0] already hold the
-    // operands of its group 0: they were prepared during the last group of stage s - 1, after
-    // that stage's barrier.  Groups 0-2 also issue the loads of stage s + 2, one per sub-chunk.
-    // The barrier before group 3 says two things at once: the data of stage s + 1 (loaded two
-    // stages ahead) have landed for every wavefront, and every wavefront has finished its LDS
-    // reads of stage s (lgkmcnt(0) precedes the barrier), so the copies that stage s + 1 issues
-    // into that buffer cannot overtake a reader.
+    // The i-th stage of this workgroup uses register set and LDS buffer i % ST.  On entry
+    // af[0] / bf[0] already hold the operands of its group 0: they were prepared during the last
+    // group of the stage before, after that stage's barrier.  Groups 0-2 also issue the loads of
+    // the stage ST - 1 ahead, one per sub-chunk, into the buffer of the stage before this one.
+    // The barrier before group 3 says two things at once: the data of the next stage have landed
+    // for every wavefront (only the loads of the ST - 2 stages after it are still outstanding),
+    // and every wavefront has finished its LDS reads of this stage (lgkmcnt(0) precedes the
+    // barrier), so the copies that the next stage issues into this buffer cannot overtake a reader.
 #define DGQ_STAGE(P, S)                                                                               \
     do {                                                                                              \
         const int s_ = (S);                                                                           \
-        const int s2_ = s_ + 2 < steps ? s_ + 2 : last; /* past the end: re-read, unused */           \
-        DGQ_GROUP(0, P, s_, 1, 0, (P + 2) % kStages, s2_);                                            \
-        DGQ_GROUP(1, P, s_, 2, 4, (P + 2) % kStages, s2_);                                            \
-        DGQ_GROUP(0, P, s_, 3, 8, (P + 2) % kStages, s2_);                                            \
-        /* stage s_+1 has landed once only the loads of stage s_+2 are outstanding; own LDS */        \
-        /* reads of stage s_ are complete                                                   */        \
-        __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerStage);                                          \
+        const int s2_ = s_ + (kStages - 1) < p1 ? s_ + (kStages - 1) : last; /* past the end: unused */ \
+        DGQ_GROUP(0, P, s_, 1, 0, (P + kStages - 1) % kStages, s2_);                                  \
+        DGQ_GROUP(1, P, s_, 2, 4, (P + kStages - 1) % kStages, s2_);                                  \
+        DGQ_GROUP(0, P, s_, 3, 8, (P + kStages - 1) % kStages, s2_);                                  \
+        __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 2) * kLoadsPerStage, true));                    \
         __syncthreads();                                                                              \
         DGQ_ARRIVE((P + 1) % kStages);                                                                \
-        DGQ_GROUP(1, (P + 1) % kStages, s_ + 1, 0, 12, (P + 2) % kStages, s2_);                       \
+        DGQ_GROUP(1, (P + 1) % kStages, s_ + 1, 0, 12, (P + kStages - 1) % kStages, s2_);             \
     } while (0)
 
-    int s = 0;
-    for (; s + 3 <= steps; s += 3) {
+    int s = p0;
+    for (; s + kStages <= p1; s += kStages) {
         DGQ_STAGE(0, s);
         DGQ_STAGE(1, s + 1);
         DGQ_STAGE(2, s + 2);
+        if constexpr (kStages > 3) DGQ_STAGE(3 % kStages, s + 3);
+        if constexpr (kStages > 4) DGQ_STAGE(4 % kStages, s + 4);
+        if constexpr (kStages > 5) DGQ_STAGE(5 % kStages, s + 5);
     }
-    if (s < steps) DGQ_STAGE(0, s);
-    if (s + 1 < steps) DGQ_STAGE(1, s + 1);
-    // The re-reads issued by the last two stages are unused but still in flight.  Their
+    // the remaining 0 .. ST - 1 stages, nested so that no path runs stage i + 1 without stage i
+    if (s < p1) {
+        DGQ_STAGE(0, s);
+        if (s + 1 < p1) {
+            DGQ_STAGE(1, s + 1);
+            if constexpr (kStages > 3) {
+                if (s + 2 < p1) {
+                    DGQ_STAGE(2, s + 2);
+                    if constexpr (kStages > 4) {
+                        if (s + 3 < p1) {
+                            DGQ_STAGE(3 % kStages, s + 3);
+                            if constexpr (kStages > 5) {
+                                if (s + 4 < p1) DGQ_STAGE(4 % kStages, s + 4);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    // The re-reads issued by the last stages are unused but still in flight.  Their
     // destination registers must stay reserved until they have landed: a register the compiler
     // considers dead could be handed to another value and then be overwritten by the late load.
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_waitcnt(wait_vm(0, false));
 #pragma unroll
     for (int p = 0; p < kStages; ++p) DGQ_ARRIVE(p);
 #undef DGQ_STAGE
@@ -279,16 +324,17 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
     __syncthreads();  // every wavefront is done with the LDS ring
     if (ACC) {
+        int32_t *dst = a.acc_out + (size_t)kpart * a.M * a.N;
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj) {
             const int n = ncol[nj];
             if (n >= a.N) continue;
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = m0 + mi * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
-                    if (m < a.M) a.acc_out[(size_t)m * a.N + n] = acc[mi][nj][r];
+                    if (m < a.M) dst[(size_t)m * a.N + n] = acc[mi][nj][r];
                 }
         }
         return;
@@ -306,7 +352,7 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     __syncthreads();
     const int nw0 = n0 + wave * 64;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
@@ -330,39 +376,85 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
 
 }  // namespace
 
-int tiled_waves(int M, int N)
+TiledPlan tiled_plan(int M, int N, int K)
 {
+    constexpr int kCus = 256;
+    const int steps = K / 128;
+    TiledPlan p;
+    p.nw = 4, p.mi = 4, p.st = 3, p.ksplit = 1;
+    const long long tiles_n = (N + 255) / 256;
+    if (M <= 64) {
+        // One 64-token tile per 256 columns: the weights are read once and the layer is bound by
+        // that stream.  Six stages keep 5 x 16 KiB of it in flight per workgroup, and K is split
+        // until there are about two workgroups per CU (at least 8 stages per part, at most 8
+        // parts: every part writes and re-reads M x N INT32 partial sums).
+        p.mi = 2, p.st = 6;
+        long long ks = (2 * kCus) / tiles_n;
+        if (ks > 8) ks = 8;
+        if (ks > steps / 8) ks = steps / 8;
+        if (ks < 1) ks = 1;
+        p.ksplit = (int)ks;
+        return p;
+    }
+    const long long tiles_128 = (long long)((M + 127) / 128) * tiles_n;
+    if (tiles_128 < kCus) {
+        // fewer 128-token tiles than CUs: 64-token tiles put twice as many SIMDs to work
+        p.mi = 2;
+        return p;
+    }
     // Two workgroups of four wavefronts per CU overlap better than one of eight: the two
     // wavefronts that share a SIMD then wait at different barriers.  The wide tile (128 x 512,
     // eight wavefronts) moves a quarter less operand data per MAC, which only pays when its grid
     // fills every CU in whole rounds (one workgroup per CU and round).
-    const long long wide = (long long)((M + BM - 1) / BM) * ((N + 511) / 512);
-    return (wide >= 256 && wide % 256 == 0) ? 8 : 4;
+    const long long wide = (long long)((M + 127) / 128) * ((N + 511) / 512);
+    if (wide >= kCus && wide % kCus == 0) p.nw = 8;
+    return p;
 }
 
-template <int G, int NW>
-static hipError_t launch_tiled_nw(const LinearArgs &a, hipStream_t st)
+size_t tiled_workspace_bytes(int M, int N, int K)
 {
-    const int tiles_m = (a.M + BM - 1) / BM;
+    const int ks = tiled_plan(M, N, K).ksplit;
+    return ks > 1 ? (size_t)ks * M * N * sizeof(int32_t) : 0;
+}
+
+template <int G, int NW, int MI, int ST>
+static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
+{
+    const int tiles_m = (a.M + 32 * MI - 1) / (32 * MI);
     const int tiles_n = (a.N + 64 * NW - 1) / (64 * NW);
-    const long long T = (long long)tiles_m * tiles_n;
+    const long long T = (long long)tiles_m * tiles_n * ksplit;
     const long long blocks = ((T + 7) / 8) * 8;
     if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(64 * NW);
+    if (ksplit > 1) {
+        // raw INT32 sums of every part into its slice of the workspace, then one pass that adds
+        // the slices and applies the scales
+        LinearArgs part = a;
+        part.acc_out = static_cast<int32_t *>(workspace);
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
+        return launch_splitk_finalize(a, ksplit, part.acc_out, st);
+    }
     if (a.acc_out)
-        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, true>), grid, block, 0, st, a, tiles_m, tiles_n);
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
     else
-        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, false>), grid, block, 0, st, a, tiles_m, tiles_n);
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
     return hipGetLastError();
 }
 
-hipError_t launch_linear_tiled(const LinearArgs &a, hipStream_t st)
+template <int G>
+static hipError_t launch_tiled_g(const LinearArgs &a, const TiledPlan &p, void *workspace, hipStream_t st)
+{
+    if (p.mi == 2 && p.st == 6) return launch_tiled_cfg<G, 4, 2, 6>(a, p.ksplit, workspace, st);
+    if (p.mi == 2) return launch_tiled_cfg<G, 4, 2, 3>(a, p.ksplit, workspace, st);
+    if (p.nw == 8) return launch_tiled_cfg<G, 8, 4, 3>(a, p.ksplit, workspace, st);
+    return launch_tiled_cfg<G, 4, 4, 3>(a, p.ksplit, workspace, st);
+}
+
+hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st)
 {
     // the activation tile is addressed with 32-bit offsets inside the kernel's copies
-    const int nw = tiled_waves(a.M, a.N);
-    if (a.group == 128)
-        return nw == 8 ? launch_tiled_nw<128, 8>(a, st) : launch_tiled_nw<128, 4>(a, st);
-    return nw == 8 ? launch_tiled_nw<64, 8>(a, st) : launch_tiled_nw<64, 4>(a, st);
+    const TiledPlan p = tiled_plan(a.M, a.N, a.K);
+    return a.group == 128 ? launch_tiled_g<128>(a, p, workspace, st) : launch_tiled_g<64>(a, p, workspace, st);
 }
 
 }  // namespace dgq

@@ -93,10 +93,21 @@ def test_linear_plan_names(dgq):
     assert dgq.linear_plan(16, 22016, 4096, 128) == "linear_decode_kernel<2, 2, 128, false, false>"
     assert dgq.linear_plan(1, 4096, 11008, 128) == "linear_decode_kernel<6, 1, 128, false, false>"
     assert dgq.linear_plan(8, 8192, 22016, 64) == "linear_decode_kernel<6, 1, 64, false, true>"
-    assert dgq.linear_plan(64, 8192, 8192, 128).startswith("linear_stream_kernel<4, 128, ")
-    assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, false>"
-    assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, false>"
-    assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, false>"   # 16 x 16 wide tiles
+    # 16 < M <= 64: 64-token tile, six stages, K split over workgroups (partial sums -> "true")
+    assert dgq.linear_plan(64, 8192, 8192, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
+    assert dgq.linear_workspace_bytes(64, 8192, 8192, 128) == 8 * 64 * 8192 * 4
+    assert dgq.linear_plan(17, 44032, 256, 64) == "linear_tiled_kernel<64, 4, 2, 6, false>"
+    assert dgq.linear_workspace_bytes(17, 44032, 256, 64) == 0
+    # fewer 128-token tiles than CUs: 64-token tiles
+    assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"
+    assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"
+    assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
+    assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 16 x 16 wide tiles
+    old = dgq.force_path(3)
+    try:
+        assert dgq.linear_plan(64, 8192, 8192, 128).startswith("linear_stream_kernel<4, 128, ")
+    finally:
+        dgq.force_path(old)
 
 
 def test_force_path_selector(dgq):

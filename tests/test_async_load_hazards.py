@@ -28,62 +28,72 @@ def _regs(tok):
     return {int(m.group(1))} if m else set()
 
 
-def _scan(lines, pending, problems, name):
-    """Walks `lines` in order; `pending` is the issue-ordered list of in-flight destination sets."""
-    for t in lines:
-        m = re.match(r"(\S+)\s*(.*)", t)
-        op, args = m.group(1), m.group(2)
-        toks = [a.strip() for a in args.split(",")]
-        if op == "s_waitcnt":
-            mm = re.search(r"vmcnt\((\d+)\)", args)
-            if mm:
-                n = int(mm.group(1))
-                del pending[: max(0, len(pending) - n)]   # all but the n youngest have landed
-            continue
-        touched = set()
-        for a in toks:
-            touched |= _regs(a)
-        if op.startswith("global_load_lds"):
-            pending.append(set())
-            continue
-        if op.startswith("global_load") or op.startswith("buffer_load"):
-            dst = _regs(toks[0])
-            for rs in pending:
-                if rs & touched:
-                    problems.append("%s: %s" % (name, t))
-            pending.append(dst)
-            continue
-        if op.startswith("global_store") or op.startswith("global_atomic"):
-            pending.append(set())            # stores also occupy a vmcnt slot on this target
-        for rs in pending:
-            if rs & touched:
-                problems.append("%s: %s" % (name, t))
-                break
+def _step(t, pending, problems, name):
+    """Applies instruction `t` to `pending`, the issue-ordered list of in-flight destination sets."""
+    m = re.match(r"(\S+)\s*(.*)", t)
+    op, args = m.group(1), m.group(2)
+    toks = [a.strip() for a in args.split(",")]
+    if op == "s_waitcnt":
+        mm = re.search(r"vmcnt\((\d+)\)", args)
+        if mm:
+            n = int(mm.group(1))
+            del pending[: max(0, len(pending) - n)]   # all but the n youngest have landed
+        return
+    touched = set()
+    for a in toks:
+        touched |= _regs(a)
+    hit = any(rs & touched for rs in pending)
+    if op.startswith("global_load_lds"):
+        pending.append(frozenset())
+    elif op.startswith("global_load") or op.startswith("buffer_load"):
+        pending.append(frozenset(_regs(toks[0])))
+    elif op.startswith("global_store") or op.startswith("global_atomic"):
+        pending.append(frozenset())            # stores also occupy a vmcnt slot on this target
+    if hit:
+        problems.add("%s: %s" % (name, t))
 
 
 def check_asm(text, kernel_substr):
-    problems, kernels = [], 0
-    for km in re.finditer(r"^(_Z\w*%s\w*):[^\n]*\n(.*?)s_endpgm" % kernel_substr, text, re.S | re.M):
+    """Follows every path of the control flow graph of each matching kernel (state = the pending
+    loads; a (block, state) pair is expanded once) and returns (kernels, sorted problems)."""
+    problems, kernels = set(), 0
+    for km in re.finditer(r"^(_Z\w*%s\w*):[^\n]*\n(.*?)\.end_amdhsa_kernel" % kernel_substr, text, re.S | re.M):
         kernels += 1
         name = km.group(1)[-48:]
         body = [l.strip() for l in km.group(2).split("\n")]
         body = [l for l in body if l and not l.startswith(";")]
-        labels = {l[:-1].split(":")[0]: i for i, l in enumerate(body) if l.startswith(".LBB")}
-        insts = [(i, l) for i, l in enumerate(body)
-                 if not l.startswith(".") and not l.startswith("s_branch")]
-        pending = []
-        _scan([l for _, l in insts if not l.startswith("s_cbranch")], pending, problems, name)
-        # loops: replay every backward-branch region once more with the state at its end
-        for i, l in insts:
-            if l.startswith("s_cbranch"):
-                tgt = l.split()[-1]
-                j = labels.get(tgt)
-                if j is not None and j < i:
-                    region = [x for k, x in insts if j <= k < i and not x.startswith("s_cbranch")]
-                    carried = []
-                    _scan(region, carried, [], name)          # state at the end of one trip
-                    _scan(region, carried, problems, name)    # second trip sees the carried loads
-    return kernels, problems
+        labels = {l.split(":")[0]: i for i, l in enumerate(body) if re.match(r"\.LBB\w+:", l)}
+        is_label = [bool(re.match(r"\.LBB\w+:", l)) for l in body]
+        work, seen = [(0, ())], set()
+        while work:
+            i, state = work.pop()
+            if (i, state) in seen:
+                continue
+            seen.add((i, state))
+            assert len(seen) < 20000, "state explosion in %s" % name
+            pending = list(state)
+            first = True
+            while i < len(body):
+                l = body[i]
+                if is_label[i] and not first:
+                    work.append((i, tuple(pending)))   # a block start: expanded once per state
+                    break
+                first = False
+                if l.startswith(".") or l.endswith(":"):
+                    i += 1
+                    continue
+                if l.startswith("s_endpgm"):
+                    break
+                if l.startswith("s_branch"):
+                    work.append((labels[l.split()[-1]], tuple(pending)))
+                    break
+                if l.startswith("s_cbranch"):
+                    work.append((labels[l.split()[-1]], tuple(pending)))
+                    work.append((i + 1, tuple(pending)))
+                    break
+                _step(l, pending, problems, name)
+                i += 1
+    return kernels, sorted(problems)
 
 
 @pytest.fixture(scope="module")
@@ -98,7 +108,7 @@ def tiled_asm(tmp_path_factory):
 
 def test_no_register_is_touched_while_an_async_load_into_it_is_in_flight(tiled_asm):
     kernels, problems = check_asm(tiled_asm, "linear_tiled_kernel")
-    assert kernels == 8
+    assert kernels == 16
     assert not problems, "\n".join(problems[:10])
 
 
@@ -112,6 +122,38 @@ def test_checker_sees_a_planted_hazard():
 	s_waitcnt vmcnt(0)
 	v_add_u32_e32 v3, v9, v2
 	s_endpgm
+	.end_amdhsa_kernel
 """
     kernels, problems = check_asm(asm, "linear_tiled_kernel")
     assert kernels == 1 and len(problems) == 1 and "v8" in problems[0]
+
+
+def test_checker_follows_branches_and_loops():
+    # the hazard exists only on the path that skips the wait, and only in the second loop trip
+    asm = """_Zfake_linear_tiled_kernel_y:   ; @y
+	s_cbranch_scc1 .LBB0_2
+	global_load_dwordx4 v[4:7], v[0:1], off
+	s_branch .LBB0_3
+.LBB0_2:
+	v_mov_b32_e32 v4, 0
+.LBB0_3:
+	v_add_u32_e32 v20, v21, v22
+	s_cbranch_scc1 .LBB0_5
+	s_waitcnt vmcnt(0)
+.LBB0_5:
+	v_add_u32_e32 v2, v4, v2
+.LBB0_6:
+	v_add_u32_e32 v3, v12, v2
+	global_load_dwordx4 v[12:15], v[0:1], off
+	s_waitcnt vmcnt(1)
+	s_cbranch_scc1 .LBB0_6
+	s_waitcnt vmcnt(0)
+	s_endpgm
+.LBB0_9:
+	s_endpgm
+	.end_amdhsa_kernel
+"""
+    kernels, problems = check_asm(asm, "linear_tiled_kernel")
+    assert kernels == 1
+    # also flagged: the second trip's load into v[12:15] while the first trip's may be outstanding
+    assert len(problems) == 3 and any("v4, v2" in p for p in problems) and any("v12, v2" in p for p in problems)

@@ -147,7 +147,12 @@ def test_onehot_probe_stream_path(dgq, torch, M, g):
 @pytest.mark.parametrize("g", [128, 64])
 @pytest.mark.parametrize("M", [1, 130])
 def test_onehot_probe_tiled_path(dgq, torch, M, g):
-    _acc_case(dgq, torch, M, 512, 320, g, seed=M, path=2, onehot=True)
+    _acc_case(dgq, torch, M, 512, 320, g, seed=M, path=2, onehot=True)     # 64-token tiles
+
+
+@pytest.mark.parametrize("g", [128, 64])
+def test_onehot_probe_tiled_path_128_token_tiles(dgq, torch, g):
+    _acc_case(dgq, torch, 2048, 256, 4096, g, seed=9, path=2, onehot=True)  # 16 x 16 tiles of 128 x 256
 
 
 @pytest.mark.parametrize("M,K,N,g", [
@@ -203,6 +208,38 @@ def test_decode_workspace_contract(dgq, torch):
 ])
 def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
     _acc_case(dgq, torch, M, K, N, g, seed=M * 5 + N, path=2)
+
+
+# 16 < M <= 64 takes the tiled kernel with a 64-token tile, six stages and K split over several
+# workgroups whose INT32 partial sums meet in the workspace.
+@pytest.mark.parametrize("M,K,N,g", [
+    (17, 128, 16, 128),          # one stage, no split
+    (64, 4096, 512, 128),        # 2 tiles x 4 parts of 8 stages
+    (40, 2048, 272, 64),         # 2 parts, ragged M and N
+    (33, 8192, 1040, 128),       # 8 parts
+    (64, 11008, 528, 64),        # 86 stages in 8 parts of 10 or 11
+    (48, 1408, 4096 + 64, 128),  # 11 stages, one part: tail of every length mod 6 is in this list
+    (64, 896, 64, 64), (64, 1024, 64, 128), (20, 1152, 64, 128), (20, 1280, 64, 64), (20, 1536, 64, 128),
+])
+def test_acc_bit_exact_mid_m(dgq, torch, M, K, N, g):
+    _acc_case(dgq, torch, M, K, N, g, seed=M + K + N, path=0)
+
+
+def test_tiled_split_workspace_contract(dgq, torch):
+    M, K, N, g = 64, 4096, 512, 128
+    need = dgq.linear_workspace_bytes(M, N, K, g)
+    assert need == 4 * M * N * 4
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 2)
+    xq, sx = workloads.integer_activations(M, K, 2)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dgq.DGQError) as e:
+        dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=small)
+    assert e.value.status == -5
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")   # contents undefined on entry
+    out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=ws))
+    oout, _ = oracle.linear_a8w4(xq, sx, w4, s2, s1, g)
+    assert_fp16_close(out, oout)
 
 
 def test_both_paths_and_split_factors_agree(dgq, torch):
