@@ -72,8 +72,9 @@ DGQ_API dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_byt
 
 /*
  * Scratch needed by dgq_linear_a8w4 / dgq_linear_a8w4_acc for this problem (host
- * function).  May be 0, in which case `workspace` may be NULL.  Non-zero only for small M
- * with very long K, where several workgroups split K and exchange INT32 partial sums.
+ * function).  May be 0, in which case `workspace` may be NULL.  Non-zero where several
+ * workgroups split K and exchange INT32 partial sums: M <= 16 with very long K, and
+ * 16 < M <= 64 (at most 8 * M * N * 4 bytes).
  */
 DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
 
@@ -138,8 +139,9 @@ DGQ_API dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, fl
  *   out               out [M][N] fp16 (raw bits)
  *   workspace         scratch of at least dgq_linear_workspace_bytes(); contents
  *                     undefined before and after
- * Small M takes a weight-streaming split-K path, large M a tiled MFMA path; both give
- * the same INT32 sums.
+ * M <= 16 takes a weight-streaming split-K kernel, larger M a tiled MFMA kernel (64-token
+ * tiles with K split over workgroups up to M = 64 and for shapes with few tiles, 128-token
+ * tiles otherwise); all give the same INT32 sums.
  */
 DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight,
                            const void *scales, const float *s1, uint16_t *out,
@@ -158,7 +160,7 @@ DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, co
  * Selects the GEMM path for later dgq_linear_a8w4* and dgq_linear_workspace_bytes calls of
  * this process (host, for tests and measurements): 0 = choose by M (default), 1 = the
  * weight-streaming kernels, 2 = the tiled kernel, 3 = the weight-streaming kernel that
- * re-reads activations every step (by default used for 16 < M <= 64 only).  Returns the
+ * re-reads activations every step (never chosen by M; kept as an independent check).  Returns the
  * previous value; an unknown value changes nothing and returns -1.  The weight-streaming
  * kernels accept M <= 64 only; forcing them for a larger M makes the linear calls return
  * DGQ_ERR_SHAPE.

@@ -194,23 +194,33 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
     }
 }
 
-// Adds the K-split partial tiles and runs the epilogue.
+// Adds the K-split partial tiles and runs the epilogue; four consecutive columns per thread
+// (N is a multiple of 16, so a group of four never crosses a row).
 template <bool ACC>
 __global__ __launch_bounds__(256) void splitk_finalize_kernel(LinearArgs a, int ksplit, const int32_t *partial)
 {
     const size_t total = (size_t)a.M * a.N;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (idx >= total) return;
-    int sum = 0;
-    for (int p = 0; p < ksplit; ++p) sum += partial[(size_t)p * total + idx];
+    v4i sum = v4i{0, 0, 0, 0};
+    for (int p = 0; p < ksplit; ++p) sum += *reinterpret_cast<const v4i *>(&partial[(size_t)p * total + idx]);
     if (ACC) {
-        a.acc_out[idx] = sum;
+        *reinterpret_cast<v4i *>(&a.acc_out[idx]) = sum;
     } else {
         const int m = (int)(idx / a.N);
         const int n = (int)(idx % a.N);
-        const float sc = a.sx[m] * a.s1[n];
-        const _Float16 h = (_Float16)(sc * (float)sum);
-        a.out[idx] = __builtin_bit_cast(unsigned short, h);
+        const float sxm = a.sx[m];
+        const float s1v[4] = {a.s1[n], a.s1[n + 1], a.s1[n + 2], a.s1[n + 3]};  // s1 need not be 16-byte aligned
+        unsigned short h[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float sc = sxm * s1v[i];
+            h[i] = __builtin_bit_cast(unsigned short, (_Float16)(sc * (float)sum[i]));
+        }
+        uint2 o;
+        o.x = h[0] | ((uint32_t)h[1] << 16);
+        o.y = h[2] | ((uint32_t)h[3] << 16);
+        *reinterpret_cast<uint2 *>(&a.out[idx]) = o;
     }
 }
 
@@ -267,7 +277,7 @@ hipError_t launch_g(const LinearArgs &a, const DecodePlan &p, void *workspace, h
 hipError_t launch_splitk_finalize(const LinearArgs &a, int ksplit, const int32_t *partial, hipStream_t st)
 {
     const size_t total = (size_t)a.M * a.N;
-    dim3 fgrid((unsigned)((total + 255) / 256));
+    dim3 fgrid((unsigned)((total / 4 + 255) / 256));
     if (a.acc_out)
         hipLaunchKernelGGL(splitk_finalize_kernel<true>, fgrid, dim3(256), 0, st, a, ksplit, partial);
     else

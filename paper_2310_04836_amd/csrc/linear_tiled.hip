@@ -396,9 +396,11 @@ TiledPlan tiled_plan(int M, int N, int K)
         p.ksplit = (int)ks;
         return p;
     }
-    const long long tiles_128 = (long long)((M + 127) / 128) * tiles_n;
-    if (tiles_128 < kCus) {
-        // fewer 128-token tiles than CUs: 64-token tiles put twice as many SIMDs to work
+    const long long tiles_64 = (long long)((M + 63) / 64) * tiles_n;
+    if (tiles_64 <= kCus) {
+        // Even 64-token tiles leave every workgroup a CU of its own: twice as many SIMDs work as
+        // with 128-token tiles.  (With more tiles than CUs the smaller tile loses: it expands
+        // every weight twice as often.)
         p.mi = 2;
         return p;
     }

@@ -99,7 +99,8 @@ def test_linear_plan_names(dgq):
     assert dgq.linear_plan(17, 44032, 256, 64) == "linear_tiled_kernel<64, 4, 2, 6, false>"
     assert dgq.linear_workspace_bytes(17, 44032, 256, 64) == 0
     # fewer 128-token tiles than CUs: 64-token tiles
-    assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"
+    assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"     # 8 x 16 tiles
+    assert dgq.linear_plan(512, 12288, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"    # 4 x 48 tiles
     assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"
     assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
     assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 16 x 16 wide tiles
