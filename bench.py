@@ -327,7 +327,7 @@ def main():
         import oracle
         qcache = {}
         t_cpu, n_steps, done_bytes = 0.0, 0, 0
-        while t_cpu < 10.0 and n_steps < 3:
+        while t_cpu < 10.0 and n_steps < 12:
             for M in Ms:
                 for name, (K, N) in shapes.items():
                     # bounded sample for large layers: a contiguous slice of output channels
