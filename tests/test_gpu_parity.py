@@ -356,3 +356,14 @@ def test_llama65b_shapes(dgq, torch, g):
     f, mlt = workloads.OUTLIERS["65b"]
     for M in (1, 8, 64, 512):
         _forward_case(dgq, torch, M, K, N, g, seed=4, frac=f, mult=mlt, cols=_cols(N, 16, seed=M))
+
+
+def test_llama65b_qkv_mid_and_large_m(dgq, torch):
+    """M = 64: 64-token tiles, six stages, K split five ways; M = 2048: the 128 x 512 tile (its grid of
+    16 x 48 fills the CUs in whole rounds)."""
+    K, N = workloads.LLAMA_SHAPES["65b"]["qkv"]
+    assert dgq.linear_plan(64, N, K, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
+    assert dgq.linear_plan(2048, N, K, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"
+    f, mlt = workloads.OUTLIERS["65b"]
+    for M in (64, 2048):
+        _forward_case(dgq, torch, M, K, N, 128, seed=5, frac=f, mult=mlt, cols=_cols(N, 16, seed=M))
