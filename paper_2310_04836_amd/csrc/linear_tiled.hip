@@ -16,8 +16,8 @@
 //   - INT32 accumulation over all of K in AGPRs (third line of Eq. 2), then the scale
 //     epilogue (first line of Eq. 2) and one rounding to fp16.
 //   - Workgroups are numbered so that each XCD (workgroup id modulo 8) walks a contiguous
-//     range of tiles, M fastest: the tiles resident on one XCD share weight columns in
-//     that XCD's L2.
+//     range of tiles, ordered in bands of eight column tiles: the 64 workgroups resident on
+//     one XCD cover about 8 x 8 tiles and share their operands in that XCD's L2.
 #include "dgq_device.hpp"
 
 namespace dgq {
@@ -107,8 +107,14 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     if (work >= T) return;
     const int tile = work / ksplit;
     const int kpart = work - tile * ksplit;
-    const int m0 = (tile % tiles_m) * BM;
-    const int n0 = (tile / tiles_m) * BN;
+    // Tiles are numbered in bands of eight column tiles: inside a band the column tile runs
+    // fastest, then the token tile.  The 64 workgroups resident on an XCD then cover about
+    // 8 x 8 tiles, the shape that needs the fewest operand bytes in that XCD's L2.
+    const int band = tile / (8 * tiles_m);
+    const int in_band = tile - band * (8 * tiles_m);
+    const int band_w = tiles_n - band * 8 < 8 ? tiles_n - band * 8 : 8;
+    const int m0 = (in_band / band_w) * BM;
+    const int n0 = (band * 8 + in_band % band_w) * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
