@@ -124,16 +124,23 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     const int steps = a.K >> 7;
     const int gqn = ((a.K / G) + 3) >> 2;
 
-    // ---- weight stream: two 32-column tiles per wavefront; per-lane byte offsets ------------
+    // ---- weight stream: two 32-column tiles per wavefront ------------------------------------
+    // Per-lane byte offsets are relative to the tile's first 16-column block and first token
+    // (at most 128 K bytes, whatever the size of the tensors); the tile's origin is part of the
+    // 64-bit scalar base.
+    const char *q_tile = reinterpret_cast<const char *>(a.qweight) + (size_t)(n0 >> 4) * steps * 1024;
+    const char *s_tile = reinterpret_cast<const char *>(a.scales) + (size_t)(n0 >> 4) * gqn * 64;
+    const char *x_tile = reinterpret_cast<const char *>(a.xq) + (size_t)m0 * a.K;
     uint32_t boff[2], soff[2];
     int ncol[2];
 #pragma unroll
     for (int nj = 0; nj < 2; ++nj) {
         int n = n0 + wave * 64 + nj * 32 + li;
         ncol[nj] = n;
-        if (n >= a.N) n = a.N - 1;  // ragged N: read a valid column, never store it
-        boff[nj] = ((uint32_t)(n >> 4) * steps * 64 + kb * 16 + (n & 15)) * 16u;
-        soff[nj] = ((uint32_t)(n >> 4) * gqn * 16 + (n & 15)) * 4u;
+        if (n >= a.N) n = a.N - 1;  // ragged N: read a valid column (n0 <= n), never store it
+        const int nr = n - n0;      // N and n0 are multiples of 16, so nr/16 counts whole blocks
+        boff[nj] = ((uint32_t)(nr >> 4) * steps * 64 + kb * 16 + (nr & 15)) * 16u;
+        soff[nj] = ((uint32_t)(nr >> 4) * gqn * 16 + (nr & 15)) * 4u;
     }
     // ---- activation tile: each wavefront moves PPW 1 KiB pieces (8 rows each) per stage ------
     // lane l of piece q lands at LDS row r = (wave*PPW+q)*8 + l/8, stored unit l%8, which is
@@ -143,8 +150,8 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     for (int q = 0; q < PPW; ++q) {
         const int r = (wave * PPW + q) * 8 + (lane >> 3);
         int m = m0 + r;
-        if (m >= a.M) m = a.M - 1;  // ragged M: duplicate the last row, never store it
-        goff[q] = (uint32_t)m * a.K + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
+        if (m >= a.M) m = a.M - 1;  // ragged M: duplicate the last row (m0 <= m), never store it
+        goff[q] = (uint32_t)(m - m0) * a.K + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
     }
 
     // LDS byte address of this wavefront's first piece in stage buffer 0
@@ -171,10 +178,9 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
 #define DGQ_LOAD_ITEM(I, P, S)                                                                        \
     do {                                                                                              \
         const int ls_ = (S);                                                                          \
-        const char *qb_ = reinterpret_cast<const char *>(a.qweight) + (size_t)ls_ * 1024;             \
-        const char *sb_ = reinterpret_cast<const char *>(a.scales) +                                  \
-                          (size_t)(((G == 128) ? ls_ : 2 * ls_) >> 2) * 64;                           \
-        const char *xb_ = reinterpret_cast<const char *>(a.xq) + (size_t)ls_ * BK;                    \
+        const char *qb_ = q_tile + (size_t)ls_ * 1024;                                                \
+        const char *sb_ = s_tile + (size_t)(((G == 128) ? ls_ : 2 * ls_) >> 2) * 64;                  \
+        const char *xb_ = x_tile + (size_t)ls_ * BK;                                                  \
         if ((I) == 0) bq[P][0][0] = load_b128_async(qb_, boff[0]);                                    \
         else if ((I) == 1) bq[P][0][1] = load_b128_async_512(qb_, boff[0]);                           \
         else if ((I) == 2) sw[P][0] = load_b32_async(sb_, soff[0]);                                   \
@@ -460,7 +466,6 @@ static hipError_t launch_tiled_g(const LinearArgs &a, const TiledPlan &p, void *
 
 hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st)
 {
-    // the activation tile is addressed with 32-bit offsets inside the kernel's copies
     const TiledPlan p = tiled_plan(a.M, a.N, a.K);
     return a.group == 128 ? launch_tiled_g<128>(a, p, workspace, st) : launch_tiled_g<64>(a, p, workspace, st);
 }

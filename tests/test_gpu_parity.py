@@ -367,3 +367,23 @@ def test_llama65b_qkv_mid_and_large_m(dgq, torch):
     f, mlt = workloads.OUTLIERS["65b"]
     for M in (64, 2048):
         _forward_case(dgq, torch, M, K, N, 128, seed=5, frac=f, mult=mlt, cols=_cols(N, 16, seed=M))
+
+
+def test_tiled_path_activation_tensor_larger_than_4_gib(dgq, torch):
+    """M * K > 2^32 with the longest K the ABI accepts: addresses inside the kernels must not be
+    computed in 32 bits.  The INT32 sums of sampled tokens (first tile, the token at byte offset
+    2^32 exactly, its neighbours, the last one) are compared with an int64 product."""
+    M, K, N, g = 33000, 131072, 16, 128
+    rng = np.random.default_rng(11)
+    base = rng.integers(-127, 128, size=(1000, K), dtype=np.int8)
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    for b in range(0, M, 1000):                      # token m = base[m % 1000] rotated by m // 1000 + 1
+        rows = min(1000, M - b)
+        xq[b:b + rows] = torch.from_numpy(np.roll(base[:rows], b // 1000 + 1, axis=1)).cuda()
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 11)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    acc = dgq.linear_a8w4_acc(xq, pw)
+    ws8 = (np.repeat(s2.astype(np.int64), g, axis=0) * w4.astype(np.int64))
+    for m in (0, 1, 127, 128, 999, 1000, 32767, 32768, 32769, M - 1):
+        row = np.roll(base[m % 1000], m // 1000 + 1).astype(np.int64)
+        assert np.array_equal(host(acc[m]).astype(np.int64), row @ ws8), "token %d" % m
