@@ -41,6 +41,11 @@ def _L():
         _lib.dgq_oracle_gemm_i32.restype = ctypes.c_long
         _lib.dgq_oracle_pack.restype = ctypes.c_long
         _lib.dgq_oracle_threads.restype = ctypes.c_int
+        _lib.dgq_oracle_expand_zp.restype = ctypes.c_long
+        _lib.dgq_oracle_pack_zp.restype = ctypes.c_long
+        _lib.dgq_oracle_quantize_grid.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                  ctypes.c_int, ctypes.c_float, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     return _lib
 
 
@@ -174,3 +179,88 @@ def unpack(qweight, scales, K: int, N: int, group: int):
     s2 = np.empty((K // group, N), np.uint8)
     _L().dgq_oracle_unpack(_p(qweight), _p(scales), K, N, group, _p(w4), _p(s2))
     return w4, s2
+
+
+# ---------------------------------------------------------------------------
+# General operands: unsigned nibbles with per-group zero points (Section 3.2),
+# the clip of Eq. 4 and the two-phase grid search of Section 3.3
+# ---------------------------------------------------------------------------
+def expand_zp(u4, s2, zp, group: int):
+    """W_s8 = S2 * (W_u4 - ZP) (Eq. 2, second line; sign as in Eq. 1 / Appendix B).
+
+    Returns (ws8 int8 [K,N], n_out_of_int8)."""
+    u4 = _c(u4, np.uint8)
+    s2 = _c(s2, np.uint8)
+    zp = _c(zp, np.uint8)
+    K, N = u4.shape
+    assert K % group == 0 and s2.shape == (K // group, N) and zp.shape == s2.shape
+    ws8 = np.empty((K, N), np.int8)
+    bad = _L().dgq_oracle_expand_zp(_p(u4), _p(s2), _p(zp), K, N, group, _p(ws8))
+    return ws8, int(bad)
+
+
+def clip_interval(s2: int, zp: int):
+    """Interval of stored nibbles that keeps S2 * (u - ZP) inside INT8 (Eq. 4).  Returns (lo, hi)."""
+    lo, hi = ctypes.c_int(), ctypes.c_int()
+    _L().dgq_oracle_clip_interval(int(s2), int(zp), ctypes.byref(lo), ctypes.byref(hi))
+    return lo.value, hi.value
+
+
+def quantize_weights_grid(W, group: int, n_alpha: int = 51, step: float = 0.01):
+    """Two-phase grid search (Section 3.3, Eq. 3-5) with the weight-only objective.
+
+    W: fp16/fp32 [K, N].  Returns (u4 uint8 [K,N], zp uint8 [K/group,N], s2 uint8 [K/group,N], s1 float32 [N]).
+    """
+    Wf = _c(W, np.float32)
+    K, N = Wf.shape
+    assert K % group == 0 and n_alpha >= 1
+    u4 = np.empty((K, N), np.uint8)
+    zp = np.empty((K // group, N), np.uint8)
+    s2 = np.empty((K // group, N), np.uint8)
+    s1 = np.empty(N, np.float32)
+    _L().dgq_oracle_quantize_grid(_p(Wf), K, N, group, n_alpha, ctypes.c_float(step), _p(u4), _p(zp), _p(s2), _p(s1))
+    return u4, zp, s2, s1
+
+
+def packed_sizes_zp(K: int, N: int, group: int):
+    ng = K // group
+    return K * N // 2, (N // 16) * ((ng + 1) // 2) * 64
+
+
+def pack_zp(u4, s2, zp, group: int):
+    """Device format of the general operands.  Returns (qweight u8, scales_zp u8, n_bad)."""
+    u4 = _c(u4, np.uint8)
+    s2 = _c(s2, np.uint8)
+    zp = _c(zp, np.uint8)
+    K, N = u4.shape
+    assert K % 128 == 0 and N % 16 == 0 and group in (64, 128)
+    assert s2.shape == (K // group, N) and zp.shape == s2.shape
+    qb, sb = packed_sizes_zp(K, N, group)
+    qweight = np.empty(qb, np.uint8)
+    scales = np.empty(sb, np.uint8)
+    bad = _L().dgq_oracle_pack_zp(_p(u4), _p(s2), _p(zp), K, N, group, _p(qweight), _p(scales))
+    return qweight, scales, int(bad)
+
+
+def unpack_zp(qweight, scales_zp, K: int, N: int, group: int):
+    """Inverse of pack_zp.  Returns (u4, s2, zp)."""
+    qweight = _c(qweight, np.uint8)
+    scales_zp = _c(scales_zp, np.uint8)
+    qb, sb = packed_sizes_zp(K, N, group)
+    assert qweight.size == qb and scales_zp.size == sb
+    u4 = np.empty((K, N), np.uint8)
+    s2 = np.empty((K // group, N), np.uint8)
+    zp = np.empty((K // group, N), np.uint8)
+    _L().dgq_oracle_unpack_zp(_p(qweight), _p(scales_zp), K, N, group, _p(u4), _p(s2), _p(zp))
+    return u4, s2, zp
+
+
+def linear_a8w4_zp(xq, sx, u4, s2, zp, s1, group: int):
+    """Eq. 2 from quantized operands with per-group zero points.  Returns (out fp16, acc int32)."""
+    ws8, bad = expand_zp(u4, s2, zp, group)
+    if bad:
+        raise ValueError("%d expanded weights fall outside INT8" % bad)
+    acc, wrapped = gemm_i32(xq, ws8)
+    if wrapped:
+        raise OverflowError("%d INT32 accumulators would wrap" % wrapped)
+    return epilogue(acc, sx, s1), acc

@@ -18,13 +18,16 @@
  *
  * Parity status: every function below is pinned by tests that do not go
  * through this file's own formulas (hand-written tiny cases, closed forms,
- * numpy int64 matmul, an fp64 group-wise "segmented GEMM").  The statistical
- * accuracy of the RTN quantizer against the paper's perplexity tables is
- * parity unpinned (needs the trained models and datasets).
+ * numpy int64 matmul, an fp64 group-wise "segmented GEMM"; for the grid search:
+ * exactly representable inputs that it must recover, a brute-force check of the
+ * Eq. 4 interval, the min-max special case, error bounds).  The statistical
+ * accuracy of the RTN and grid-search quantizers against the paper's perplexity
+ * tables is parity unpinned (needs the trained models and datasets).
  */
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -267,6 +270,247 @@ void dgq_oracle_unpack(const uint8_t *qweight, const uint8_t *scales, int K, int
             uint8_t b = qweight[cell * 16 + k % 16];
             unsigned u = (k % 32 < 16) ? (b & 15u) : (b >> 4);
             w4[(size_t)k * N + n] = (int8_t)((int)u - 8);
+        }
+    }
+}
+
+/* ======================================================================================
+ * General form of the weight operands: unsigned nibbles with per-group zero points
+ * (operands of Eq. 2 as Section 3.2 lists them), the overflow-safe clip of Eq. 4 and the
+ * two-phase grid search of Section 3.3.
+ * ====================================================================================== */
+
+/*
+ * Second line of Eq. 2 with an explicit zero point, in the sign convention of Eq. 1 and
+ * Appendix B:  W_s8[k][n] = S2[k/g][n] * (W_u4[k][n] - ZP[k/g][n]).
+ * Returns how many results fall outside [-128, 127]; those are stored saturated.
+ */
+long dgq_oracle_expand_zp(const uint8_t *u4, const uint8_t *s2, const uint8_t *zp, int K, int N, int g,
+                          int8_t *ws8)
+{
+    long bad = 0;
+#pragma omp parallel for schedule(static) reduction(+ : bad)
+    for (int k = 0; k < K; ++k) {
+        for (int n = 0; n < N; ++n) {
+            const size_t gi = (size_t)(k / g) * N + n;
+            int v = (int)s2[gi] * ((int)u4[(size_t)k * N + n] - (int)zp[gi]);
+            if (v < -128 || v > 127) {
+                ++bad;
+                v = v < -128 ? -128 : 127;
+            }
+            ws8[(size_t)k * N + n] = (int8_t)v;
+        }
+    }
+    return bad;
+}
+
+/*
+ * Interval of Eq. 4: the stored nibbles u for which S2 * (u - ZP) stays inside
+ * [-127, 127], intersected with [0, 15].  The quotient 127 / S2 is truncated (the paper
+ * prints a rounding bracket; rounding it up would admit a product above 127, which is
+ * what the interval exists to prevent).
+ */
+void dgq_oracle_clip_interval(int s2, int zp, int *lo, int *hi)
+{
+    const int r = 127 / s2;
+    *lo = zp - r < 0 ? 0 : zp - r;
+    *hi = zp + r > 15 ? 15 : zp + r;
+}
+
+
+/*
+ * Two-phase grid search (Section 3.3) with the weight-only objective ||W - Q(W)||^2 (the
+ * activations of Eq. 3 and of the phase-2 objective are taken as the identity: there is no
+ * calibration set).  alpha runs over 1, 1 - step, ..., 1 - (n_alpha-1)*step.
+ *
+ * Phase 1, for every group j and column n on its own (Eq. 3, quantizer of Eq. 1 with
+ * N = 4 bits):
+ *     lo = min(min_k W, 0), hi = max(max_k W, 0)         the range always contains zero
+ *     s  = alpha * (hi - lo) / 15,  ZP = clamp(round(-(alpha * lo) / s), 0, 15)
+ *     u  = clamp(round(W / s) + ZP, 0, 15),  err = sum_k (W - (u - ZP) * s)^2
+ *   the alpha with the smallest err (the first one on ties) gives S'[j][n] and ZP[j][n];
+ *   an all-zero group gets S' = 0 and ZP = 0.
+ *
+ * Phase 2, for every column n (Eq. 5, clip of Eq. 4):
+ *     s1 = alpha * max_j S'[j][n] / 15
+ *     S2[j] = clamp(round(S'[j] / s1), 1, 127),  S = s1 * S2[j]
+ *     u = clamp(round(W / S) + ZP[j], lo4, hi4) with [lo4, hi4] from dgq_oracle_clip_interval
+ *     err = sum over the whole column of (W - (u - ZP) * S)^2
+ *   the alpha with the smallest err (first on ties) gives s1[n], S2[:, n] and u4[:, n];
+ *   an all-zero column gets s1 = 1, S2 = 1, u = ZP = 0.
+ *
+ * fp32 throughout, one IEEE division where a '/' is written, ties to even, sums in
+ * increasing k.  W is [K][N]; u4 [K][N]; zp, s2 [K/g][N]; s1 [N].
+ */
+void dgq_oracle_quantize_grid(const float *W, int K, int N, int g, int n_alpha, float step,
+                              uint8_t *u4, uint8_t *zp, uint8_t *s2, float *s1)
+{
+    const int ng = K / g;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int n = 0; n < N; ++n) {
+        float *Sp = (float *)malloc(sizeof(float) * (size_t)ng);
+        /* ---- phase 1 ---- */
+        for (int j = 0; j < ng; ++j) {
+            float lo = 0.0f, hi = 0.0f;
+            for (int k = j * g; k < (j + 1) * g; ++k) {
+                const float w = W[(size_t)k * N + n];
+                if (w < lo) lo = w;
+                if (w > hi) hi = w;
+            }
+            float best_err = 0.0f, best_s = 0.0f;
+            int best_zp = 0, have = 0;
+            if (hi - lo > 0.0f) {
+                for (int i = 0; i < n_alpha; ++i) {
+                    const float alpha = 1.0f - (float)i * step;
+                    const float s = (alpha * (hi - lo)) / 15.0f;
+                    const float z = clampf(rintf(-(alpha * lo) / s), 0.0f, 15.0f);
+                    float err = 0.0f;
+                    for (int k = j * g; k < (j + 1) * g; ++k) {
+                        const float w = W[(size_t)k * N + n];
+                        const float u = clampf(rintf(w / s) + z, 0.0f, 15.0f);
+                        const float d = w - (u - z) * s;
+                        err = err + d * d;
+                    }
+                    if (!have || err < best_err) {
+                        have = 1;
+                        best_err = err;
+                        best_s = s;
+                        best_zp = (int)z;
+                    }
+                }
+            }
+            Sp[j] = best_s;
+            zp[(size_t)j * N + n] = (uint8_t)best_zp;
+        }
+        /* ---- phase 2 ---- */
+        float smax = 0.0f;
+        for (int j = 0; j < ng; ++j)
+            if (Sp[j] > smax) smax = Sp[j];
+        if (!(smax > 0.0f)) {
+            s1[n] = 1.0f;
+            for (int j = 0; j < ng; ++j) s2[(size_t)j * N + n] = 1, zp[(size_t)j * N + n] = 0;
+            for (int k = 0; k < K; ++k) u4[(size_t)k * N + n] = 0;
+            free(Sp);
+            continue;
+        }
+        float best_err = 0.0f, best_s1 = 0.0f;
+        int have = 0;
+        for (int i = 0; i < n_alpha; ++i) {
+            const float alpha = 1.0f - (float)i * step;
+            const float c1 = (alpha * smax) / 15.0f;
+            float err = 0.0f;
+            for (int j = 0; j < ng; ++j) {
+                const float q2 = clampf(rintf(Sp[j] / c1), 1.0f, 127.0f);
+                const float S = c1 * q2;
+                const int z = zp[(size_t)j * N + n];
+                int lo4, hi4;
+                dgq_oracle_clip_interval((int)q2, z, &lo4, &hi4);
+                for (int k = j * g; k < (j + 1) * g; ++k) {
+                    const float w = W[(size_t)k * N + n];
+                    const float u = clampf(rintf(w / S) + (float)z, (float)lo4, (float)hi4);
+                    const float d = w - (u - (float)z) * S;
+                    err = err + d * d;
+                }
+            }
+            if (!have || err < best_err) {
+                have = 1;
+                best_err = err;
+                best_s1 = c1;
+            }
+        }
+        s1[n] = best_s1;
+        for (int j = 0; j < ng; ++j) {
+            const float q2 = clampf(rintf(Sp[j] / best_s1), 1.0f, 127.0f);
+            const float S = best_s1 * q2;
+            const int z = zp[(size_t)j * N + n];
+            int lo4, hi4;
+            dgq_oracle_clip_interval((int)q2, z, &lo4, &hi4);
+            s2[(size_t)j * N + n] = (uint8_t)q2;
+            for (int k = j * g; k < (j + 1) * g; ++k) {
+                const float w = W[(size_t)k * N + n];
+                const float u = clampf(rintf(w / S) + (float)z, (float)lo4, (float)hi4);
+                u4[(size_t)k * N + n] = (uint8_t)u;
+            }
+        }
+        free(Sp);
+    }
+}
+
+/*
+ * Device format for the general operands, written from the layout text alone.
+ *   qweight: as in dgq_oracle_pack, the stored nibble being W_u4 itself.
+ *   scales_zp: two bytes per (group, column), the group scale S2 then the zero point, at
+ *     ((n/16) * ceil(ng/2) + gi/2) * 64 + (n%16) * 4 + (gi%2) * 2;   padding bytes are zero.
+ * Returns the number of inputs that break a rule: S2 outside [1, 127] (packed as 1), ZP
+ * above 15 (packed as 0), a nibble above 15 or a product S2 * (u - ZP) outside [-128, 127]
+ * (the nibble is then packed as ZP, a zero weight).
+ */
+long dgq_oracle_pack_zp(const uint8_t *u4, const uint8_t *s2, const uint8_t *zp, int K, int N, int g,
+                        uint8_t *qweight, uint8_t *scales_zp)
+{
+    const int ng = K / g;
+    const int gh = (ng + 1) / 2;
+    const int ksteps = K / 128;
+    long bad = 0;
+    memset(qweight, 0, (size_t)K * N / 2);
+    memset(scales_zp, 0, (size_t)(N / 16) * gh * 64);
+    for (int gi = 0; gi < ng; ++gi) {
+        for (int n = 0; n < N; ++n) {
+            int s = s2[(size_t)gi * N + n], z = zp[(size_t)gi * N + n];
+            if (s < 1 || s > 127) {
+                ++bad;
+                s = 1;
+            }
+            if (z > 15) {
+                ++bad;
+                z = 0;
+            }
+            const size_t at = ((size_t)(n / 16) * gh + gi / 2) * 64 + (size_t)(n % 16) * 4 + (size_t)(gi % 2) * 2;
+            scales_zp[at] = (uint8_t)s;
+            scales_zp[at + 1] = (uint8_t)z;
+        }
+    }
+    for (int k = 0; k < K; ++k) {
+        for (int n = 0; n < N; ++n) {
+            const int gi = k / g;
+            int s = s2[(size_t)gi * N + n], z = zp[(size_t)gi * N + n];
+            if (s < 1 || s > 127) s = 1;
+            if (z > 15) z = 0;
+            int u = u4[(size_t)k * N + n];
+            const int v = s * (u - z);
+            if (u > 15 || v < -128 || v > 127) {
+                ++bad;
+                u = z;
+            }
+            size_t cell = ((size_t)(n / 16) * ksteps + k / 128) * 64 + (size_t)((k % 128) / 32) * 16 + n % 16;
+            size_t byte = cell * 16 + k % 16;
+            if (k % 32 < 16)
+                qweight[byte] |= (uint8_t)u;
+            else
+                qweight[byte] |= (uint8_t)(u << 4);
+        }
+    }
+    return bad;
+}
+
+/* Inverse of dgq_oracle_pack_zp. */
+void dgq_oracle_unpack_zp(const uint8_t *qweight, const uint8_t *scales_zp, int K, int N, int g,
+                          uint8_t *u4, uint8_t *s2, uint8_t *zp)
+{
+    const int ng = K / g;
+    const int gh = (ng + 1) / 2;
+    const int ksteps = K / 128;
+    for (int gi = 0; gi < ng; ++gi)
+        for (int n = 0; n < N; ++n) {
+            const size_t at = ((size_t)(n / 16) * gh + gi / 2) * 64 + (size_t)(n % 16) * 4 + (size_t)(gi % 2) * 2;
+            s2[(size_t)gi * N + n] = scales_zp[at];
+            zp[(size_t)gi * N + n] = scales_zp[at + 1];
+        }
+    for (int k = 0; k < K; ++k) {
+        for (int n = 0; n < N; ++n) {
+            size_t cell = ((size_t)(n / 16) * ksteps + k / 128) * 64 + (size_t)((k % 128) / 32) * 16 + n % 16;
+            uint8_t b = qweight[cell * 16 + k % 16];
+            u4[(size_t)k * N + n] = (uint8_t)((k % 32 < 16) ? (b & 15u) : (b >> 4));
         }
     }
 }
