@@ -157,6 +157,49 @@ DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, co
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ---- General operands of Eq. 2: unsigned nibbles with per-group zero points --------------
+ *
+ * Section 3.2 lists the operands as W_u4 in [0, 15], group-wise zero points ZP and group-wise
+ * INT8 scales S2, with W_s8 = S2 * (W_u4 - ZP) (sign as in Eq. 1 and Appendix B); Section 3.3
+ * allows S2 above 15 as long as W_s8 fits INT8 (Eq. 4).  The calls below take that form:
+ * S2 in [1, 127], ZP in [0, 15], every product S2 * (u - ZP) inside [-128, 127].  The calls
+ * above are the special case ZP = 8, S2 <= 15 with a smaller scale array.
+ *
+ * Format: qweight as written by dgq_pack_weights, the stored nibble being W_u4 itself.
+ * scales_zp: two bytes per (group, column), S2 then ZP, at
+ * ((n/16)*ceil(ng/2) + gi/2)*64 + (n%16)*4 + (gi%2)*2; padding bytes are 0;
+ * scales_zp_bytes = (N/16) * ceil((K/group)/2) * 64.
+ */
+DGQ_API dgq_status dgq_packed_sizes_zp(int K, int N, int group, size_t *qweight_bytes, size_t *scales_zp_bytes);
+
+/*
+ *   w_u4  in  [K][N] uint8, nibbles in [0, 15]
+ *   s2    in  [K/group][N] uint8 in [1, 127];  zp in [K/group][N] uint8 in [0, 15]
+ *   bad_count in/out, nullable, zeroed by the caller: the kernels add the number of rule
+ *         breakers.  A scale outside its range is packed as 1, a zero point above 15 as 0, a
+ *         nibble above 15 or with S2 * (u - ZP) outside [-128, 127] as ZP (a zero weight).
+ */
+DGQ_API dgq_status dgq_pack_weights_zp(const uint8_t *w_u4, const uint8_t *s2, const uint8_t *zp, int K, int N,
+                               int group, void *qweight, void *scales_zp, int32_t *bad_count, void *stream);
+
+/* Test hook: W_s8[K][N] = S2 * (W_u4 - ZP) from the packed form. */
+DGQ_API dgq_status dgq_unpack_weights_zp(const void *qweight, const void *scales_zp, int K, int N, int group,
+                                 int8_t *w_s8, void *stream);
+
+/*
+ * dgq_linear_a8w4 / dgq_linear_a8w4_acc for operands packed by dgq_pack_weights_zp: same
+ * kernels (the zero point is one more byte in the scale word), same arguments, same workspace
+ * rule.  Not available under dgq_force_path(3).
+ */
+DGQ_API dgq_status dgq_linear_a8w4_zp(const int8_t *xq, const float *sx, const void *qweight,
+                              const void *scales_zp, const float *s1, uint16_t *out,
+                              int M, int N, int K, int group,
+                              void *workspace, size_t workspace_bytes, void *stream);
+DGQ_API dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight, const void *scales_zp,
+                                  int32_t *acc_out, int M, int N, int K, int group,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Selects the GEMM path for later dgq_linear_a8w4* and dgq_linear_workspace_bytes calls of
  * this process (host, for tests and measurements): 0 = choose by M (default), 1 = the
  * weight-streaming kernels, 2 = the tiled kernel, 3 = the weight-streaming kernel that

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "probe_mfma", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -52,12 +52,18 @@ def _load() -> ctypes.CDLL:
     L.dgq_quant_act.argtypes = [vp, i, i, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_packed_sizes_zp.argtypes = [i, i, i, psz, psz]
+    L.dgq_pack_weights_zp.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, vp]
+    L.dgq_unpack_weights_zp.argtypes = [vp, vp, i, i, i, vp, vp]
+    L.dgq_linear_a8w4_zp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_linear_a8w4_zp_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_probe_read.argtypes = [vp, sz, vp, i, vp]
     L.dgq_probe_mfma.argtypes = [vp, sz, i, vp, i, vp]
     L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
-                 "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan"):
+                 "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan", "dgq_packed_sizes_zp", "dgq_pack_weights_zp",
+                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc"):
         getattr(L, name).restype = i
     return L
 
@@ -107,11 +113,15 @@ def linear_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
 
 
 class PackedWeight:
-    """Device buffers of one packed layer: qweight, scales (both uint8), s1 (float32 [N])."""
+    """Device buffers of one packed layer: qweight, scales (both uint8), s1 (float32 [N]).
 
-    def __init__(self, qweight, scales, s1, K, N, group):
+    zp_form False: signed nibbles, `scales` holds S2 bytes (dgq_pack_weights).  True: unsigned nibbles
+    with per-group zero points, `scales` holds (S2, ZP) byte pairs (dgq_pack_weights_zp)."""
+
+    def __init__(self, qweight, scales, s1, K, N, group, zp_form=False):
         self.qweight, self.scales, self.s1 = qweight, scales, s1
         self.K, self.N, self.group = K, N, group
+        self.zp_form = zp_form
         self.layout = layout_version()
 
     @property
@@ -137,11 +147,36 @@ def pack_weights(w4: torch.Tensor, s2: torch.Tensor, s1: torch.Tensor, group: in
     return pw
 
 
+def packed_sizes_zp(K: int, N: int, group: int):
+    q, s = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.dgq_packed_sizes_zp(K, N, group, ctypes.byref(q), ctypes.byref(s)), "dgq_packed_sizes_zp")
+    return q.value, s.value
+
+
+def pack_weights_zp(u4: torch.Tensor, s2: torch.Tensor, zp: torch.Tensor, s1: torch.Tensor, group: int,
+                    return_bad: bool = False):
+    """dgq_pack_weights_zp: u4 uint8 [K,N], s2 and zp uint8 [K/group,N], s1 float32 [N] -> PackedWeight."""
+    _dev(u4, torch.uint8, "u4"); _dev(s2, torch.uint8, "s2"); _dev(zp, torch.uint8, "zp"); _dev(s1, torch.float32, "s1")
+    K, N = u4.shape
+    if tuple(s2.shape) != (K // group, N) or tuple(zp.shape) != tuple(s2.shape) or tuple(s1.shape) != (N,):
+        raise ValueError("s2/zp/s1 shapes do not match u4 and group")
+    qb, sb = packed_sizes_zp(K, N, group)
+    qweight = torch.empty(qb, dtype=torch.uint8, device=u4.device)
+    scales = torch.empty(sb, dtype=torch.uint8, device=u4.device)
+    bad = torch.zeros(1, dtype=torch.int32, device=u4.device)
+    _check(lib.dgq_pack_weights_zp(_ptr(u4), _ptr(s2), _ptr(zp), K, N, group, _ptr(qweight), _ptr(scales),
+                                   _ptr(bad), _stream()), "dgq_pack_weights_zp")
+    pw = PackedWeight(qweight, scales, s1, K, N, group, zp_form=True)
+    if return_bad:
+        return pw, int(bad.item())
+    return pw
+
+
 def unpack_weights(pw: PackedWeight) -> torch.Tensor:
-    """dgq_unpack_weights: W_s8 int8 [K,N]."""
+    """dgq_unpack_weights / dgq_unpack_weights_zp: W_s8 int8 [K,N]."""
     out = torch.empty((pw.K, pw.N), dtype=torch.int8, device=pw.qweight.device)
-    _check(lib.dgq_unpack_weights(_ptr(pw.qweight), _ptr(pw.scales), pw.K, pw.N, pw.group, _ptr(out), _stream()),
-           "dgq_unpack_weights")
+    fn = lib.dgq_unpack_weights_zp if pw.zp_form else lib.dgq_unpack_weights
+    _check(fn(_ptr(pw.qweight), _ptr(pw.scales), pw.K, pw.N, pw.group, _ptr(out), _stream()), "dgq_unpack_weights")
     return out
 
 
@@ -187,8 +222,9 @@ def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch
     if workspace is None:
         workspace = _workspace(M, pw.N, K, pw.group, xq.device)
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.dgq_linear_a8w4(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
-                               M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
+    fn = lib.dgq_linear_a8w4_zp if pw.zp_form else lib.dgq_linear_a8w4
+    _check(fn(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
+              M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
     return out
 
 
@@ -222,6 +258,7 @@ def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor 
     if workspace is None:
         workspace = _workspace(M, pw.N, K, pw.group, xq.device)
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.dgq_linear_a8w4_acc(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group,
-                                   _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4_acc")
+    fn = lib.dgq_linear_a8w4_zp_acc if pw.zp_form else lib.dgq_linear_a8w4_acc
+    _check(fn(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group,
+              _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4_acc")
     return acc

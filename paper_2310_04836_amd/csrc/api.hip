@@ -53,6 +53,7 @@ dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_byte
     const int forced = g_force_path.load(std::memory_order_relaxed);
     if ((forced == kPathStream || forced == kPathStreamGeneric) && a.M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
     const int path = pick_path(a.M, forced);
+    if (path == kPathStreamGeneric && a.zp) return DGQ_ERR_SHAPE;  // that kernel knows the constant zero point only
     const size_t need = workspace_needed(path, a.M, a.N, a.K);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return DGQ_ERR_WORKSPACE;
@@ -132,7 +133,38 @@ dgq_status dgq_unpack_weights(const void *qweight, const void *scales, int K, in
     if (!qweight || !scales || !w_s8) return DGQ_ERR_NULL;
     if (dgq_status st = check_shape(N, K, group)) return st;
     if (!aligned16(qweight) || !aligned16(scales) || !aligned16(w_s8)) return DGQ_ERR_ALIGN;
-    return hip_result(dgq::launch_unpack(qweight, scales, K, N, group, w_s8, static_cast<hipStream_t>(stream)));
+    return hip_result(dgq::launch_unpack(qweight, scales, 0, K, N, group, w_s8, static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_packed_sizes_zp(int K, int N, int group, size_t *qweight_bytes, size_t *scales_zp_bytes)
+{
+    if (!qweight_bytes || !scales_zp_bytes) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    const size_t ng = (size_t)K / group;
+    *qweight_bytes = (size_t)K * (size_t)N / 2;
+    *scales_zp_bytes = ((size_t)N / 16) * ((ng + 1) / 2) * 64;
+    return DGQ_OK;
+}
+
+dgq_status dgq_pack_weights_zp(const uint8_t *w_u4, const uint8_t *s2, const uint8_t *zp, int K, int N, int group,
+                               void *qweight, void *scales_zp, int32_t *bad_count, void *stream)
+{
+    if (!w_u4 || !s2 || !zp || !qweight || !scales_zp) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(w_u4) || !aligned16(s2) || !aligned16(zp) || !aligned16(qweight) || !aligned16(scales_zp))
+        return DGQ_ERR_ALIGN;
+    if (bad_count && (reinterpret_cast<uintptr_t>(bad_count) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_pack_zp(w_u4, s2, zp, K, N, group, qweight, scales_zp, bad_count,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_unpack_weights_zp(const void *qweight, const void *scales_zp, int K, int N, int group, int8_t *w_s8,
+                                 void *stream)
+{
+    if (!qweight || !scales_zp || !w_s8) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(qweight) || !aligned16(scales_zp) || !aligned16(w_s8)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_unpack(qweight, scales_zp, 1, K, N, group, w_s8, static_cast<hipStream_t>(stream)));
 }
 
 dgq_status dgq_quantize_weights_rtn(const uint16_t *W, int K, int N, int group, int8_t *w4, uint8_t *s2,
@@ -152,9 +184,9 @@ dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx,
     return hip_result(dgq::launch_quant_act(x, M, K, xq, sx, static_cast<hipStream_t>(stream)));
 }
 
-dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight, const void *scales,
-                           const float *s1, uint16_t *out, int M, int N, int K, int group, void *workspace,
-                           size_t workspace_bytes, void *stream)
+static dgq_status linear_fp16(const int8_t *xq, const float *sx, const void *qweight, const void *scales,
+                              int zp_form, const float *s1, uint16_t *out, int M, int N, int K, int group,
+                              void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!xq || !sx || !qweight || !scales || !s1 || !out) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
@@ -163,21 +195,49 @@ dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweigh
         (reinterpret_cast<uintptr_t>(sx) & 3u) || (reinterpret_cast<uintptr_t>(s1) & 3u))
         return DGQ_ERR_ALIGN;
     dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
-                      s1, out, nullptr, M, N, K, group};
+                      s1, out, nullptr, M, N, K, group, zp_form};
     return run_linear(a, workspace, workspace_bytes, stream);
 }
 
-dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales, int32_t *acc_out,
-                               int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
-                               void *stream)
+static dgq_status linear_acc(const int8_t *xq, const void *qweight, const void *scales, int zp_form,
+                             int32_t *acc_out, int M, int N, int K, int group, void *workspace,
+                             size_t workspace_bytes, void *stream)
 {
     if (!xq || !qweight || !scales || !acc_out) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
     if (!aligned16(xq) || !aligned16(qweight) || !aligned16(scales) || !aligned16(acc_out)) return DGQ_ERR_ALIGN;
     dgq::LinearArgs a{xq, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
-                      nullptr, nullptr, acc_out, M, N, K, group};
+                      nullptr, nullptr, acc_out, M, N, K, group, zp_form};
     return run_linear(a, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight, const void *scales,
+                           const float *s1, uint16_t *out, int M, int N, int K, int group, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return linear_fp16(xq, sx, qweight, scales, 0, s1, out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales, int32_t *acc_out,
+                               int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    return linear_acc(xq, qweight, scales, 0, acc_out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_a8w4_zp(const int8_t *xq, const float *sx, const void *qweight, const void *scales_zp,
+                              const float *s1, uint16_t *out, int M, int N, int K, int group, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    return linear_fp16(xq, sx, qweight, scales_zp, 1, s1, out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight, const void *scales_zp, int32_t *acc_out,
+                                  int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    return linear_acc(xq, qweight, scales_zp, 1, acc_out, M, N, K, group, workspace, workspace_bytes, stream);
 }
 
 dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes)

@@ -16,27 +16,44 @@ typedef unsigned short v2u16 __attribute__((ext_vector_type(2)));
 
 // ---- INT4 -> INT8 expansion in registers (second line of Eq. 2) -------------------
 //
-// A 32-bit word holds eight stored nibbles u = w4 + 8.  The even nibbles (low halves of
-// the four bytes) and the odd nibbles (high halves) are separated into two words of four
-// bytes each; every byte is then turned into the signed INT8 value s2 * (u - 8):
+// A 32-bit word holds eight stored nibbles u.  The even nibbles (low halves of the four
+// bytes) and the odd nibbles (high halves) are separated into two words of four bytes each;
+// every byte is then turned into the signed INT8 value s2 * (u - zp):
 //
-//   s2*u + (128 - 8*s2)  lies in [8, 233] for s2 in [1, 15], u in [0, 15], so a packed
-//   16-bit multiply-add over byte pairs never carries from one byte into the next, and
-//   flipping bit 7 of each byte subtracts the 128 again in two's complement.
+//   r = s2*u + (128 - zp*s2) is the wanted value plus 128, so it lies in [0, 255] whenever
+//   the value fits INT8 (which packing has checked).  One packed 16-bit multiply-add over
+//   byte pairs computes (r0 + 256*r1) modulo 2^16: intermediate products may wrap, the sum
+//   cannot, because both r are bytes.  Flipping bit 7 of each byte then subtracts the 128
+//   again in two's complement.  With the constant zero point 8 of the signed-nibble format
+//   and s2 <= 15, r lies in [8, 233].
 struct GroupScale {
     uint32_t mul;  // s2 in both 16-bit halves
-    uint32_t add;  // (128 - 8*s2) in all four bytes
+    uint32_t add;  // (128 - zp*s2) modulo 256 in all four bytes
 };
 
-__device__ __forceinline__ GroupScale make_group_scale(uint32_t s2)
+__device__ __forceinline__ GroupScale make_group_scale(uint32_t s2, uint32_t zp)
 {
     GroupScale g;
     g.mul = s2 | (s2 << 16);
-    // 0x8080 - s2*0x0808 per 16-bit half, as one packed multiply-add (mod 2^16)
-    const v2u16 m = __builtin_bit_cast(v2u16, g.mul);
-    const v2u16 r = m * (v2u16){0xF7F8, 0xF7F8} + (v2u16){0x8080, 0x8080};
+    // 0x8080 - s2*zp*0x0101 per 16-bit half (mod 2^16): -0x0101 = 0xFEFF
+    const uint32_t z2 = zp | (zp << 16);
+    const v2u16 f = __builtin_bit_cast(v2u16, z2) * (v2u16){0xFEFF, 0xFEFF};
+    const v2u16 r = __builtin_bit_cast(v2u16, g.mul) * f + (v2u16){0x8080, 0x8080};
     g.add = __builtin_bit_cast(uint32_t, r);
     return g;
+}
+
+// The scale array has one of two forms (LinearArgs::zp): 0 = one byte per group and column,
+// the group scale S2, with the constant zero point 8; 1 = two bytes, S2 then the zero point.
+// A 32-bit word therefore holds 4 or 2 consecutive groups of one column.
+__device__ __forceinline__ int scale_word_shift(int zp_form) { return zp_form ? 1 : 2; }
+__device__ __forceinline__ GroupScale group_scale_from_word(uint32_t word, int gi, int zp_form)
+{
+    if (zp_form) {
+        const uint32_t e = word >> (16 * (gi & 1));
+        return make_group_scale(e & 0xFFu, (e >> 8) & 0xFFu);
+    }
+    return make_group_scale((word >> (8 * (gi & 3))) & 0xFFu, 8u);
 }
 
 __device__ __forceinline__ uint32_t scale_bytes(uint32_t four_nibbles_in_bytes, const GroupScale &g)
@@ -66,8 +83,10 @@ hipError_t launch_quantize_rtn(const uint16_t *W, int K, int N, int group, int8_
                                float *s1, hipStream_t st);
 hipError_t launch_pack(const int8_t *w4, const uint8_t *s2, int K, int N, int group, void *qweight,
                        void *scales, int32_t *bad_count, hipStream_t st);
-hipError_t launch_unpack(const void *qweight, const void *scales, int K, int N, int group,
+hipError_t launch_unpack(const void *qweight, const void *scales, int zp_form, int K, int N, int group,
                          int8_t *w_s8, hipStream_t st);
+hipError_t launch_pack_zp(const uint8_t *u4, const uint8_t *s2, const uint8_t *zp, int K, int N, int group,
+                          void *qweight, void *scales_zp, int32_t *bad_count, hipStream_t st);
 
 struct LinearArgs {
     const int8_t *xq;
@@ -78,6 +97,7 @@ struct LinearArgs {
     uint16_t *out;         // fp16 bits, null in acc mode
     int32_t *acc_out;      // null in fp16 mode
     int M, N, K, group;
+    int zp;                // form of `scales`: 0 = S2 bytes (zero point 8), 1 = (S2, ZP) byte pairs
 };
 // Largest M the weight-streaming kernels take.
 constexpr int kStreamMaxM = 64;

@@ -40,7 +40,8 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
     const int kb = lane >> 4;
     const int steps = a.K >> 7;
     const int tiles = a.N >> 4;
-    const int gqn = ((a.K / G) + 3) >> 2;
+    const int fsh = scale_word_shift(a.zp);  // groups per scale word: 4 (S2 bytes) or 2 (S2, ZP pairs)
+    const int gqn = ((a.K / G) + (1 << fsh) - 1) >> fsh;
 
     // This workgroup's part of K; wavefront w takes steps [p0 + w*SPW, p0 + (w+1)*SPW) of it.
     // Only the last active wavefront can be short; wavefronts past the end only help reduce.
@@ -91,8 +92,8 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
             const int s = i < nst ? sb + i : sb;
             const int gi = (G == 128) ? s : 2 * s + (kb >> 1);
             qoff[i] = s * 64 + lane;
-            soff[i] = (gi >> 2) * 16 + j;
-            ssh[i] = 8 * (gi & 3);
+            soff[i] = (gi >> fsh) * 16 + j;
+            ssh[i] = gi;
         }
 
         uint4 q[PF][SPW];
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
         v4i acc = v4i{0, 0, 0, 0};                                                                   \
         _Pragma("unroll") for (int i = 0; i < SPW; ++i)                                              \
         {                                                                                            \
-            const GroupScale gs = make_group_scale((sw[P][i] >> ssh[i]) & 0xFFu);                    \
+            const GroupScale gs = group_scale_from_word(sw[P][i], ssh[i], a.zp);                     \
             v4i b0, b1;                                                                              \
             expand_cell(q[P][i], gs, b0, b1);                                                        \
             acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, xa[i][0]), b0, acc, 0, 0, 0); \

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(W * 64) void linear_stream_kernel(LinearArgs a)
         }
     };
     auto compute = [&](const Slot<MT> &sl, int s) {
-        const GroupScale gs = make_group_scale((sl.sw >> (8 * (group_of(s) & 3))) & 0xFFu);
+        const GroupScale gs = make_group_scale((sl.sw >> (8 * (group_of(s) & 3))) & 0xFFu, 8u);
         v4i b0, b1;
         expand_cell(sl.q, gs, b0, b1);
 #pragma unroll

@@ -122,7 +122,8 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     const int kb = lane >> 5;
     const int li = lane & 31;
     const int steps = a.K >> 7;
-    const int gqn = ((a.K / G) + 3) >> 2;
+    const int fsh = scale_word_shift(a.zp);  // groups per scale word: 4 (S2 bytes) or 2 (S2, ZP pairs)
+    const int gqn = ((a.K / G) + (1 << fsh) - 1) >> fsh;
 
     // ---- weight stream: two 32-column tiles per wavefront ------------------------------------
     // Per-lane byte offsets are relative to the tile's first 16-column block and first token
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     do {                                                                                              \
         const int ls_ = (S);                                                                          \
         const char *qb_ = q_tile + (size_t)ls_ * 1024;                                                \
-        const char *sb_ = s_tile + (size_t)(((G == 128) ? ls_ : 2 * ls_) >> 2) * 64;                  \
+        const char *sb_ = s_tile + (size_t)(((G == 128) ? ls_ : 2 * ls_) >> fsh) * 64;                \
         const char *xb_ = x_tile + (size_t)ls_ * BK;                                                  \
         if ((I) == 0) bq[P][0][0] = load_b128_async(qb_, boff[0]);                                    \
         else if ((I) == 1) bq[P][0][1] = load_b128_async_512(qb_, boff[0]);                           \
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     do {                                                                                              \
         const int gi_ = (G == 128) ? (SN) : 2 * (SN) + ((GRPN) >> 1);                                 \
         _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) gsn[nj] =                                    \
-            make_group_scale((sw[PN][nj] >> (8 * (gi_ & 3))) & 0xFFu);                                \
+            group_scale_from_word(sw[PN][nj], gi_, a.zp);                                            \
     } while (0)
     // prepares piece C of group GRPN (stage set PN) into parity PARN
 #define DGQ_PREP(PARN, C, PN, GRPN)                                                                   \

@@ -129,24 +129,97 @@ __global__ __launch_bounds__(256) void pack_scales_kernel(const uint8_t *__restr
 }
 
 // ------------------------------------------------------------------------------------
+// Packer for the general operands of Eq. 2: unsigned nibbles, group scales in [1, 127] and
+// per-group zero points.  Same cells; the scale array holds (S2, ZP) byte pairs.  A nibble
+// whose product S2 * (u - ZP) leaves INT8 (the constraint that Eq. 4 enforces) is counted and
+// packed as ZP, i.e. as a zero weight.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_cells_zp_kernel(const uint8_t *__restrict__ u4,
+                                                            const uint8_t *__restrict__ s2,
+                                                            const uint8_t *__restrict__ zp, int K, int N,
+                                                            int group, uint4 *__restrict__ qweight,
+                                                            int32_t *__restrict__ bad_count)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    const int kk = blockIdx.y;  // 32-k block
+    if (n >= N) return;
+    const int gi = (kk * 32) / group;
+    int s = s2[(size_t)gi * N + n], z = zp[(size_t)gi * N + n];
+    if (s < 1 || s > 127) s = 1;  // counted by pack_scales_zp_kernel
+    if (z > 15) z = 0;
+    const uint8_t *src = u4 + (size_t)kk * 32 * N + n;
+    uint32_t word[4] = {0, 0, 0, 0};
+    int bad = 0;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        int u = src[(size_t)r * N];
+        const int v = s * (u - z);
+        if (u > 15 || v < -128 || v > 127) {
+            ++bad;
+            u = z;
+        }
+        const int byte = r & 15;
+        const int shift = (byte & 3) * 8 + (r >> 4) * 4;
+        word[byte >> 2] |= (uint32_t)u << shift;
+    }
+    const int ksteps = K >> 7;
+    const size_t cell = ((size_t)(n >> 4) * ksteps + (kk >> 2)) * 64 + (size_t)(kk & 3) * 16 + (n & 15);
+    qweight[cell] = make_uint4(word[0], word[1], word[2], word[3]);
+    if (bad && bad_count) atomicAdd(bad_count, bad);
+}
+
+// Thread = two consecutive groups of one column -> one 32-bit word of (S2, ZP) pairs.
+__global__ __launch_bounds__(256) void pack_scales_zp_kernel(const uint8_t *__restrict__ s2,
+                                                             const uint8_t *__restrict__ zp, int ng, int N,
+                                                             uint32_t *__restrict__ scales,
+                                                             int32_t *__restrict__ bad_count)
+{
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    const int gh = blockIdx.y;
+    if (n >= N) return;
+    const int ghn = (ng + 1) >> 1;
+    uint32_t word = 0;
+    int bad = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int gi = gh * 2 + i;
+        if (gi < ng) {
+            uint32_t s = s2[(size_t)gi * N + n], z = zp[(size_t)gi * N + n];
+            if (s < 1 || s > 127) {
+                ++bad;
+                s = 1;
+            }
+            if (z > 15) {
+                ++bad;
+                z = 0;
+            }
+            word |= (s | (z << 8)) << (16 * i);
+        }
+    }
+    scales[((size_t)(n >> 4) * ghn + gh) * 16 + (n & 15)] = word;
+    if (bad && bad_count) atomicAdd(bad_count, bad);
+}
+
+// ------------------------------------------------------------------------------------
 // Unpack test hook: thread = one cell, expanded with the same device function the GEMM
 // kernels use, written to W_s8[K][N].
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void unpack_kernel(const uint4 *__restrict__ qweight,
-                                                     const uint32_t *__restrict__ scales, int K, int N,
-                                                     int group, int8_t *__restrict__ w_s8)
+                                                     const uint32_t *__restrict__ scales, int zp_form,
+                                                     int K, int N, int group, int8_t *__restrict__ w_s8)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
     const int kk = blockIdx.y;
     if (n >= N) return;
     const int ksteps = K >> 7;
     const int ng = K / group;
-    const int gqn = (ng + 3) >> 2;
+    const int fsh = scale_word_shift(zp_form);
+    const int gqn = (ng + (1 << fsh) - 1) >> fsh;
     const size_t cell = ((size_t)(n >> 4) * ksteps + (kk >> 2)) * 64 + (size_t)(kk & 3) * 16 + (n & 15);
     const uint4 q = qweight[cell];
     const int gi = (kk * 32) / group;
-    const uint32_t sw = scales[((size_t)(n >> 4) * gqn + (gi >> 2)) * 16 + (n & 15)];
-    const GroupScale gs = make_group_scale((sw >> (8 * (gi & 3))) & 0xFFu);
+    const uint32_t sw = scales[((size_t)(n >> 4) * gqn + (gi >> fsh)) * 16 + (n & 15)];
+    const GroupScale gs = group_scale_from_word(sw, gi, zp_form);
     v4i first, second;
     expand_cell(q, gs, first, second);
     int8_t *dst = w_s8 + (size_t)kk * 32 * N + n;
@@ -179,13 +252,27 @@ hipError_t launch_pack(const int8_t *w4, const uint8_t *s2, int K, int N, int gr
     return hipGetLastError();
 }
 
-hipError_t launch_unpack(const void *qweight, const void *scales, int K, int N, int group, int8_t *w_s8,
-                         hipStream_t st)
+hipError_t launch_pack_zp(const uint8_t *u4, const uint8_t *s2, const uint8_t *zp, int K, int N, int group,
+                          void *qweight, void *scales_zp, int32_t *bad_count, hipStream_t st)
+{
+    const int ng = K / group;
+    dim3 block(256);
+    dim3 grid_c((N + 255) / 256, K / 32);
+    hipLaunchKernelGGL(pack_cells_zp_kernel, grid_c, block, 0, st, u4, s2, zp, K, N, group, (uint4 *)qweight,
+                       bad_count);
+    dim3 grid_s((N + 255) / 256, (ng + 1) / 2);
+    hipLaunchKernelGGL(pack_scales_zp_kernel, grid_s, block, 0, st, s2, zp, ng, N, (uint32_t *)scales_zp,
+                       bad_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(const void *qweight, const void *scales, int zp_form, int K, int N, int group,
+                         int8_t *w_s8, hipStream_t st)
 {
     dim3 block(256);
     dim3 grid((N + 255) / 256, K / 32);
     hipLaunchKernelGGL(unpack_kernel, grid, block, 0, st, (const uint4 *)qweight, (const uint32_t *)scales,
-                       K, N, group, w_s8);
+                       zp_form, K, N, group, w_s8);
     return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 15 and len(set(names)) == 15
+    assert len(names) == 20 and len(set(names)) == 20
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -82,6 +82,13 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4(good, good, odd, good, good, good, 1, 16, 128, 128, None, 0, None) == -3
     assert L.dgq_pack_weights(good, good, 128, 16, 128, odd, good, None, None) == -3
     assert L.dgq_pack_weights(good, good, 128, 16, 128, good, good, 0x10002, None) == -3
+    # general operands
+    assert L.dgq_pack_weights_zp(good, good, None, 128, 16, 128, good, good, None, None) == -1
+    assert L.dgq_pack_weights_zp(good, good, good, 128, 24, 128, good, good, None, None) == -2
+    assert L.dgq_pack_weights_zp(good, odd, good, 128, 16, 128, good, good, None, None) == -3
+    assert L.dgq_linear_a8w4_zp(good, good, good, None, good, good, 1, 16, 128, 128, None, 0, None) == -1
+    assert L.dgq_linear_a8w4_zp_acc(good, good, good, good, 0, 16, 128, 128, None, 0, None) == -2
+    assert L.dgq_unpack_weights_zp(good, good, 128, 16, 32, good, None) == -2
     # measurement aids
     assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
     assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2
@@ -109,6 +116,11 @@ def test_linear_plan_names(dgq):
         assert dgq.linear_plan(64, 8192, 8192, 128).startswith("linear_stream_kernel<4, 128, ")
     finally:
         dgq.force_path(old)
+
+
+def test_packed_sizes_zp(dgq):
+    assert dgq.packed_sizes_zp(4096, 4096, 128) == (4096 * 4096 // 2, 256 * 16 * 64)
+    assert dgq.packed_sizes_zp(384, 48, 128) == (384 * 48 // 2, 3 * 2 * 64)     # 3 groups padded to 4
 
 
 def test_force_path_selector(dgq):

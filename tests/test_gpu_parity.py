@@ -387,3 +387,131 @@ def test_tiled_path_activation_tensor_larger_than_4_gib(dgq, torch):
     for m in (0, 1, 127, 128, 999, 1000, 32767, 32768, 32769, M - 1):
         row = np.roll(base[m % 1000], m // 1000 + 1).astype(np.int64)
         assert np.array_equal(host(acc[m]).astype(np.int64), row @ ws8), "token %d" % m
+
+
+# ----------------------------------------------------------------------------
+# General operands of Eq. 2: unsigned nibbles, per-group zero points, S2 up to 127
+# ----------------------------------------------------------------------------
+def _zp_operands(K, N, g, seed):
+    """Random (u4, s2, zp, s1) that satisfy the INT8 constraint of Eq. 4: small scales with any
+    nibble, large scales with nibbles close to the zero point; every value of the ranges occurs."""
+    rng = np.random.default_rng([seed, 77])
+    ng = K // g
+    s2 = np.where(rng.random((ng, N)) < 0.5, rng.integers(1, 9, (ng, N)), rng.integers(9, 128, (ng, N))).astype(np.uint8)
+    zp = rng.integers(0, 16, (ng, N)).astype(np.uint8)
+    room = 127 // s2.astype(int)
+    lo = np.maximum(0, zp.astype(int) - room)
+    hi = np.minimum(15, zp.astype(int) + room)
+    r = rng.random((K, N))
+    u4 = (np.repeat(lo, g, axis=0) + np.floor(r * np.repeat(hi - lo + 1, g, axis=0))).astype(np.uint8)
+    s1 = rng.uniform(1e-4, 4e-4, N).astype(np.float32)
+    return u4, s2, zp, s1
+
+
+@pytest.mark.parametrize("K,N,g", [(128, 16, 128), (384, 48, 128), (384, 272, 64), (1024, 4096 + 16, 64)])
+def test_pack_zp_bytes_and_unpack(dgq, torch, K, N, g):
+    u4, s2, zp, s1 = _zp_operands(K, N, g, K + N)
+    pw, bad = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), g, return_bad=True)
+    oq, osc, obad = oracle.pack_zp(u4, s2, zp, g)
+    assert bad == obad == 0
+    assert np.array_equal(host(pw.qweight), oq) and np.array_equal(host(pw.scales), osc)
+    ws8, obad = oracle.expand_zp(u4, s2, zp, g)
+    assert obad == 0 and np.array_equal(host(dgq.unpack_weights(pw)), ws8)
+
+
+def test_pack_zp_counts_rule_breakers(dgq, torch):
+    K, N, g = 128, 16, 64
+    u4 = np.zeros((K, N), np.uint8)
+    s2 = np.ones((2, N), np.uint8)
+    zp = np.zeros((2, N), np.uint8)
+    s2[0, 0], s2[1, 1], zp[0, 2], u4[5, 3] = 0, 128, 16, 16
+    s2[1, 4], u4[70, 4] = 20, 7                                     # 140 leaves INT8
+    pw, bad = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp),
+                                  dev(torch, np.ones(N, np.float32)), g, return_bad=True)
+    oq, osc, obad = oracle.pack_zp(u4, s2, zp, g)
+    assert bad == obad == 5
+    assert np.array_equal(host(pw.qweight), oq) and np.array_equal(host(pw.scales), osc)
+
+
+def _acc_case_zp(dgq, torch, M, K, N, g, seed, path=0):
+    u4, s2, zp, s1 = _zp_operands(K, N, g, seed)
+    xq, _ = workloads.integer_activations(M, K, seed)
+    pw = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), g)
+    old = dgq.force_path(path)
+    try:
+        acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
+    finally:
+        dgq.force_path(old)
+    ws8, bad = oracle.expand_zp(u4, s2, zp, g)
+    assert bad == 0
+    oacc, wrapped = oracle.gemm_i32(xq, ws8)
+    assert wrapped == 0
+    assert np.array_equal(acc, oacc), "mismatch at %s" % (np.argwhere(acc != oacc)[:4].tolist(),)
+
+
+@pytest.mark.parametrize("M,K,N,g", [
+    (1, 128, 16, 128), (16, 384, 48, 128), (7, 2176, 272, 64), (16, 11008, 528, 128), (3, 22016, 64, 64),
+    (5, 640, 131200 // 8, 128),
+])
+def test_acc_bit_exact_zp_decode_kernel(dgq, torch, M, K, N, g):
+    _acc_case_zp(dgq, torch, M, K, N, g, seed=M + K, path=1)
+
+
+@pytest.mark.parametrize("M,K,N,g", [
+    (17, 128, 16, 128), (64, 4096, 512, 128), (40, 2048, 272, 64), (33, 384, 1040, 128),     # 64-token tiles, split K
+    (130, 384, 320, 64), (300, 640, 1040, 128),                                              # 64-token tiles
+    (4000, 256, 4096 + 16, 64), (2000, 384, 8192 - 64, 128),                                 # 128-token tiles, both widths
+])
+def test_acc_bit_exact_zp_tiled_kernel(dgq, torch, M, K, N, g):
+    _acc_case_zp(dgq, torch, M, K, N, g, seed=M + N, path=0 if M > 16 else 2)
+
+
+def test_zp_form_with_zero_point_8_equals_signed_nibble_form(dgq, torch):
+    M, K, N, g = 48, 1152, 272, 128
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 3)
+    xq, _ = workloads.integer_activations(M, K, 3)
+    a = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    b = dgq.pack_weights_zp(dev(torch, (w4 + 8).astype(np.uint8)), dev(torch, s2),
+                            dev(torch, np.full_like(s2, 8)), dev(torch, s1), g)
+    assert np.array_equal(host(a.qweight), host(b.qweight))
+    for path in (1, 2):
+        if path == 1:
+            xs = xq[:16]
+        else:
+            xs = xq
+        old = dgq.force_path(path)
+        try:
+            assert np.array_equal(host(dgq.linear_a8w4_acc(dev(torch, xs), a)), host(dgq.linear_a8w4_acc(dev(torch, xs), b)))
+        finally:
+            dgq.force_path(old)
+
+
+def test_zp_form_is_refused_by_the_forced_streaming_kernel(dgq, torch):
+    u4, s2, zp, s1 = _zp_operands(128, 16, 128, 1)
+    pw = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), 128)
+    xq, _ = workloads.integer_activations(20, 128, 1)
+    old = dgq.force_path(3)
+    try:
+        with pytest.raises(dgq.DGQError) as e:
+            dgq.linear_a8w4_acc(dev(torch, xq), pw)
+        assert e.value.status == -2
+    finally:
+        dgq.force_path(old)
+
+
+@pytest.mark.parametrize("M,K,N,g", [(8, 1024, 256, 128), (64, 1024, 512, 64), (200, 512, 272, 128)])
+def test_whole_path_with_grid_searched_weights(dgq, torch, M, K, N, g):
+    """fp16 activations -> dgq_quant_act -> dgq_linear_a8w4_zp on weights quantized by the two-phase grid
+    search of Section 3.3 (here by the oracle), against the oracle's Eq. 2."""
+    x = workloads.activations(M, K, M + N)
+    W = workloads.weights(K, N, M + N)
+    u4, zp, s2, s1 = oracle.quantize_weights_grid(W, g, n_alpha=21, step=0.025)
+    pw, bad = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), g, return_bad=True)
+    assert bad == 0
+    xq, sx = dgq.quant_act(dev(torch, x))
+    out = host(dgq.linear_a8w4(xq, sx, pw))
+    oxq, osx = oracle.quant_act(x)
+    assert np.array_equal(host(xq), oxq) and np.array_equal(host(sx), osx)
+    oout, oacc = oracle.linear_a8w4_zp(oxq, osx, u4, s2, zp, s1, g)
+    assert np.array_equal(host(dgq.linear_a8w4_acc(xq, pw)), oacc)
+    assert_fp16_close(out, oout)
