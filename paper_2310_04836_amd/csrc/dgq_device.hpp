@@ -46,14 +46,30 @@ __device__ __forceinline__ GroupScale make_group_scale(uint32_t s2, uint32_t zp)
 // The scale array has one of two forms (LinearArgs::zp): 0 = one byte per group and column,
 // the group scale S2, with the constant zero point 8; 1 = two bytes, S2 then the zero point.
 // A 32-bit word therefore holds 4 or 2 consecutive groups of one column.
-__device__ __forceinline__ int scale_word_shift(int zp_form) { return zp_form ? 1 : 2; }
-__device__ __forceinline__ GroupScale group_scale_from_word(uint32_t word, int gi, int zp_form)
+// Everything that depends on the form is a handful of uniform constants, so that the kernels'
+// loops contain no branch on it.
+struct ScaleForm {
+    int fsh;         // log2 of the groups per word: word index of group gi is gi >> fsh
+    uint32_t gmask;  // groups per word - 1
+    uint32_t width;  // bits per group
+    uint32_t zmask;  // 0xFF if the entry carries a zero point, else 0
+    uint32_t zor;    // the constant zero point 8 if it does not
+};
+__device__ __forceinline__ ScaleForm scale_form(int zp_form)
 {
-    if (zp_form) {
-        const uint32_t e = word >> (16 * (gi & 1));
-        return make_group_scale(e & 0xFFu, (e >> 8) & 0xFFu);
-    }
-    return make_group_scale((word >> (8 * (gi & 3))) & 0xFFu, 8u);
+    ScaleForm f;
+    f.fsh = zp_form ? 1 : 2;
+    f.gmask = zp_form ? 1u : 3u;
+    f.width = zp_form ? 16u : 8u;
+    f.zmask = zp_form ? 0xFFu : 0u;
+    f.zor = zp_form ? 0u : 8u;
+    return f;
+}
+__device__ __forceinline__ uint32_t scale_entry_shift(int gi, const ScaleForm &f) { return ((uint32_t)gi & f.gmask) * f.width; }
+__device__ __forceinline__ GroupScale group_scale_at(uint32_t word, uint32_t shift, const ScaleForm &f)
+{
+    const uint32_t e = word >> shift;
+    return make_group_scale(e & 0xFFu, ((e >> 8) & f.zmask) | f.zor);
 }
 
 __device__ __forceinline__ uint32_t scale_bytes(uint32_t four_nibbles_in_bytes, const GroupScale &g)

@@ -28,8 +28,9 @@ constexpr int kWaves = 16;
 // them after the weight loop, so that the loop itself contains no global stores.
 constexpr int kMaxTilesPerWg = 32;
 
-template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
-__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, int ksplit, int32_t *partial)
+// ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes (compile-time).
+template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP>
+__device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int32_t *partial)
 {
     __shared__ int red[2][kWaves][256];
     __shared__ int sums[kMaxTilesPerWg][256];
@@ -40,8 +41,8 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
     const int kb = lane >> 4;
     const int steps = a.K >> 7;
     const int tiles = a.N >> 4;
-    const int fsh = scale_word_shift(a.zp);  // groups per scale word: 4 (S2 bytes) or 2 (S2, ZP pairs)
-    const int gqn = ((a.K / G) + (1 << fsh) - 1) >> fsh;
+    const ScaleForm sf = scale_form(ZP ? 1 : 0);  // scale words hold 4 groups (S2 bytes) or 2 (S2, ZP pairs)
+    const int gqn = ((a.K / G) + (1 << sf.fsh) - 1) >> sf.fsh;
 
     // This workgroup's part of K; wavefront w takes steps [p0 + w*SPW, p0 + (w+1)*SPW) of it.
     // Only the last active wavefront can be short; wavefronts past the end only help reduce.
@@ -92,8 +93,8 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
             const int s = i < nst ? sb + i : sb;
             const int gi = (G == 128) ? s : 2 * s + (kb >> 1);
             qoff[i] = s * 64 + lane;
-            soff[i] = (gi >> fsh) * 16 + j;
-            ssh[i] = gi;
+            soff[i] = (gi >> sf.fsh) * 16 + j;
+            ssh[i] = (int)scale_entry_shift(gi, sf);
         }
 
         uint4 q[PF][SPW];
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
         v4i acc = v4i{0, 0, 0, 0};                                                                   \
         _Pragma("unroll") for (int i = 0; i < SPW; ++i)                                              \
         {                                                                                            \
-            const GroupScale gs = group_scale_from_word(sw[P][i], ssh[i], a.zp);                     \
+            const GroupScale gs = group_scale_at(sw[P][i], ssh[i], sf);                              \
             v4i b0, b1;                                                                              \
             expand_cell(q[P][i], gs, b0, b1);                                                        \
             acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, xa[i][0]), b0, acc, 0, 0, 0); \
@@ -195,6 +196,17 @@ __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a
     }
 }
 
+template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, int ksplit, int32_t *partial)
+{
+    decode_body<SPW, PF, G, ACC, PARTIAL, false>(a, ksplit, partial);
+}
+template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_zp_kernel(LinearArgs a, int ksplit, int32_t *partial)
+{
+    decode_body<SPW, PF, G, ACC, PARTIAL, true>(a, ksplit, partial);
+}
+
 // Adds the K-split partial tiles and runs the epilogue; four consecutive columns per thread
 // (N is a multiple of 16, so a group of four never crosses a row).
 template <bool ACC>
@@ -249,8 +261,16 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
     int32_t *partial = static_cast<int32_t *>(workspace);
     const bool acc = a.acc_out != nullptr;
     if (ksplit > 1) {
-        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
+        if (a.zp)
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
+        else
+            hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
         return launch_splitk_finalize(a, ksplit, partial, st);
+    } else if (a.zp) {
+        if (acc)
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, 1, partial);
+        else
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, 1, partial);
     } else if (acc) {
         hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, 1, partial);
     } else {

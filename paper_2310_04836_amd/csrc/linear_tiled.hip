@@ -86,8 +86,10 @@ __device__ __forceinline__ void arrive(v4u &a, v4u &b, v4u &c, v4u &d, uint32_t 
 // NW wavefronts per workgroup, each owning 64 output channels of the (32*MI) x (64*NW) tile;
 // ST stages of operands in flight or in use.  ksplit workgroups share one tile, each walking its
 // own part of K; then (and in the test hook) the raw INT32 sums go to a.acc_out, slice kpart.
-template <int G, int NW, int MI, int ST, bool ACC>
-__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
+// ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes; a compile-time choice, so that the
+// signed-nibble form pays nothing for the general one.
+template <int G, int NW, int MI, int ST, bool ACC, bool ZP>
+__device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int tiles_n, int ksplit)
 {
     constexpr int kStages = ST;
     constexpr int BM = 32 * MI;
@@ -122,7 +124,8 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     const int kb = lane >> 5;
     const int li = lane & 31;
     const int steps = a.K >> 7;
-    const int fsh = scale_word_shift(a.zp);  // groups per scale word: 4 (S2 bytes) or 2 (S2, ZP pairs)
+    const ScaleForm sf = scale_form(ZP ? 1 : 0);  // scale words hold 4 groups (S2 bytes) or 2 (S2, ZP pairs)
+    const int fsh = sf.fsh;
     const int gqn = ((a.K / G) + (1 << fsh) - 1) >> fsh;
 
     // ---- weight stream: two 32-column tiles per wavefront ------------------------------------
@@ -212,11 +215,15 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     v4i af[2][MI];  // [group parity][mi]
     v4i bf[2][2];  // [group parity][nj]
     GroupScale gsn[2];
+    // (a group of 128 k is a whole stage, a group of 64 k half of one: new scales are needed at
+    // k-group 0 and, for G = 64, at k-group 2)
 #define DGQ_SCALES(PN, SN, GRPN)                                                                      \
     do {                                                                                              \
-        const int gi_ = (G == 128) ? (SN) : 2 * (SN) + ((GRPN) >> 1);                                 \
-        _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) gsn[nj] =                                    \
-            group_scale_from_word(sw[PN][nj], gi_, a.zp);                                            \
+        if ((GRPN) == 0 || (G == 64 && (GRPN) == 2)) {                                                \
+            const int gi_ = (G == 128) ? (SN) : 2 * (SN) + ((GRPN) >> 1);                             \
+            const uint32_t sh_ = scale_entry_shift(gi_, sf);                                          \
+            _Pragma("unroll") for (int nj = 0; nj < 2; ++nj) gsn[nj] = group_scale_at(sw[PN][nj], sh_, sf); \
+        }                                                                                             \
     } while (0)
     // prepares piece C of group GRPN (stage set PN) into parity PARN
 #define DGQ_PREP(PARN, C, PN, GRPN)                                                                   \
@@ -387,6 +394,17 @@ __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, 
     }
 }
 
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
+{
+    tiled_body<G, NW, MI, ST, ACC, false>(a, tiles_m, tiles_n, ksplit);
+}
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_zp_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
+{
+    tiled_body<G, NW, MI, ST, ACC, true>(a, tiles_m, tiles_n, ksplit);
+}
+
 }  // namespace
 
 TiledPlan tiled_plan(int M, int N, int K)
@@ -446,13 +464,22 @@ static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *worksp
         // the slices and applies the scales
         LinearArgs part = a;
         part.acc_out = static_cast<int32_t *>(workspace);
-        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
+        if (a.zp)
+            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
+        else
+            hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
         return launch_splitk_finalize(a, ksplit, part.acc_out, st);
     }
-    if (a.acc_out)
+    if (a.zp) {
+        if (a.acc_out)
+            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+        else
+            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+    } else if (a.acc_out) {
         hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
-    else
+    } else {
         hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+    }
     return hipGetLastError();
 }
 

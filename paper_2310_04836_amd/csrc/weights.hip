@@ -213,13 +213,14 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint4 *__restrict__ q
     if (n >= N) return;
     const int ksteps = K >> 7;
     const int ng = K / group;
-    const int fsh = scale_word_shift(zp_form);
+    const ScaleForm sf = scale_form(zp_form);
+    const int fsh = sf.fsh;
     const int gqn = (ng + (1 << fsh) - 1) >> fsh;
     const size_t cell = ((size_t)(n >> 4) * ksteps + (kk >> 2)) * 64 + (size_t)(kk & 3) * 16 + (n & 15);
     const uint4 q = qweight[cell];
     const int gi = (kk * 32) / group;
     const uint32_t sw = scales[((size_t)(n >> 4) * gqn + (gi >> fsh)) * 16 + (n & 15)];
-    const GroupScale gs = group_scale_from_word(sw, gi, zp_form);
+    const GroupScale gs = group_scale_at(sw, scale_entry_shift(gi, sf), sf);
     v4i first, second;
     expand_cell(q, gs, first, second);
     int8_t *dst = w_s8 + (size_t)kk * 32 * N + n;

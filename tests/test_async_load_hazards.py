@@ -107,9 +107,10 @@ def tiled_asm(tmp_path_factory):
 
 
 def test_no_register_is_touched_while_an_async_load_into_it_is_in_flight(tiled_asm):
-    kernels, problems = check_asm(tiled_asm, "linear_tiled_kernel")
-    assert kernels == 16
-    assert not problems, "\n".join(problems[:10])
+    for name in ("linear_tiled_kernel", "linear_tiled_zp_kernel"):     # signed-nibble and zero-point forms
+        kernels, problems = check_asm(tiled_asm, name)
+        assert kernels == 16
+        assert not problems, "\n".join(problems[:10])
 
 
 def test_checker_sees_a_planted_hazard():
