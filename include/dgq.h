@@ -182,6 +182,27 @@ DGQ_API dgq_status dgq_packed_sizes_zp(int K, int N, int group, size_t *qweight_
 DGQ_API dgq_status dgq_pack_weights_zp(const uint8_t *w_u4, const uint8_t *s2, const uint8_t *zp, int K, int N,
                                int group, void *qweight, void *scales_zp, int32_t *bad_count, void *stream);
 
+/*
+ * Two-phase grid search quantizer (Section 3.3, Eq. 3 to Eq. 5, clip of Eq. 4) with the
+ * weight-only objective ||W - Q(W)||^2 (no calibration activations).  alpha runs over
+ * 1, 1 - step, ..., 1 - (n_alpha - 1)*step, in both phases; the first minimum wins.
+ *   phase 1, per group and column:  lo = min(min W, 0), hi = max(max W, 0),
+ *       s = alpha*(hi - lo)/15, ZP = clamp(round(-(alpha*lo)/s), 0, 15),
+ *       u = clamp(round(W/s) + ZP, 0, 15); the best alpha gives S' and ZP
+ *   phase 2, per column:  s1 = alpha * max_j S'_j / 15, S2 = clamp(round(S'/s1), 1, 127),
+ *       u = clamp(round(W/(s1*S2)) + ZP, ZP - floor(127/S2), ZP + floor(127/S2)) within [0, 15]
+ * fp32, IEEE division, ties to even, sums in increasing k; an all-zero group gets S' = 0 and
+ * ZP = 0, an all-zero column s1 = 1, S2 = 1.
+ *   W      in  [K][N] fp16 (raw bits)
+ *   w_u4   out [K][N] uint8;  zp, s2 out [K/group][N] uint8;  s1 out [N] float
+ *   workspace  at least (K/group)*N*4 bytes (the S' of phase 1)
+ * Errors: DGQ_ERR_RANGE if n_alpha is outside [1, 1024] or the smallest alpha is not positive.
+ * The outputs are the inputs of dgq_pack_weights_zp.
+ */
+DGQ_API dgq_status dgq_quantize_weights_grid(const uint16_t *W, int K, int N, int group, int n_alpha, float step,
+                                     uint8_t *w_u4, uint8_t *zp, uint8_t *s2, float *s1,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test hook: W_s8[K][N] = S2 * (W_u4 - ZP) from the packed form. */
 DGQ_API dgq_status dgq_unpack_weights_zp(const void *qweight, const void *scales_zp, int K, int N, int group,
                                  int8_t *w_s8, void *stream);

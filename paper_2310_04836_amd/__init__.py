@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -52,6 +52,7 @@ def _load() -> ctypes.CDLL:
     L.dgq_quant_act.argtypes = [vp, i, i, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_quantize_weights_grid.argtypes = [vp, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
     L.dgq_packed_sizes_zp.argtypes = [i, i, i, psz, psz]
     L.dgq_pack_weights_zp.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, vp]
     L.dgq_unpack_weights_zp.argtypes = [vp, vp, i, i, i, vp, vp]
@@ -63,7 +64,7 @@ def _load() -> ctypes.CDLL:
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
                  "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan", "dgq_packed_sizes_zp", "dgq_pack_weights_zp",
-                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc"):
+                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid"):
         getattr(L, name).restype = i
     return L
 
@@ -190,6 +191,21 @@ def quantize_weights_rtn(W: torch.Tensor, group: int):
     _check(lib.dgq_quantize_weights_rtn(_ptr(W), K, N, group, _ptr(w4), _ptr(s2), _ptr(s1), _stream()),
            "dgq_quantize_weights_rtn")
     return w4, s2, s1
+
+
+def quantize_weights_grid(W: torch.Tensor, group: int, n_alpha: int = 51, step: float = 0.01):
+    """dgq_quantize_weights_grid: fp16 [K,N] -> (u4 uint8 [K,N], zp uint8 [K/group,N], s2 uint8 [K/group,N],
+    s1 float32 [N]) by the two-phase grid search of Section 3.3."""
+    _dev(W, torch.float16, "W")
+    K, N = W.shape
+    u4 = torch.empty((K, N), dtype=torch.uint8, device=W.device)
+    zp = torch.empty((K // group, N), dtype=torch.uint8, device=W.device)
+    s2 = torch.empty((K // group, N), dtype=torch.uint8, device=W.device)
+    s1 = torch.empty(N, dtype=torch.float32, device=W.device)
+    ws = torch.empty((K // group) * N, dtype=torch.float32, device=W.device)
+    _check(lib.dgq_quantize_weights_grid(_ptr(W), K, N, group, n_alpha, step, _ptr(u4), _ptr(zp), _ptr(s2), _ptr(s1),
+                                         _ptr(ws), ws.numel() * 4, _stream()), "dgq_quantize_weights_grid")
+    return u4, zp, s2, s1
 
 
 def quant_act(x: torch.Tensor, xq: torch.Tensor = None, sx: torch.Tensor = None):

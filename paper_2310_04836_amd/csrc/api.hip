@@ -176,6 +176,20 @@ dgq_status dgq_quantize_weights_rtn(const uint16_t *W, int K, int N, int group, 
     return hip_result(dgq::launch_quantize_rtn(W, K, N, group, w4, s2, s1, static_cast<hipStream_t>(stream)));
 }
 
+dgq_status dgq_quantize_weights_grid(const uint16_t *W, int K, int N, int group, int n_alpha, float step,
+                                     uint8_t *w_u4, uint8_t *zp, uint8_t *s2, float *s1, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    if (!W || !w_u4 || !zp || !s2 || !s1 || !workspace) return DGQ_ERR_NULL;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (n_alpha < 1 || n_alpha > 1024 || !(step >= 0.0f) || !((float)(n_alpha - 1) * step < 1.0f)) return DGQ_ERR_RANGE;
+    if (workspace_bytes < (size_t)(K / group) * (size_t)N * sizeof(float)) return DGQ_ERR_WORKSPACE;
+    if (!aligned16(W) || !aligned16(w_u4) || !aligned16(zp) || !aligned16(s2) || !aligned16(s1) || !aligned16(workspace))
+        return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_quantize_grid(W, K, N, group, n_alpha, step, w_u4, zp, s2, s1,
+                                                static_cast<float *>(workspace), static_cast<hipStream_t>(stream)));
+}
+
 dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, void *stream)
 {
     if (!x || !xq || !sx) return DGQ_ERR_NULL;

@@ -97,6 +97,8 @@ __device__ __forceinline__ void expand_cell(const uint4 &q, const GroupScale &g,
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_quantize_rtn(const uint16_t *W, int K, int N, int group, int8_t *w4, uint8_t *s2,
                                float *s1, hipStream_t st);
+hipError_t launch_quantize_grid(const uint16_t *W, int K, int N, int group, int n_alpha, float step, uint8_t *u4,
+                                uint8_t *zp, uint8_t *s2, float *s1, float *sprime, hipStream_t st);
 hipError_t launch_pack(const int8_t *w4, const uint8_t *s2, int K, int N, int group, void *qweight,
                        void *scales, int32_t *bad_count, hipStream_t st);
 hipError_t launch_unpack(const void *qweight, const void *scales, int zp_form, int K, int N, int group,

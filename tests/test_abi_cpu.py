@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 20 and len(set(names)) == 20
+    assert len(names) == 21 and len(set(names)) == 21
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -89,6 +89,13 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4_zp(good, good, good, None, good, good, 1, 16, 128, 128, None, 0, None) == -1
     assert L.dgq_linear_a8w4_zp_acc(good, good, good, good, 0, 16, 128, 128, None, 0, None) == -2
     assert L.dgq_unpack_weights_zp(good, good, 128, 16, 32, good, None) == -2
+    # grid-search quantizer: alpha grid and workspace are checked on the host
+    import ctypes
+    f = ctypes.c_float
+    assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 0, f(0.01), good, good, good, good, good, 1 << 20, None) == -4
+    assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.02), good, good, good, good, good, 1 << 20, None) == -4
+    assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.01), good, good, good, good, good, 63, None) == -5
+    assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.01), good, good, good, good, None, 64, None) == -1
     # measurement aids
     assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
     assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2

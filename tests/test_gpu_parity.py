@@ -515,3 +515,21 @@ def test_whole_path_with_grid_searched_weights(dgq, torch, M, K, N, g):
     oout, oacc = oracle.linear_a8w4_zp(oxq, osx, u4, s2, zp, s1, g)
     assert np.array_equal(host(dgq.linear_a8w4_acc(xq, pw)), oacc)
     assert_fp16_close(out, oout)
+
+
+@pytest.mark.parametrize("K,N,g,n_alpha,step", [(256, 64, 128, 51, 0.01), (512, 272, 64, 21, 0.025), (1024, 48, 128, 1, 0.0),
+                                                (384, 1040, 128, 11, 0.05)])
+def test_grid_search_quantizer_bit_exact(dgq, torch, K, N, g, n_alpha, step):
+    W = workloads.weights(K, N, K + N)
+    W[:, 3] = 0                                    # an all-zero column
+    W[g:2 * g, 5] = 0                              # an all-zero group
+    W[:, 7] = np.abs(W[:, 7])                      # one-sided groups
+    W[::37, 9] *= 8                                # outliers: clipping pays
+    u4, zp, s2, s1 = dgq.quantize_weights_grid(dev(torch, W), g, n_alpha, step)
+    ou, oz, os2, os1 = oracle.quantize_weights_grid(W, g, n_alpha, step)
+    assert np.array_equal(host(zp), oz)
+    assert np.array_equal(host(s1), os1)
+    assert np.array_equal(host(s2), os2)
+    assert np.array_equal(host(u4), ou)
+    pw, bad = dgq.pack_weights_zp(u4, s2, zp, s1, g, return_bad=True)
+    assert bad == 0                                # the clip of Eq. 4 keeps every product inside INT8
