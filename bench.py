@@ -53,10 +53,13 @@ def act_quant_bytes(M, K):
     return 2 * M * K + M * K + 4 * M
 
 
+SCALE_BYTES = 1   # bytes per (group, column) in the scale array: 1 = S2, 2 = (S2, ZP); set by --format
+
+
 def algorithmic_bytes(M, K, N, g):
-    """Bytes one linear launch must move: packed weights + group scales + channel scales,
-    quantized activations + token scales, fp16 output."""
-    return K * N // 2 + (K // g) * N + 4 * N + M * K + 4 * M + 2 * M * N
+    """Bytes one linear launch must move: packed weights + group scales (and zero points) + channel
+    scales, quantized activations + token scales, fp16 output."""
+    return K * N // 2 + SCALE_BYTES * (K // g) * N + 4 * N + M * K + 4 * M + 2 * M * N
 
 
 def main():
@@ -65,6 +68,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--format", default="s4", choices=["s4", "zp"],
+                    help="weight operands: s4 = signed nibbles, S2 <= 15, RTN quantizer (the benchmark configs); "
+                         "zp = unsigned nibbles with per-group zero points, S2 <= 127, two-phase grid search")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-breakdown", action="store_true")
@@ -81,6 +87,8 @@ def main():
     import paper_2310_04836_amd as dgq
     import workloads
 
+    global SCALE_BYTES
+    SCALE_BYTES = 2 if args.format == "zp" else 1
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     size, Ms, g = WORKLOADS[args.workload]
@@ -93,16 +101,26 @@ def main():
     layer_bytes = sum(K * N // 2 + (K // g) * N for K, N in shapes.values())
     ncopies = max(2, -(-2 * MALL_BYTES // layer_bytes))
     ncopies = -(-ncopies // len(Ms)) * len(Ms)      # a whole number of steps per rotation
-    packed = {}
+    packed, qerr = {}, {}
     for name, (K, N) in shapes.items():
         W = torch.from_numpy(workloads.weights(K, N, seed)).to(dev)
-        w4, s2, s1 = dgq.quantize_weights_rtn(W, g)
-        pw = dgq.pack_weights(w4, s2, s1, g)
+        if args.format == "zp":
+            w4, zp, s2, s1 = dgq.quantize_weights_grid(W, g)
+            pw, nbad = dgq.pack_weights_zp(w4, s2, zp, s1, g, return_bad=True)
+            assert nbad == 0
+            del zp
+        else:
+            w4, s2, s1 = dgq.quantize_weights_rtn(W, g)
+            pw = dgq.pack_weights(w4, s2, s1, g)
+        # relative error of the quantized weights (context for the quantizer, not a timed quantity)
+        deq = dgq.unpack_weights(pw).float() * s1[None, :]
+        qerr[name] = float(((deq - W.float()) ** 2).sum() / (W.float() ** 2).sum())
+        del deq
         torch.cuda.synchronize()
         del W, w4, s2
         copies = [pw]
         for _ in range(ncopies - 1):
-            copies.append(dgq.PackedWeight(pw.qweight.clone(), pw.scales.clone(), pw.s1.clone(), K, N, g))
+            copies.append(dgq.PackedWeight(pw.qweight.clone(), pw.scales.clone(), pw.s1.clone(), K, N, g, pw.zp_form))
         packed[name] = copies
     acts, bufs = {}, {}
     for M in Ms:
@@ -198,7 +216,10 @@ def main():
     for M in Ms:
         for name, (K, N) in shapes.items():
             pair_sec[(M, name)] = time_linear(M, name, reps_pair)
-            groups.setdefault(dgq.linear_plan(M, N, K, g), []).append((M, name))
+            sym = dgq.linear_plan(M, N, K, g)
+            if args.format == "zp":      # same plan, the kernels of the zero-point form
+                sym = sym.replace("_kernel<", "_zp_kernel<")
+            groups.setdefault(sym, []).append((M, name))
     kernel_name = max(groups, key=lambda k: sum(pair_sec[p] for p in groups[k]))
     dpairs = groups[kernel_name]
     dsec = sum(pair_sec[p] for p in dpairs) / len(dpairs)
@@ -327,26 +348,35 @@ def main():
         import oracle
         qcache = {}
         t_cpu, n_steps, done_bytes = 0.0, 0, 0
-        while t_cpu < 10.0 and n_steps < 12:
+        while t_cpu < 10.0 and n_steps < 400:
             for M in Ms:
                 for name, (K, N) in shapes.items():
                     # bounded sample for large layers: a contiguous slice of output channels
                     ncol = N
                     if 2 * M * K * N > 4e9:
                         ncol = max(256, int(4e9 / (2 * M * K)) // 256 * 256)
+                    if args.format == "zp":
+                        ncol = min(ncol, 512)      # the oracle's (untimed) grid search is slow
                     if (name, ncol) not in qcache:
                         Wn = workloads.weights(K, N, seed)[:, :ncol]
-                        qcache[(name, ncol)] = oracle.quantize_weights_rtn(Wn, g)
-                    w4, s2, s1 = qcache[(name, ncol)]
+                        qcache[(name, ncol)] = (oracle.quantize_weights_grid(Wn, g) if args.format == "zp"
+                                                else oracle.quantize_weights_rtn(Wn, g))
                     x = acts[(M, name)].cpu().numpy()
                     t1 = time.perf_counter()
-                    oracle.forward(x, w4, s2, s1, g)
+                    if args.format == "zp":
+                        u4_, zp_, s2_, s1_ = qcache[(name, ncol)]
+                        xq_, sx_ = oracle.quant_act(x)
+                        oracle.linear_a8w4_zp(xq_, sx_, u4_, s2_, zp_, s1_, g)
+                    else:
+                        w4, s2, s1 = qcache[(name, ncol)]
+                        oracle.forward(x, w4, s2, s1, g)
                     t_cpu += time.perf_counter() - t1
                     done_bytes += algorithmic_bytes(M, K, ncol, g) + act_quant_bytes(M, K)
             n_steps += 1
         cpu = {"value": done_bytes / t_cpu / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
                "sample": "%d whole step(s) of the same workload%s, %.1f s of CPU time" %
-                         (n_steps, "" if max(Ms) <= 64 else " (output channels of large layers cut to a contiguous slice)", t_cpu)}
+                         (n_steps, "" if (max(Ms) <= 64 and args.format != "zp") else
+                          " (output channels of large layers cut to a contiguous slice)", t_cpu)}
         log("cpu oracle: %.3f GB/s on %d threads" % (cpu["value"], cpu["cores"]))
 
     result = {
@@ -357,11 +387,14 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
                    "layers_per_step": list(shapes), "weight_copies": ncopies,
+                   "weight_format": ("unsigned nibbles, per-group zero points, S2 <= 127, two-phase grid search"
+                                     if args.format == "zp" else "signed nibbles, S2 <= 15, RTN"),
                    "launch": "eager" if args.no_graph else "hip_graph"},
         "tops": step_ops / (elapsed / args.steps) / 1e12,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "a16_fp16_gemm_ms_per_step": a16_ms if breakdown else None,
+        "weight_quantization_rel_sq_error": qerr,
         "measured_read_bandwidth": probe,
         "measured_mfma_rate": mfma_probe,
         "breakdown": breakdown,
