@@ -74,7 +74,7 @@ DGQ_API dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_byt
  * Scratch needed by dgq_linear_a8w4 / dgq_linear_a8w4_acc for this problem (host
  * function).  May be 0, in which case `workspace` may be NULL.  Non-zero where several
  * workgroups split K and exchange INT32 partial sums: M <= 16 with very long K, and
- * 16 < M <= 64 (at most 8 * M * N * 4 bytes).
+ * 16 < M <= 256 for shapes with few output-channel tiles (at most 8 * M * N * 4 bytes).
  */
 DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
 
@@ -140,8 +140,8 @@ DGQ_API dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, fl
  *   workspace         scratch of at least dgq_linear_workspace_bytes(); contents
  *                     undefined before and after
  * M <= 16 takes a weight-streaming split-K kernel, larger M a tiled MFMA kernel (64-token
- * tiles with K split over workgroups up to M = 64 and for shapes with few tiles, 128-token
- * tiles otherwise); all give the same INT32 sums.
+ * tiles, with K split over workgroups where that is faster, up to M = 64 and for shapes with
+ * few tiles; 128-token tiles otherwise); all give the same INT32 sums.
  */
 DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight,
                            const void *scales, const float *s1, uint16_t *out,

@@ -414,20 +414,32 @@ TiledPlan tiled_plan(int M, int N, int K)
     TiledPlan p;
     p.nw = 4, p.mi = 4, p.st = 3, p.ksplit = 1;
     const long long tiles_n = (N + 255) / 256;
-    if (M <= 64) {
-        // One 64-token tile per 256 columns: the weights are read once and the layer is bound by
-        // that stream.  Six stages keep 5 x 16 KiB of it in flight per workgroup, and K is split
-        // until there are about two workgroups per CU (at least 8 stages per part, at most 8
-        // parts: every part writes and re-reads M x N INT32 partial sums).
-        p.mi = 2, p.st = 6;
-        long long ks = (2 * kCus) / tiles_n;
-        if (ks > 8) ks = 8;
-        if (ks > steps / 8) ks = steps / 8;
-        if (ks < 1) ks = 1;
-        p.ksplit = (int)ks;
-        return p;
-    }
     const long long tiles_64 = (long long)((M + 63) / 64) * tiles_n;
+    if (M <= 256 && tiles_64 < 2 * kCus) {
+        // Few 64-token tiles: the weights are read about once and the layer is bound by that
+        // stream and by how many stages one workgroup walks in sequence.  Splitting K over
+        // several workgroups per tile shortens the walk but every part writes and re-reads
+        // M x N INT32 partial sums and a second kernel adds them.  The split (1, 2, 4 or 8 parts,
+        // at least 4 stages each) is the one a small model fitted to measurements predicts to be
+        // fastest: 0.5 us per stage and round of workgroups, 3.5 us for the second kernel, 0.45 us
+        // per MB of partial sums written and read.
+        int best = 1;
+        double best_t = 0.0;
+        for (int ks = 1; ks <= 8; ks *= 2) {
+            if (ks > 1 && steps / ks < 4) break;
+            const double rounds = (double)((tiles_64 * ks + 2 * kCus - 1) / (2 * kCus));
+            double t = 0.5 * ((steps + ks - 1) / ks) * rounds;
+            if (ks > 1) t += 3.5 + 0.45 * (8e-6 * ks * (double)M * (double)N);
+            if (ks == 1 || t < best_t) best = ks, best_t = t;
+        }
+        if (M <= 64 || best > 1) {
+            // six stages keep 5 x 16 KiB of weights in flight per workgroup
+            p.ksplit = best;
+            p.mi = 2;
+            p.st = 6;
+            return p;
+        }
+    }
     if (tiles_64 <= kCus) {
         // Even 64-token tiles leave every workgroup a CU of its own: twice as many SIMDs work as
         // with 128-token tiles.  (With more tiles than CUs the smaller tile loses: it expands

@@ -214,10 +214,11 @@ def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
 # workgroups whose INT32 partial sums meet in the workspace.
 @pytest.mark.parametrize("M,K,N,g", [
     (17, 128, 16, 128),          # one stage, no split
-    (64, 4096, 512, 128),        # 2 tiles x 4 parts of 8 stages
-    (40, 2048, 272, 64),         # 2 parts, ragged M and N
+    (64, 4096, 512, 128),        # 2 tiles x 8 parts of 4 stages
+    (40, 2048, 272, 64),         # 4 parts, ragged M and N
     (33, 8192, 1040, 128),       # 8 parts
     (64, 11008, 528, 64),        # 86 stages in 8 parts of 10 or 11
+    (128, 11008, 528, 128), (200, 4096, 272, 64),   # 64 < M <= 256 with few tiles: split as well
     (48, 1408, 4096 + 64, 128),  # 11 stages, one part: tail of every length mod 6 is in this list
     (64, 896, 64, 64), (64, 1024, 64, 128), (20, 1152, 64, 128), (20, 1280, 64, 64), (20, 1536, 64, 128),
 ])
@@ -228,7 +229,7 @@ def test_acc_bit_exact_mid_m(dgq, torch, M, K, N, g):
 def test_tiled_split_workspace_contract(dgq, torch):
     M, K, N, g = 64, 4096, 512, 128
     need = dgq.linear_workspace_bytes(M, N, K, g)
-    assert need == 4 * M * N * 4
+    assert need == 8 * M * N * 4
     w4, s2, s1 = workloads.integer_weights(K, N, g, 2)
     xq, sx = workloads.integer_activations(M, K, 2)
     pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
@@ -359,7 +360,7 @@ def test_llama65b_shapes(dgq, torch, g):
 
 
 def test_llama65b_qkv_mid_and_large_m(dgq, torch):
-    """M = 64: 64-token tiles, six stages, K split five ways; M = 2048: the 128 x 512 tile (its grid of
+    """M = 64: 64-token tiles, six stages, K split two ways; M = 2048: the 128 x 512 tile (its grid of
     16 x 48 fills the CUs in whole rounds)."""
     K, N = workloads.LLAMA_SHAPES["65b"]["qkv"]
     assert dgq.linear_plan(64, N, K, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
