@@ -43,6 +43,7 @@ def _L():
         _lib.dgq_oracle_threads.restype = ctypes.c_int
         _lib.dgq_oracle_expand_zp.restype = ctypes.c_long
         _lib.dgq_oracle_pack_zp.restype = ctypes.c_long
+        _lib.dgq_oracle_quant_act_static.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_float, ctypes.c_void_p]
         _lib.dgq_oracle_quantize_grid.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                   ctypes.c_int, ctypes.c_float, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -264,3 +265,15 @@ def linear_a8w4_zp(xq, sx, u4, s2, zp, s1, group: int):
     if wrapped:
         raise OverflowError("%d INT32 accumulators would wrap" % wrapped)
     return epilogue(acc, sx, s1), acc
+
+
+def quant_act_static(x, scale: float):
+    """Static tensor-wise INT8 activation quantizer ("S" scheme of Section 4.1 / Table 5; Eq. 1, symmetric).
+
+    x: fp16/fp32 [M, K], scale > 0.  Returns (xq int8 [M,K], sx float32 [M] filled with the scale)."""
+    xf = _c(x, np.float32)
+    M, K = xf.shape
+    assert scale > 0
+    xq = np.empty((M, K), np.int8)
+    _L().dgq_oracle_quant_act_static(_p(xf), M * K, ctypes.c_float(scale), _p(xq))
+    return xq, np.full(M, np.float32(scale), np.float32)

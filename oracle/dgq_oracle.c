@@ -514,3 +514,19 @@ void dgq_oracle_unpack_zp(const uint8_t *qweight, const uint8_t *scales_zp, int 
         }
     }
 }
+
+/*
+ * Static tensor-wise activation quantizer (the "S" scheme of Section 4.1 and Table 5): one
+ * scale s for the whole tensor, fixed offline, symmetric form of Eq. 1 with 8 bits:
+ *     xq = clamp(round(x / s), -127, 127)          one IEEE division per element, ties to even
+ * Values beyond 127 * s saturate (with a dynamic scale they cannot occur).  s must be positive.
+ */
+void dgq_oracle_quant_act_static(const float *x, long count, float s, int8_t *xq)
+{
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < count; ++i) {
+        float q = rintf(x[i] / s);
+        q = clampf(q, -127.0f, 127.0f);
+        xq[i] = (int8_t)q;
+    }
+}

@@ -350,3 +350,34 @@ def test_config0_end_to_end_properties():
     out0, *_ = oracle.forward(x0, w4, s2, s1, g)
     ref0 = x0.astype(np.float64) @ W.astype(np.float64)
     assert np.linalg.norm(out0.astype(np.float64) - ref0) / np.linalg.norm(ref0) < 0.12
+
+
+# ---------------------------------------------------------------- static activation scale
+def test_quant_act_static_hand_values():
+    # scale 0.5: 0.74/0.5 = 1.48 -> 1; 0.76 -> 1.52 -> 2; ties to even: 1.25 -> 2.5 -> 2, 1.75 -> 3.5 -> 4;
+    # saturation: 100 -> 200 -> 127, -64 -> -128 -> -127; signs are symmetric
+    x = np.array([[0.74, 0.76, 1.25, 1.75, 100.0, -64.0, -0.76, 0.0]], np.float32)
+    xq, sx = oracle.quant_act_static(x, 0.5)
+    assert xq.tolist() == [[1, 2, 2, 4, 127, -127, -2, 0]] and sx.tolist() == [0.5]
+
+
+def test_quant_act_static_equals_dynamic_when_the_scale_is_exact():
+    # a row whose absmax is 127 * 2^-5 has the dynamic scale 2^-5 exactly, and both x * (127/a) and
+    # x / s are then exact scalings by 32: the two quantizers must agree
+    rng = np.random.default_rng(8)
+    x = rng.normal(0, 1, (6, 512)).astype(np.float16).astype(np.float32)
+    x = np.clip(x, -3.9, 3.9)
+    x[:, 17] = 127 * 2.0 ** -5
+    xd, sd = oracle.quant_act(x)
+    xs, ss = oracle.quant_act_static(x, 2.0 ** -5)
+    assert (sd == np.float32(2.0 ** -5)).all() and np.array_equal(xd, xs) and np.array_equal(sd, ss)
+
+
+def test_quant_act_static_error_bound_and_saturation():
+    rng = np.random.default_rng(9)
+    x = rng.normal(0, 1, (4, 2048)).astype(np.float16).astype(np.float32)
+    s = np.float32(0.02)
+    xq, _ = oracle.quant_act_static(x, float(s))
+    inside = np.abs(x) <= 127 * s
+    assert (np.abs(x - s * xq)[inside] <= 0.5 * s * (1 + 1e-6)).all()
+    assert (np.abs(xq[~inside]) == 127).all() and (np.sign(xq[~inside]) == np.sign(x[~inside])).all()
