@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--format", default="s4", choices=["s4", "zp"],
                     help="weight operands: s4 = signed nibbles, S2 <= 15, RTN quantizer (the benchmark configs); "
                          "zp = unsigned nibbles with per-group zero points, S2 <= 127, two-phase grid search")
+    ap.add_argument("--act", default="dynamic", choices=["dynamic", "static"],
+                    help="activation quantizer: per-token dynamic (the benchmark configs) or one static "
+                         "tensor-wise scale fixed before the timed region (Section 4.1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-breakdown", action="store_true")
@@ -135,9 +138,14 @@ def main():
     log("inputs ready in %.1fs: %s, M=%s, g=%d, %d weight copies of %.1f MB" %
         (time.time() - t0, size, Ms, g, ncopies, layer_bytes / 1e6))
 
+    static_scale = {k: float(v.float().abs().max().item() / 127.0) for k, v in acts.items()} if args.act == "static" else {}
+
     def one_pair(M, name, copy):
         xq, sx, out, ws = bufs[(M, name)]
-        dgq.quant_act(acts[(M, name)], xq, sx)
+        if args.act == "static":
+            dgq.quant_act_static(acts[(M, name)], static_scale[(M, name)], xq, sx)
+        else:
+            dgq.quant_act(acts[(M, name)], xq, sx)
         dgq.linear_a8w4(xq, sx, packed[name][copy % ncopies], out, ws)
 
     def step_body(i):
@@ -365,11 +373,16 @@ def main():
                     t1 = time.perf_counter()
                     if args.format == "zp":
                         u4_, zp_, s2_, s1_ = qcache[(name, ncol)]
-                        xq_, sx_ = oracle.quant_act(x)
+                        xq_, sx_ = (oracle.quant_act_static(x, static_scale[(M, name)]) if args.act == "static"
+                                    else oracle.quant_act(x))
                         oracle.linear_a8w4_zp(xq_, sx_, u4_, s2_, zp_, s1_, g)
                     else:
                         w4, s2, s1 = qcache[(name, ncol)]
-                        oracle.forward(x, w4, s2, s1, g)
+                        if args.act == "static":
+                            xq_, sx_ = oracle.quant_act_static(x, static_scale[(M, name)])
+                            oracle.linear_a8w4(xq_, sx_, w4, s2, s1, g)
+                        else:
+                            oracle.forward(x, w4, s2, s1, g)
                     t_cpu += time.perf_counter() - t1
                     done_bytes += algorithmic_bytes(M, K, ncol, g) + act_quant_bytes(M, K)
             n_steps += 1
@@ -387,6 +400,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
                    "layers_per_step": list(shapes), "weight_copies": ncopies,
+                   "activation_quantizer": args.act,
                    "weight_format": ("unsigned nibbles, per-group zero points, S2 <= 127, two-phase grid search"
                                      if args.format == "zp" else "signed nibbles, S2 <= 15, RTN"),
                    "launch": "eager" if args.no_graph else "hip_graph"},

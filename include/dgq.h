@@ -130,6 +130,16 @@ DGQ_API dgq_status dgq_quantize_weights_rtn(const uint16_t *W, int K, int N, int
 DGQ_API dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, void *stream);
 
 /*
+ * Static tensor-wise INT8 activation quantizer (the "S" scheme of Section 4.1 and Table 5;
+ * symmetric form of Eq. 1): one positive scale for the whole tensor, fixed offline,
+ *   xq = clamp(round(x / scale), -127, 127)   (one IEEE division per element, ties to even)
+ * and sx[m] = scale for every token, so that dgq_linear_a8w4 takes the result unchanged.
+ * Values beyond 127*scale saturate.  DGQ_ERR_RANGE unless 0 < scale < 3e38.
+ */
+DGQ_API dgq_status dgq_quant_act_static(const uint16_t *x, int M, int K, float scale, int8_t *xq, float *sx,
+                                void *stream);
+
+/*
  * Fused A8W4 linear: in-register INT4->INT8 expansion, INT8 MFMA GEMM with INT32
  * accumulation over all of K, scale epilogue (all three lines of Eq. 2):
  *   out[m][n] = fp16( (sx[m] * s1[n]) * (float) sum_k xq[m][k] * (s2[k/group][n] * w4[k][n]) )

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -50,6 +50,7 @@ def _load() -> ctypes.CDLL:
     L.dgq_unpack_weights.argtypes = [vp, vp, i, i, i, vp, vp]
     L.dgq_quantize_weights_rtn.argtypes = [vp, i, i, i, vp, vp, vp, vp]
     L.dgq_quant_act.argtypes = [vp, i, i, vp, vp, vp]
+    L.dgq_quant_act_static.argtypes = [vp, i, i, ctypes.c_float, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_quantize_weights_grid.argtypes = [vp, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
@@ -64,7 +65,7 @@ def _load() -> ctypes.CDLL:
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
                  "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan", "dgq_packed_sizes_zp", "dgq_pack_weights_zp",
-                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid"):
+                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid", "dgq_quant_act_static"):
         getattr(L, name).restype = i
     return L
 
@@ -224,6 +225,18 @@ def _workspace(M, N, K, group, device):
     """Scratch of the size the library asks for (None when it needs none)."""
     nbytes = linear_workspace_bytes(M, N, K, group)
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
+def quant_act_static(x: torch.Tensor, scale: float, xq: torch.Tensor = None, sx: torch.Tensor = None):
+    """dgq_quant_act_static: fp16 [M,K] and one scale -> (xq int8 [M,K], sx float32 [M] = scale)."""
+    _dev(x, torch.float16, "x")
+    M, K = x.shape
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if sx is None:
+        sx = torch.empty(M, dtype=torch.float32, device=x.device)
+    _check(lib.dgq_quant_act_static(_ptr(x), M, K, scale, _ptr(xq), _ptr(sx), _stream()), "dgq_quant_act_static")
+    return xq, sx
 
 
 def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch.Tensor = None,

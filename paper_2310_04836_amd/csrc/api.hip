@@ -226,6 +226,15 @@ static dgq_status linear_acc(const int8_t *xq, const void *qweight, const void *
     return run_linear(a, workspace, workspace_bytes, stream);
 }
 
+dgq_status dgq_quant_act_static(const uint16_t *x, int M, int K, float scale, int8_t *xq, float *sx, void *stream)
+{
+    if (!x || !xq || !sx) return DGQ_ERR_NULL;
+    if (M < 1 || K < 128 || K > 131072 || (K % 128) != 0) return DGQ_ERR_SHAPE;
+    if (!(scale > 0.0f) || !(scale < 3.0e38f)) return DGQ_ERR_RANGE;
+    if (!aligned16(x) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_quant_act_static(x, M, K, scale, xq, sx, static_cast<hipStream_t>(stream)));
+}
+
 dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight, const void *scales,
                            const float *s1, uint16_t *out, int M, int N, int K, int group, void *workspace,
                            size_t workspace_bytes, void *stream)

@@ -113,7 +113,44 @@ __global__ __launch_bounds__(kThreads) void quant_act_kernel(const uint16_t *__r
     }
 }
 
+// Static tensor-wise scale (the "S" scheme of Section 4.1 / Table 5; symmetric form of Eq. 1 with
+// 8 bits): xq = clamp(round(x / s), -127, 127) with one IEEE division per element, and every
+// token's scale is s.  One thread per eight values; no reduction.
+__global__ __launch_bounds__(kThreads) void quant_act_static_kernel(const uint16_t *__restrict__ x, size_t nvec,
+                                                                    int M, float s, int8_t *__restrict__ xq,
+                                                                    float *__restrict__ sx)
+{
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < (size_t)M) sx[i] = s;
+    if (i >= nvec) return;
+    const uint4 v = reinterpret_cast<const uint4 *>(x)[i];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t b[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            float q = rintf(half_bits_to_float((w[k] >> (16 * h)) & 0xFFFFu) / s);
+            q = fminf(fmaxf(q, -127.0f), 127.0f);
+            b[2 * k + h] = (uint32_t)((int)q) & 0xFFu;
+        }
+    }
+    uint2 r;
+    r.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+    r.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
+    reinterpret_cast<uint2 *>(xq)[i] = r;
+}
+
 }  // namespace
+
+hipError_t launch_quant_act_static(const uint16_t *x, int M, int K, float s, int8_t *xq, float *sx, hipStream_t st)
+{
+    const size_t nvec = (size_t)M * (size_t)K / 8;   // K is a multiple of 128, so M <= nvec
+    const size_t blocks = (nvec + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(quant_act_static_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, nvec, M, s, xq, sx);
+    return hipGetLastError();
+}
 
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st)
 {

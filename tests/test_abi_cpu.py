@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 21 and len(set(names)) == 21
+    assert len(names) == 22 and len(set(names)) == 22
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -96,6 +96,10 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.02), good, good, good, good, good, 1 << 20, None) == -4
     assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.01), good, good, good, good, good, 63, None) == -5
     assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.01), good, good, good, good, None, 64, None) == -1
+    assert L.dgq_quant_act_static(good, 1, 128, f(0.0), good, good, None) == -4
+    assert L.dgq_quant_act_static(good, 1, 128, f(-1.0), good, good, None) == -4
+    assert L.dgq_quant_act_static(good, 1, 100, f(0.1), good, good, None) == -2
+    assert L.dgq_quant_act_static(None, 1, 128, f(0.1), good, good, None) == -1
     # measurement aids
     assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
     assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2

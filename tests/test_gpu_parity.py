@@ -534,3 +534,26 @@ def test_grid_search_quantizer_bit_exact(dgq, torch, K, N, g, n_alpha, step):
     assert np.array_equal(host(u4), ou)
     pw, bad = dgq.pack_weights_zp(u4, s2, zp, s1, g, return_bad=True)
     assert bad == 0                                # the clip of Eq. 4 keeps every product inside INT8
+
+
+@pytest.mark.parametrize("M,K", [(1, 128), (7, 1024), (300, 4096), (64, 11008)])
+def test_quant_act_static_bit_exact(dgq, torch, M, K):
+    x = workloads.activations(M, K, M + K)
+    scale = float(np.float32(np.abs(x.astype(np.float32)).max() / 127 / 3))     # a third of the range: saturates
+    xq, sx = dgq.quant_act_static(dev(torch, x), scale)
+    oxq, osx = oracle.quant_act_static(x, scale)
+    assert np.array_equal(host(xq), oxq) and np.array_equal(host(sx), osx)
+    assert (np.abs(oxq) == 127).any()
+
+
+def test_static_activation_scale_through_the_linear(dgq, torch):
+    M, K, N, g = 40, 1024, 272, 128
+    x = workloads.activations(M, K, 5)
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 5)
+    scale = float(np.float32(np.abs(x.astype(np.float32)).max() / 127))
+    xq, sx = dgq.quant_act_static(dev(torch, x), scale)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    out = host(dgq.linear_a8w4(xq, sx, pw))
+    oxq, osx = oracle.quant_act_static(x, scale)
+    oout, _ = oracle.linear_a8w4(oxq, osx, w4, s2, s1, g)
+    assert_fp16_close(out, oout)
