@@ -1,5 +1,8 @@
-// Weight-streaming A8W4 linear for decode-size M (M <= 64): the layer is bound by reading
-// the 4-bit weights once from HBM, so the kernel is organised around that stream.
+// Weight-streaming A8W4 linear for M <= 64, the simplest of the three GEMM kernels.  It is not
+// chosen by M any more (the decode kernel serves M <= 16 and the tiled kernel everything above:
+// this kernel re-reads the activations at every step and is bound by that L2 traffic for
+// M > 16); it stays selectable as an independently written check of the other two, for the
+// signed-nibble operands only.
 //
 //   - One workgroup owns one tile of 16 output channels; its W wavefronts split K between
 //     them (split-K inside the workgroup) and combine their INT32 partial sums through LDS,

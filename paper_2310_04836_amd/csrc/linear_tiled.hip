@@ -1,20 +1,23 @@
-// Tiled A8W4 linear for prefill-size M, bound by the INT8 matrix cores.
+// Tiled A8W4 linear for M > 16: bound by the INT8 matrix cores at prefill sizes, by the weight
+// stream up to M = 64.
 //
-//   - Workgroup tile 128 tokens x 256 or 512 output channels (4 or 8 wavefronts, two per
-//     SIMD), K walked in stages of 128.  The wavefronts split the output channels (64 each),
-//     so every packed weight is expanded to INT8 exactly once per workgroup.
+//   - Workgroup tile (32*MI) tokens x (64*NW) output channels: 128 x 256 (four wavefronts, two
+//     workgroups per CU) by default, 128 x 512 or 64 x 256 where the plan says so; K walked in
+//     stages of 128.  The wavefronts split the output channels (64 each), so every packed
+//     weight is expanded to INT8 exactly once per workgroup.
 //   - Weights never touch LDS: each lane loads 16-byte cells of qweight straight into VGPRs
-//     (a cell = 32 consecutive k of one column) two stages ahead of their use, expands them
-//     with the group scale (second line of Eq. 2) and feeds them as the B operand of
-//     v_mfma_i32_32x32x32_i8.
-//   - The INT8 activation tile goes from global memory directly into a three-stage LDS ring
-//     (global_load_lds_dwordx4, no registers in between), two stages ahead.  A row is 128
+//     (a cell = 32 consecutive k of one column) ST - 1 stages ahead of their use (ST = 3, or 6
+//     where the weight stream is the bound), expands them with the group scale (second line
+//     of Eq. 2) and feeds them as the B operand of v_mfma_i32_32x32x32_i8.
+//   - The INT8 activation tile goes from global memory directly into an ST-stage LDS ring
+//     (global_load_lds_dwordx4, no registers in between), as far ahead.  A row is 128
 //     bytes = eight 16-byte units; unit u of row r is stored at unit u ^ ((r/2) % 8), so that
 //     the 128-bit reads of sixteen consecutive rows (one read phase) fall on sixteen different
 //     16-byte slots of the 256-byte bank line.  Lane (kb, i) reads as the A
 //     operand the same k that the weight cell of lane (kb, j) holds.
-//   - INT32 accumulation over all of K in AGPRs (third line of Eq. 2), then the scale
-//     epilogue (first line of Eq. 2) and one rounding to fp16.
+//   - INT32 accumulation over all of K (third line of Eq. 2), then the scale epilogue (first
+//     line of Eq. 2) and one rounding to fp16; or, when several workgroups split K, raw INT32
+//     partial sums for a second kernel that adds them and scales.
 //   - Workgroups are numbered so that each XCD (workgroup id modulo 8) walks a contiguous
 //     range of tiles, ordered in bands of eight column tiles: the 64 workgroups resident on
 //     one XCD cover about 8 x 8 tiles and share their operands in that XCD's L2.
@@ -32,9 +35,9 @@ constexpr int wait_vm(int n, bool lgkm0) { return (n & 15) | ((n >> 4) << 14) | 
 typedef __attribute__((address_space(3))) void *lptr_t;
 
 // All global loads of the main loop are written as inline assembly, and all waiting for them
-// is explicit (one s_waitcnt vmcnt(N) + barrier at the top of each stage).
+// is explicit (one s_waitcnt vmcnt(N) + barrier per stage).
 //
-// Why: the stage prefetch runs two stages ahead, both for weights (into registers) and for
+// Why: the stage prefetch runs several stages ahead, both for weights (into registers) and for
 // activations (straight into LDS).  The compiler makes every LDS read that follows a
 // direct-to-LDS load it knows about wait for ALL outstanding vector loads (vmcnt(0)), which
 // would serialise the prefetch behind the current stage.  With the loads invisible to its
