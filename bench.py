@@ -39,7 +39,7 @@ WORKLOADS = {
 # (FETCH_SIZE reads 0.5 GiB per GiB read: x2.0; WRITE_SIZE x1.0).  Figures and commands are in
 # profiles/; a workload that has not been profiled reports null.
 TRAFFIC_BYTES = {
-    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14147.0 + 175.0) * 1024,
+    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14135.6 + 175.0) * 1024,
     ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"): (2.0 * 75912.5 + 34112.0) * 1024,
 }
 
