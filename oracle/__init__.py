@@ -44,6 +44,7 @@ def _L():
         _lib.dgq_oracle_expand_zp.restype = ctypes.c_long
         _lib.dgq_oracle_pack_zp.restype = ctypes.c_long
         _lib.dgq_oracle_quant_act_static.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_float, ctypes.c_void_p]
+        _lib.dgq_oracle_smooth_scales.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
         _lib.dgq_oracle_quantize_grid.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                   ctypes.c_int, ctypes.c_float, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -277,3 +278,24 @@ def quant_act_static(x, scale: float):
     xq = np.empty((M, K), np.int8)
     _L().dgq_oracle_quant_act_static(_p(xf), M * K, ctypes.c_float(scale), _p(xq))
     return xq, np.full(M, np.float32(scale), np.float32)
+
+
+def smooth_scales(X, pct: float = 0.005):
+    """Percentile clipping smoothing scale k [K] (Section 3.4, Eq. 6) from calibration activations X [M, K]."""
+    Xf = _c(X, np.float32)
+    M, K = Xf.shape
+    k = np.empty(K, np.float32)
+    _L().dgq_oracle_smooth_scales(_p(Xf), M, K, ctypes.c_float(pct), _p(k))
+    return k
+
+
+def smooth_apply(W, X, k):
+    """Moves the scale from activations to weights: returns (fp16(diag(k) W), fp16(X / k)) (Section 3.4)."""
+    Wf, Xf, kf = _c(W, np.float32), _c(X, np.float32), _c(k, np.float32)
+    K, N = Wf.shape
+    M = Xf.shape[0]
+    assert Xf.shape[1] == K and kf.shape == (K,)
+    Wo, Xo = np.empty_like(Wf), np.empty_like(Xf)
+    _L().dgq_oracle_smooth_apply(_p(Wf), _p(Xf), _p(kf), M, K, N, _p(Wo), _p(Xo))
+    with np.errstate(over="ignore"):
+        return Wo.astype(np.float16), Xo.astype(np.float16)

@@ -530,3 +530,53 @@ void dgq_oracle_quant_act_static(const float *x, long count, float s, int8_t *xq
         xq[i] = (int8_t)q;
     }
 }
+
+/*
+ * Percentile clipping smoothing (Section 3.4, Eq. 6), offline:
+ *     z_j = max_m |X[m][j]|                                   absolute maximum of input channel j
+ *     t   = the r-th largest of z, r = ceil(pct * K)          the "top pct" threshold, nearest rank
+ *     k_j = max(z_j / t, 1)                                   clamp(., low = 1)
+ * so the fewer than r channels above the threshold get k_j > 1 and every other channel 1.
+ * If t is zero (no activations), every k_j is 1.  X is [M][K] fp32; k is [K].
+ * The scale is then moved from the activations to the weights: X' = X / k, W' = diag(k) W.
+ */
+static int cmp_desc(const void *a, const void *b)
+{
+    const float x = *(const float *)a, y = *(const float *)b;
+    return x < y ? 1 : (x > y ? -1 : 0);
+}
+
+void dgq_oracle_smooth_scales(const float *X, int M, int K, float pct, float *k)
+{
+    float *z = (float *)malloc(sizeof(float) * (size_t)K);
+    float *sorted = (float *)malloc(sizeof(float) * (size_t)K);
+    for (int j = 0; j < K; ++j) {
+        float a = 0.0f;
+        for (int m = 0; m < M; ++m) {
+            const float v = fabsf(X[(size_t)m * K + j]);
+            if (v > a) a = v;
+        }
+        z[j] = sorted[j] = a;
+    }
+    qsort(sorted, (size_t)K, sizeof(float), cmp_desc);
+    int r = (int)ceilf(pct * (float)K);
+    if (r < 1) r = 1;
+    if (r > K) r = K;
+    const float t = sorted[r - 1];
+    for (int j = 0; j < K; ++j) {
+        const float q = t > 0.0f ? z[j] / t : 1.0f;
+        k[j] = q < 1.0f ? 1.0f : q;
+    }
+    free(z);
+    free(sorted);
+}
+
+/* W'[j][n] = k_j * W[j][n] and X'[m][j] = X[m][j] / k_j in fp32 (the caller rounds to fp16). */
+void dgq_oracle_smooth_apply(const float *W, const float *X, const float *k, int M, int K, int N,
+                             float *Wout, float *Xout)
+{
+    for (int j = 0; j < K; ++j)
+        for (int n = 0; n < N; ++n) Wout[(size_t)j * N + n] = k[j] * W[(size_t)j * N + n];
+    for (int m = 0; m < M; ++m)
+        for (int j = 0; j < K; ++j) Xout[(size_t)m * K + j] = X[(size_t)m * K + j] / k[j];
+}

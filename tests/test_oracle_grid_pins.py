@@ -237,3 +237,36 @@ def test_grid_search_beats_direct_rounding_on_gaussian_weights():
     w4, r2, r1 = oracle.quantize_weights_rtn(W, g)
     e_rtn = mse(oracle.expand(w4, r2, g)[0], r1)
     assert e_grid < e_minmax and e_grid < e_rtn
+
+
+# ---------------------------------------------------------------- Eq. 6 smoothing
+def test_smooth_scales_hand_example():
+    # 400 channels, pct 0.5 % -> r = 2: the threshold is the second largest channel maximum.
+    # Channel maxima: 40 at j=7, 10 at j=3, 4 at j=11, 2 elsewhere -> t = 10, k = 4 at j=7, 1 everywhere else
+    X = np.full((3, 400), 2.0, np.float32)
+    X[1, 7], X[2, 3], X[0, 11] = -40.0, 10.0, 4.0
+    k = oracle.smooth_scales(X, 0.005)
+    assert k[7] == 4.0 and (np.delete(k, 7) == 1.0).all()
+
+
+def test_smooth_scales_properties_and_product_is_preserved():
+    rng = np.random.default_rng(12)
+    M, K, N = 64, 4096, 32
+    X = rng.normal(0, 1, (M, K)).astype(np.float32)
+    hot = rng.choice(K, 41, replace=False)
+    X[:, hot] *= 20                                                   # 1 % outlier channels
+    k = oracle.smooth_scales(X, 0.005)
+    r = int(np.ceil(0.005 * K))
+    z = np.abs(X).max(axis=0)
+    assert (k >= 1).all() and (k > 1).sum() == r - 1                  # strictly above the r-th largest
+    assert set(np.nonzero(k > 1)[0]) <= set(hot)
+    assert np.isclose((z / k).max(), np.sort(z)[-r])                  # outliers are clipped to the threshold
+    W = rng.normal(0, 0.02, (K, N)).astype(np.float32)
+    lhs = (X.astype(np.float64) / k) @ (W.astype(np.float64) * k[:, None])
+    assert np.allclose(lhs, X.astype(np.float64) @ W.astype(np.float64), rtol=1e-12, atol=1e-12)
+    Wo, Xo = oracle.smooth_apply(W, X, k)
+    assert np.array_equal(Wo, (W * k[:, None]).astype(np.float16)) and np.array_equal(Xo[:, k == 1], X[:, k == 1].astype(np.float16))
+
+
+def test_smooth_scales_without_activations_is_the_identity():
+    assert (oracle.smooth_scales(np.zeros((2, 256), np.float32)) == 1).all()
