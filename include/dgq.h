@@ -130,6 +130,28 @@ DGQ_API dgq_status dgq_quantize_weights_rtn(const uint16_t *W, int K, int N, int
 DGQ_API dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, void *stream);
 
 /*
+ * Percentile clipping smoothing (Section 3.4, Eq. 6), offline.  From calibration activations
+ *   z_j = max_m |X[m][j]|,  t = the r-th largest z with r = ceil(pct * K) (nearest rank),
+ *   k_j = max(z_j / t, 1)                                (all ones if t is 0)
+ * so fewer than r outlier channels get a scale above 1 (the paper uses pct = 0.005).
+ *   X   in  [M][K] fp16 (raw bits), M <= 65535;  k out [K] float
+ *   workspace  at least K*4 bytes (the channel maxima)
+ * Errors: DGQ_ERR_RANGE unless 0 < pct <= 1.
+ */
+DGQ_API dgq_status dgq_smooth_scales(const uint16_t *X, int M, int K, float pct, float *k,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Moves the smoothing scale from the activations into the weights (Section 3.4):
+ *   Wout[j][n] = fp16(k_j * W[j][n])   if W is not NULL ([K][N] fp16)
+ *   Xout[m][j] = fp16(X[m][j] / k_j)   if X is not NULL ([M][K] fp16, M <= 65535)
+ * fp32 arithmetic, one rounding to fp16; K <= 65535.  In a model the division is folded into the
+ * producer of X; the entry point exists so that the identity (X/k)(kW) = XW can be exercised.
+ */
+DGQ_API dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k, int M, int K, int N,
+                            uint16_t *Wout, uint16_t *Xout, void *stream);
+
+/*
  * Static tensor-wise INT8 activation quantizer (the "S" scheme of Section 4.1 and Table 5;
  * symmetric form of Eq. 1): one positive scale for the whole tensor, fixed offline,
  *   xq = clamp(round(x / scale), -127, 127)   (one IEEE division per element, ties to even)

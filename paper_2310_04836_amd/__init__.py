@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -51,6 +51,8 @@ def _load() -> ctypes.CDLL:
     L.dgq_quantize_weights_rtn.argtypes = [vp, i, i, i, vp, vp, vp, vp]
     L.dgq_quant_act.argtypes = [vp, i, i, vp, vp, vp]
     L.dgq_quant_act_static.argtypes = [vp, i, i, ctypes.c_float, vp, vp, vp]
+    L.dgq_smooth_scales.argtypes = [vp, i, i, ctypes.c_float, vp, vp, sz, vp]
+    L.dgq_smooth_apply.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_quantize_weights_grid.argtypes = [vp, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
@@ -65,7 +67,7 @@ def _load() -> ctypes.CDLL:
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
                  "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan", "dgq_packed_sizes_zp", "dgq_pack_weights_zp",
-                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid", "dgq_quant_act_static"):
+                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid", "dgq_quant_act_static", "dgq_smooth_scales", "dgq_smooth_apply"):
         getattr(L, name).restype = i
     return L
 
@@ -225,6 +227,30 @@ def _workspace(M, N, K, group, device):
     """Scratch of the size the library asks for (None when it needs none)."""
     nbytes = linear_workspace_bytes(M, N, K, group)
     return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+
+
+def smooth_scales(X: torch.Tensor, pct: float = 0.005) -> torch.Tensor:
+    """dgq_smooth_scales: calibration activations fp16 [M,K] -> smoothing scale k float32 [K] (Eq. 6)."""
+    _dev(X, torch.float16, "X")
+    M, K = X.shape
+    k = torch.empty(K, dtype=torch.float32, device=X.device)
+    ws = torch.empty(K, dtype=torch.float32, device=X.device)
+    _check(lib.dgq_smooth_scales(_ptr(X), M, K, pct, _ptr(k), _ptr(ws), K * 4, _stream()), "dgq_smooth_scales")
+    return k
+
+
+def smooth_apply(W: torch.Tensor, X: torch.Tensor, k: torch.Tensor):
+    """dgq_smooth_apply: (fp16(diag(k) W), fp16(X / k)); either input may be None."""
+    _dev(k, torch.float32, "k")
+    K = k.numel()
+    Wout = Xout = None
+    M = N = 0
+    if W is not None:
+        _dev(W, torch.float16, "W"); N = W.shape[1]; Wout = torch.empty_like(W)
+    if X is not None:
+        _dev(X, torch.float16, "X"); M = X.shape[0]; Xout = torch.empty_like(X)
+    _check(lib.dgq_smooth_apply(_ptr(W), _ptr(X), _ptr(k), M, K, N, _ptr(Wout), _ptr(Xout), _stream()), "dgq_smooth_apply")
+    return Wout, Xout
 
 
 def quant_act_static(x: torch.Tensor, scale: float, xq: torch.Tensor = None, sx: torch.Tensor = None):

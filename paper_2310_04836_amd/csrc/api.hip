@@ -1,6 +1,7 @@
 // extern "C" boundary of libdgq.so: argument validation on the host, then one launcher.
 // Every check happens before anything is enqueued.
 #include <atomic>
+#include <cmath>
 #include <cstdio>
 
 #include "dgq_device.hpp"
@@ -224,6 +225,33 @@ static dgq_status linear_acc(const int8_t *xq, const void *qweight, const void *
     dgq::LinearArgs a{xq, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
                       nullptr, nullptr, acc_out, M, N, K, group, zp_form};
     return run_linear(a, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_smooth_scales(const uint16_t *X, int M, int K, float pct, float *k, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    if (!X || !k || !workspace) return DGQ_ERR_NULL;
+    if (M < 1 || M > 65535 || K < 128 || K > 131072 || (K % 128) != 0) return DGQ_ERR_SHAPE;
+    if (!(pct > 0.0f) || !(pct <= 1.0f)) return DGQ_ERR_RANGE;
+    if (workspace_bytes < (size_t)K * sizeof(float)) return DGQ_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(k) || !aligned16(workspace)) return DGQ_ERR_ALIGN;
+    int r = (int)std::ceil(pct * (float)K);   // fp32 product, as the definition is stated
+    if (r < 1) r = 1;
+    if (r > K) r = K;
+    return hip_result(dgq::launch_smooth_scales(X, M, K, r, k, static_cast<float *>(workspace),
+                                                static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k, int M, int K, int N,
+                            uint16_t *Wout, uint16_t *Xout, void *stream)
+{
+    if (!k || (!W && !X) || (W && !Wout) || (X && !Xout)) return DGQ_ERR_NULL;
+    if (K < 1 || K > 65535 || (W && N < 1) || (X && (M < 1 || M > 65535))) return DGQ_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Wout) |
+         reinterpret_cast<uintptr_t>(Xout)) & 1u)
+        return DGQ_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(k) & 3u) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_smooth_apply(W, X, k, M, K, N, Wout, Xout, static_cast<hipStream_t>(stream)));
 }
 
 dgq_status dgq_quant_act_static(const uint16_t *x, int M, int K, float scale, int8_t *xq, float *sx, void *stream)

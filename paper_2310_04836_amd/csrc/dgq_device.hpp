@@ -96,6 +96,9 @@ __device__ __forceinline__ void expand_cell(const uint4 &q, const GroupScale &g,
 // ---- kernel launchers (defined one per .hip file) ----------------------------------
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_quant_act_static(const uint16_t *x, int M, int K, float s, int8_t *xq, float *sx, hipStream_t st);
+hipError_t launch_smooth_scales(const uint16_t *X, int M, int K, int r, float *k, float *z, hipStream_t st);
+hipError_t launch_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k, int M, int K, int N,
+                               uint16_t *Wout, uint16_t *Xout, hipStream_t st);
 hipError_t launch_quantize_rtn(const uint16_t *W, int K, int N, int group, int8_t *w4, uint8_t *s2,
                                float *s1, hipStream_t st);
 hipError_t launch_quantize_grid(const uint16_t *W, int K, int N, int group, int n_alpha, float step, uint8_t *u4,

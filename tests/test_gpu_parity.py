@@ -557,3 +557,21 @@ def test_static_activation_scale_through_the_linear(dgq, torch):
     oxq, osx = oracle.quant_act_static(x, scale)
     oout, _ = oracle.linear_a8w4(oxq, osx, w4, s2, s1, g)
     assert_fp16_close(out, oout)
+
+
+@pytest.mark.parametrize("M,K,N,pct", [(64, 4096, 64, 0.005), (7, 11008, 16, 0.005), (300, 1024, 48, 0.02), (2, 128, 16, 1.0)])
+def test_smoothing_bit_exact(dgq, torch, M, K, N, pct):
+    x = workloads.activations(M, K, M + K)                       # 1 % of the channels are outliers
+    W = workloads.weights(K, N, M + K)
+    k = dgq.smooth_scales(dev(torch, x), pct)
+    ok = oracle.smooth_scales(x, pct)
+    assert np.array_equal(host(k), ok)
+    Wo, Xo = dgq.smooth_apply(dev(torch, W), dev(torch, x), k)
+    oW, oX = oracle.smooth_apply(W, x, ok)
+    assert np.array_equal(host(Wo).view(np.uint16), oW.view(np.uint16))
+    assert np.array_equal(host(Xo).view(np.uint16), oX.view(np.uint16))
+
+
+def test_smoothing_of_all_zero_activations_is_the_identity(dgq, torch):
+    x = np.zeros((3, 256), np.float16)
+    assert (host(dgq.smooth_scales(dev(torch, x))) == 1).all()
