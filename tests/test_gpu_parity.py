@@ -575,3 +575,28 @@ def test_smoothing_bit_exact(dgq, torch, M, K, N, pct):
 def test_smoothing_of_all_zero_activations_is_the_identity(dgq, torch):
     x = np.zeros((3, 256), np.float16)
     assert (host(dgq.smooth_scales(dev(torch, x))) == 1).all()
+
+
+def test_offline_pipeline_lowers_the_output_error(dgq, torch):
+    """Directions the paper reports (Table 1, Table 5), on synthetic data and against the fp64 product of the
+    unquantized operands: the grid search beats direct rounding, and smoothing does not undo it."""
+    M, K, N, g = 256, 4096, 512, 128
+    x = workloads.activations(M, K, 21)
+    W = workloads.weights(K, N, 21)
+    ref = x.astype(np.float64) @ W.astype(np.float64)
+
+    def err(o):
+        return float(np.linalg.norm(host(o).astype(np.float64) - ref) / np.linalg.norm(ref))
+    X, Wd = dev(torch, x), dev(torch, W)
+    xq, sx = dgq.quant_act(X)
+    w4, s2, s1 = dgq.quantize_weights_rtn(Wd, g)
+    e_rtn = err(dgq.linear_a8w4(xq, sx, dgq.pack_weights(w4, s2, s1, g)))
+    u4, zp, s2, s1 = dgq.quantize_weights_grid(Wd, g)
+    e_grid = err(dgq.linear_a8w4(xq, sx, dgq.pack_weights_zp(u4, s2, zp, s1, g)))
+    k = dgq.smooth_scales(X)
+    Ws, Xs = dgq.smooth_apply(Wd, X, k)
+    u4, zp, s2, s1 = dgq.quantize_weights_grid(Ws, g)
+    xq2, sx2 = dgq.quant_act(Xs)
+    e_smooth = err(dgq.linear_a8w4(xq2, sx2, dgq.pack_weights_zp(u4, s2, zp, s1, g)))
+    assert e_grid < 0.95 * e_rtn and e_smooth < 0.95 * e_rtn and e_smooth < 1.05 * e_grid
+    assert e_rtn < 0.2                                  # and all of them are sane
