@@ -600,3 +600,28 @@ def test_offline_pipeline_lowers_the_output_error(dgq, torch):
     e_smooth = err(dgq.linear_a8w4(xq2, sx2, dgq.pack_weights_zp(u4, s2, zp, s1, g)))
     assert e_grid < 0.95 * e_rtn and e_smooth < 0.95 * e_rtn and e_smooth < 1.05 * e_grid
     assert e_rtn < 0.2                                  # and all of them are sane
+
+
+def test_random_shapes_all_plans(dgq, torch):
+    """Forty seeded random problems across every plan boundary (M around 16, 64, 256; few and many tiles;
+    both group sizes; both operand forms): INT32 sums against an int64 product."""
+    rng = np.random.default_rng(2024)
+    seen = set()
+    for case in range(40):
+        M = int(rng.choice([1, 3, 15, 16, 17, 31, 63, 64, 65, 100, 129, 255, 256, 257, 400, 700]))
+        K = 128 * int(rng.integers(1, 24))
+        N = 16 * int(rng.integers(1, 90)) if case % 4 else 16 * int(rng.integers(200, 600))
+        g = int(rng.choice([64, 128]))
+        xq, _ = workloads.integer_activations(M, K, case)
+        if case % 2:
+            u4, s2, zp, s1 = _zp_operands(K, N, g, case)
+            pw = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), g)
+            ws8 = np.repeat(s2.astype(np.int64), g, axis=0) * (u4.astype(np.int64) - np.repeat(zp.astype(np.int64), g, axis=0))
+        else:
+            w4, s2, s1 = workloads.integer_weights(K, N, g, case)
+            pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+            ws8 = np.repeat(s2.astype(np.int64), g, axis=0) * w4.astype(np.int64)
+        seen.add(dgq.linear_plan(M, N, K, g))
+        acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
+        assert np.array_equal(acc.astype(np.int64), xq.astype(np.int64) @ ws8), (case, M, K, N, g)
+    assert len(seen) >= 8, seen                          # decode variants, tiled with and without a K split, ...
