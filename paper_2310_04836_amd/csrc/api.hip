@@ -312,8 +312,8 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
     }
     default: {
         const dgq::TiledPlan p = dgq::tiled_plan(M, N, K);
-        std::snprintf(buf, buf_bytes, "linear_tiled_%skernel<%d, %d, %d, %d, %s>", p.kw == 2 ? "k2_" : "", group,
-                      p.nw, p.mi, p.st, p.ksplit > 1 ? "true" : "false");
+        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, %d, %d, %d, %s>", group, p.nw, p.mi, p.st,
+                      p.ksplit > 1 ? "true" : "false");
     }
     }
     return DGQ_OK;

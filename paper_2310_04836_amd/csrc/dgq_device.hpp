@@ -148,7 +148,6 @@ struct TiledPlan {
     int mi;      // 32-token blocks per tile (template MI)
     int st;      // stages of operands in flight or in use (template ST)
     int ksplit;  // workgroups that share one tile, each taking a part of K
-    int kw;      // halves of the stages inside a workgroup (template KW): 1, or 2 with 2*nw wavefronts
 };
 TiledPlan tiled_plan(int M, int N, int K);
 size_t tiled_workspace_bytes(int M, int N, int K);

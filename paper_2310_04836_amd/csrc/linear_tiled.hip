@@ -89,12 +89,9 @@ __device__ __forceinline__ void arrive(v4u &a, v4u &b, v4u &c, v4u &d, uint32_t 
 // NW wavefronts per workgroup, each owning 64 output channels of the (32*MI) x (64*NW) tile;
 // ST stages of operands in flight or in use.  ksplit workgroups share one tile, each walking its
 // own part of K; then (and in the test hook) the raw INT32 sums go to a.acc_out, slice kpart.
-// KW = 2: the workgroup has 2 x NW wavefronts; the upper NW walk the second half of the stages with
-// an LDS ring of their own, and the two halves' INT32 sums are added through LDS at the end.  A
-// workgroup that has a CU to itself then runs two wavefronts per SIMD instead of one.
 // ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes; a compile-time choice, so that the
 // signed-nibble form pays nothing for the general one.
-template <int G, int NW, int MI, int ST, int KW, bool ACC, bool ZP>
+template <int G, int NW, int MI, int ST, bool ACC, bool ZP>
 __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int tiles_n, int ksplit)
 {
     constexpr int kStages = ST;
@@ -106,9 +103,8 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
     static_assert(ST >= 3 && ST <= 6 && PPW >= 1 && kLoadsPerStage <= 12, "loads are spread over 12 sub-chunks");
     static_assert((ST - 1) * kLoadsPerStage <= 63, "vmcnt counts to 63");
     static_assert(1024 + NW * 4096 <= ST * BM * BK, "the epilogue reuses the ring");
-    static_assert(KW == 1 || (KW == 2 && NW * 8192 <= KW * ST * BM * BK), "the halves meet in the ring");
 
-    __shared__ __attribute__((aligned(1024))) int8_t lds_a[KW * kStages][BM * BK];
+    __shared__ __attribute__((aligned(1024))) int8_t lds_a[kStages][BM * BK];
 
     const int T = tiles_m * tiles_n * ksplit;
     const int per_xcd = (T + 7) >> 3;
@@ -127,9 +123,7 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kw = KW == 1 ? 0 : wave_all / NW;  // which half of the stages
-    const int wave = wave_all - kw * NW;         // which 64 output channels
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = lane >> 5;
     const int li = lane & 31;
     const int steps = a.K >> 7;
@@ -168,14 +162,11 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
     }
 
     // LDS byte address of this wavefront's first piece in stage buffer 0
-    const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[kw * kStages][0] + wave * PPW * 1024;
+    const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[0][0] + wave * PPW * 1024;
 
-    // this workgroup's stages of K, and this wavefront's share of them (the host makes sure that
-    // the halves are equal, so that every wavefront meets the same number of barriers)
-    const int wg0 = (steps * kpart) / ksplit;
-    const int wg1 = (steps * (kpart + 1)) / ksplit;
-    const int p0 = wg0 + kw * ((wg1 - wg0) / KW);
-    const int p1 = p0 + (wg1 - wg0) / KW;
+    // this workgroup's stages of K
+    const int p0 = (steps * kpart) / ksplit;
+    const int p1 = (steps * (kpart + 1)) / ksplit;
 
     v16i acc[MI][2];
 #pragma unroll
@@ -241,8 +232,7 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 #define DGQ_PREP(PARN, C, PN, GRPN)                                                                   \
     do {                                                                                              \
         if ((C) < MI)                                                                                 \
-            af[PARN][(C) % MI] =                                                                      \
-                *reinterpret_cast<const v4i *>(&lds_a[kw * kStages + (PN)][((C) % MI) * 32 * BK + a_off[GRPN]]); \
+            af[PARN][(C) % MI] = *reinterpret_cast<const v4i *>(&lds_a[PN][((C) % MI) * 32 * BK + a_off[GRPN]]); \
         _Pragma("unroll") for (int nj = 0; nj < 2; ++nj)                                              \
         {                                                                                             \
             const uint32_t w_ = bq[PN][nj][(GRPN) >> 1][C];                                           \
@@ -356,35 +346,12 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
     // ---- epilogue ---------------------------------------------------------------------------
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
     __syncthreads();  // every wavefront is done with the LDS ring
-    if (KW == 2) {
-        // The upper half hands its sums to the lower half through LDS, one 32-token block at a
-        // time (32 registers x 64 lanes x 4 bytes = 8 KiB per wavefront); integer addition, so the
-        // result does not depend on the split.  Every wavefront takes part in every barrier.
-        int *red = reinterpret_cast<int *>(&lds_a[0][0]) + wave * 2048 + lane;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            if (kw == 1) {
-#pragma unroll
-                for (int nj = 0; nj < 2; ++nj)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) red[(nj * 16 + r) * 64] = acc[mi][nj][r];
-            }
-            __syncthreads();
-            if (kw == 0) {
-#pragma unroll
-                for (int nj = 0; nj < 2; ++nj)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[mi][nj][r] += red[(nj * 16 + r) * 64];
-            }
-            __syncthreads();
-        }
-    }
     if (ACC) {
         int32_t *dst = a.acc_out + (size_t)kpart * a.M * a.N;
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj) {
             const int n = ncol[nj];
-            if (n >= a.N || kw != 0) continue;
+            if (n >= a.N) continue;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -406,7 +373,6 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 #pragma unroll
     for (int nj = 0; nj < 2; ++nj) s1n[nj] = ncol[nj] < a.N ? a.s1[ncol[nj]] : 0.0f;
     __syncthreads();
-    if (kw != 0) return;  // no barrier follows
     const int nw0 = n0 + wave * 64;
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
@@ -434,23 +400,12 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 template <int G, int NW, int MI, int ST, bool ACC>
 __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
 {
-    tiled_body<G, NW, MI, ST, 1, ACC, false>(a, tiles_m, tiles_n, ksplit);
+    tiled_body<G, NW, MI, ST, ACC, false>(a, tiles_m, tiles_n, ksplit);
 }
 template <int G, int NW, int MI, int ST, bool ACC>
 __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_zp_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
 {
-    tiled_body<G, NW, MI, ST, 1, ACC, true>(a, tiles_m, tiles_n, ksplit);
-}
-// two halves of K inside the workgroup (2 x NW wavefronts, one workgroup per CU)
-template <int G, int NW, int MI, int ST, bool ACC>
-__global__ __launch_bounds__(128 * NW, 2) void linear_tiled_k2_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
-{
-    tiled_body<G, NW, MI, ST, 2, ACC, false>(a, tiles_m, tiles_n, ksplit);
-}
-template <int G, int NW, int MI, int ST, bool ACC>
-__global__ __launch_bounds__(128 * NW, 2) void linear_tiled_k2_zp_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
-{
-    tiled_body<G, NW, MI, ST, 2, ACC, true>(a, tiles_m, tiles_n, ksplit);
+    tiled_body<G, NW, MI, ST, ACC, true>(a, tiles_m, tiles_n, ksplit);
 }
 
 }  // namespace
@@ -460,7 +415,7 @@ TiledPlan tiled_plan(int M, int N, int K)
     constexpr int kCus = 256;
     const int steps = K / 128;
     TiledPlan p;
-    p.nw = 4, p.mi = 4, p.st = 3, p.ksplit = 1, p.kw = 1;
+    p.nw = 4, p.mi = 4, p.st = 3, p.ksplit = 1;
     const long long tiles_n = (N + 255) / 256;
     const long long tiles_64 = (long long)((M + 63) / 64) * tiles_n;
     if (M <= 256 && tiles_64 < 2 * kCus) {
@@ -485,8 +440,6 @@ TiledPlan tiled_plan(int M, int N, int K)
             p.ksplit = best;
             p.mi = 2;
             p.st = 6;
-            // not split over workgroups: split inside the workgroup (two wavefronts per SIMD)
-            if (best == 1 && tiles_64 <= kCus && (steps & 1) == 0) p.kw = 2;
             return p;
         }
     }
@@ -495,9 +448,6 @@ TiledPlan tiled_plan(int M, int N, int K)
         // with 128-token tiles.  (With more tiles than CUs the smaller tile loses: it expands
         // every weight twice as often.)
         p.mi = 2;
-        // a workgroup with a CU to itself runs one wavefront per SIMD; with the stages split in two
-        // inside the workgroup it runs two
-        if ((steps & 1) == 0) p.kw = 2;
         return p;
     }
     // Two workgroups of four wavefronts per CU overlap better than one of eight: the two
@@ -515,24 +465,7 @@ size_t tiled_workspace_bytes(int M, int N, int K)
     return ks > 1 ? (size_t)ks * M * N * sizeof(int32_t) : 0;
 }
 
-template <int G, int NW, int MI, int ST, int KW, bool ACC>
-static void launch_tiled_kernel(const LinearArgs &a, dim3 grid, int tiles_m, int tiles_n, int ksplit, hipStream_t st)
-{
-    const dim3 block(64 * NW * KW);
-    if constexpr (KW == 2) {
-        if (a.zp)
-            hipLaunchKernelGGL((linear_tiled_k2_zp_kernel<G, NW, MI, ST, ACC>), grid, block, 0, st, a, tiles_m, tiles_n, ksplit);
-        else
-            hipLaunchKernelGGL((linear_tiled_k2_kernel<G, NW, MI, ST, ACC>), grid, block, 0, st, a, tiles_m, tiles_n, ksplit);
-    } else {
-        if (a.zp)
-            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, ACC>), grid, block, 0, st, a, tiles_m, tiles_n, ksplit);
-        else
-            hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, ACC>), grid, block, 0, st, a, tiles_m, tiles_n, ksplit);
-    }
-}
-
-template <int G, int NW, int MI, int ST, int KW>
+template <int G, int NW, int MI, int ST>
 static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
 {
     const int tiles_m = (a.M + 32 * MI - 1) / (32 * MI);
@@ -540,35 +473,38 @@ static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *worksp
     const long long T = (long long)tiles_m * tiles_n * ksplit;
     const long long blocks = ((T + 7) / 8) * 8;
     if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
-    // the two halves inside a workgroup must have the same number of stages
-    if (KW == 2 && (ksplit != 1 || ((a.K / 128) & 1))) return hipErrorInvalidValue;
-    dim3 grid((unsigned)blocks);
+    dim3 grid((unsigned)blocks), block(64 * NW);
     if (ksplit > 1) {
         // raw INT32 sums of every part into its slice of the workspace, then one pass that adds
         // the slices and applies the scales
         LinearArgs part = a;
         part.acc_out = static_cast<int32_t *>(workspace);
-        launch_tiled_kernel<G, NW, MI, ST, KW, true>(part, grid, tiles_m, tiles_n, ksplit, st);
+        if (a.zp)
+            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
+        else
+            hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
         return launch_splitk_finalize(a, ksplit, part.acc_out, st);
     }
-    if (a.acc_out)
-        launch_tiled_kernel<G, NW, MI, ST, KW, true>(a, grid, tiles_m, tiles_n, 1, st);
-    else
-        launch_tiled_kernel<G, NW, MI, ST, KW, false>(a, grid, tiles_m, tiles_n, 1, st);
+    if (a.zp) {
+        if (a.acc_out)
+            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+        else
+            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+    } else if (a.acc_out) {
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+    } else {
+        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+    }
     return hipGetLastError();
 }
 
 template <int G>
 static hipError_t launch_tiled_g(const LinearArgs &a, const TiledPlan &p, void *workspace, hipStream_t st)
 {
-    if (p.mi == 2 && p.st == 6)
-        return p.kw == 2 ? launch_tiled_cfg<G, 4, 2, 6, 2>(a, p.ksplit, workspace, st)
-                         : launch_tiled_cfg<G, 4, 2, 6, 1>(a, p.ksplit, workspace, st);
-    if (p.mi == 2)
-        return p.kw == 2 ? launch_tiled_cfg<G, 4, 2, 3, 2>(a, p.ksplit, workspace, st)
-                         : launch_tiled_cfg<G, 4, 2, 3, 1>(a, p.ksplit, workspace, st);
-    if (p.nw == 8) return launch_tiled_cfg<G, 8, 4, 3, 1>(a, p.ksplit, workspace, st);
-    return launch_tiled_cfg<G, 4, 4, 3, 1>(a, p.ksplit, workspace, st);
+    if (p.mi == 2 && p.st == 6) return launch_tiled_cfg<G, 4, 2, 6>(a, p.ksplit, workspace, st);
+    if (p.mi == 2) return launch_tiled_cfg<G, 4, 2, 3>(a, p.ksplit, workspace, st);
+    if (p.nw == 8) return launch_tiled_cfg<G, 8, 4, 3>(a, p.ksplit, workspace, st);
+    return launch_tiled_cfg<G, 4, 4, 3>(a, p.ksplit, workspace, st);
 }
 
 hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st)

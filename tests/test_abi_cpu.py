@@ -119,16 +119,15 @@ def test_linear_plan_names(dgq):
     # 16 < M <= 64: 64-token tile, six stages, K split over workgroups (partial sums -> "true")
     assert dgq.linear_plan(64, 8192, 8192, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
     assert dgq.linear_workspace_bytes(64, 8192, 8192, 128) == 4 * 64 * 8192 * 4
-    assert dgq.linear_plan(17, 44032, 256, 64) == "linear_tiled_k2_kernel<64, 4, 2, 6, false>"   # two stages: one per half
+    assert dgq.linear_plan(17, 44032, 256, 64) == "linear_tiled_kernel<64, 4, 2, 6, false>"
     assert dgq.linear_workspace_bytes(17, 44032, 256, 64) == 0
-    assert dgq.linear_plan(64, 22016, 4096, 128) == "linear_tiled_k2_kernel<128, 4, 2, 6, false>"   # 86 tiles: split inside the workgroup only
-    assert dgq.linear_plan(48, 4160, 1408, 128) == "linear_tiled_kernel<128, 4, 2, 6, false>"       # 11 stages: odd, no halves
+    assert dgq.linear_plan(64, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 2, 6, false>"    # 86 tiles: no split
     # 64 < M <= 256 with very few tiles splits K as well
     assert dgq.linear_plan(128, 4096, 11008, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
     assert dgq.linear_workspace_bytes(128, 4096, 11008, 128) == 4 * 128 * 4096 * 4
-    assert dgq.linear_plan(128, 12288, 4096, 128) == "linear_tiled_k2_kernel<128, 4, 2, 3, false>"
+    assert dgq.linear_plan(128, 12288, 4096, 128) == "linear_tiled_kernel<128, 4, 2, 3, false>"
     # fewer 128-token tiles than CUs: 64-token tiles
-    assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_k2_kernel<64, 4, 2, 3, false>"  # 8 x 16 tiles, a CU each
+    assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"     # 8 x 16 tiles
     assert dgq.linear_plan(512, 12288, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"    # 4 x 48 tiles
     assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"
     assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
