@@ -299,3 +299,24 @@ def smooth_apply(W, X, k):
     _L().dgq_oracle_smooth_apply(_p(Wf), _p(Xf), _p(kf), M, K, N, _p(Wo), _p(Xo))
     with np.errstate(over="ignore"):
         return Wo.astype(np.float16), Xo.astype(np.float16)
+
+
+def silu_mul(GU):
+    """h = fp16(float(silu(gate) * up)) of a gated MLP (gate columns first, then up), silu and product in fp64.
+
+    GU: fp16/fp32 [M, 2*I].  Returns h float16 [M, I]."""
+    G = _c(GU, np.float32)
+    M, I2 = G.shape
+    assert I2 % 2 == 0
+    h = np.empty((M, I2 // 2), np.float32)
+    _L().dgq_oracle_silu_mul(_p(G), M, I2 // 2, _p(h))
+    h16 = h.astype(np.float16)
+    assert np.array_equal(h16.astype(np.float32), h) or not np.isfinite(h).all()   # already fp16 values
+    return h16
+
+
+def silu_mul_quant_act(GU):
+    """The fused producer + per-token quantizer.  Returns (xq int8 [M,I], sx float32 [M], h float16 [M,I])."""
+    h = silu_mul(GU)
+    xq, sx = quant_act(h)
+    return xq, sx, h

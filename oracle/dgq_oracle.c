@@ -580,3 +580,55 @@ void dgq_oracle_smooth_apply(const float *W, const float *X, const float *k, int
     for (int m = 0; m < M; ++m)
         for (int j = 0; j < K; ++j) Xout[(size_t)m * K + j] = X[(size_t)m * K + j] / k[j];
 }
+
+/*
+ * Producer of the MLP's second linear layer fused with its activation quantizer (the fusion the
+ * paper's remark on per-token statistics, Section 4.2, asks for; LLaMA's gated MLP):
+ *     h[m][i] = fp16( float( silu(g) * u ) ),  g = GU[m][i], u = GU[m][I + i],
+ *     silu(g) = g / (1 + exp(-g))
+ * with silu and the product evaluated in fp64, rounded once to fp32 and once more to fp16 (the
+ * tensor a model would store), followed by the per-token quantizer of dgq_oracle_quant_act on h.
+ * This function writes h as fp32 values that are exactly representable in fp16; the caller
+ * quantizes them.  GU is [M][2*I]: the gate columns first, then the up columns.
+ */
+static float round_to_half(float v)
+{
+    /* fp32 -> fp16 -> fp32, round to nearest even, by integer arithmetic on the bit pattern */
+    union { float f; uint32_t u; } in = {v};
+    const uint32_t sign = in.u & 0x80000000u;
+    uint32_t x = in.u & 0x7FFFFFFFu;
+    union { float f; uint32_t u; } out;
+    if (x >= 0x7F800000u) {               /* inf / nan */
+        out.u = in.u;
+        return out.f;
+    }
+    if (x >= 0x477FF000u) {               /* rounds to >= 65520: infinity in fp16 */
+        out.u = sign | 0x7F800000u;
+        return out.f;
+    }
+    if (x < 0x38800000u) {                /* below 2^-14: fp16 subnormal, spacing 2^-24 */
+        const float mag = in.f < 0 ? -in.f : in.f;
+        const float q = rintf(mag * 16777216.0f) / 16777216.0f;
+        out.f = q;
+        out.u |= sign;
+        return out.f;
+    }
+    const uint32_t rem = x & 0x1FFFu;     /* 13 bits dropped */
+    x &= ~0x1FFFu;
+    if (rem > 0x1000u || (rem == 0x1000u && (x & 0x2000u))) x += 0x2000u;
+    out.u = sign | x;
+    return out.f;
+}
+
+void dgq_oracle_silu_mul(const float *GU, int M, int I, float *h)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        for (int i = 0; i < I; ++i) {
+            const double g = (double)GU[(size_t)m * 2 * I + i];
+            const double u = (double)GU[(size_t)m * 2 * I + I + i];
+            const double p = (g / (1.0 + exp(-g))) * u;
+            h[(size_t)m * I + i] = round_to_half((float)p);
+        }
+    }
+}

@@ -381,3 +381,23 @@ def test_quant_act_static_error_bound_and_saturation():
     inside = np.abs(x) <= 127 * s
     assert (np.abs(x - s * xq)[inside] <= 0.5 * s * (1 + 1e-6)).all()
     assert (np.abs(xq[~inside]) == 127).all() and (np.sign(xq[~inside]) == np.sign(x[~inside])).all()
+
+
+# ---------------------------------------------------------------- gated-MLP producer
+def test_silu_mul_hand_values_and_fp16_rounding():
+    # silu(0) = 0; silu(g) -> g for large g, -> 0 for very negative g; silu(1) = 0.7310585786...
+    GU = np.array([[0.0, 1.0, 20.0, -20.0, 2.0,   3.0, 2.0, 0.5, 4.0, -1.5]], np.float32)
+    h = oracle.silu_mul(GU)
+    assert h[0, 0] == 0
+    assert h[0, 1] == np.float16(0.7310585786300049 * 2.0)
+    assert h[0, 2] == np.float16(10.0)                      # 20 * (1 - 2e-9) * 0.5
+    assert abs(float(h[0, 3])) < 1e-6                       # -20 * e^-20 * 4: a subnormal fp16 or zero
+    assert h[0, 4] == np.float16(-1.5 * 2.0 / (1.0 + np.exp(-2.0)))
+
+
+def test_silu_mul_equals_numpy_fp64_then_two_roundings():
+    rng = np.random.default_rng(14)
+    GU = (rng.normal(0, 2, (5, 512)) * rng.choice([1e-3, 1, 8], (5, 512))).astype(np.float16)
+    g, u = GU[:, :256].astype(np.float64), GU[:, 256:].astype(np.float64)
+    ref = ((g / (1.0 + np.exp(-g))) * u).astype(np.float32).astype(np.float16)
+    assert np.array_equal(oracle.silu_mul(GU).view(np.uint16), ref.view(np.uint16))
