@@ -152,6 +152,19 @@ DGQ_API dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const 
                             uint16_t *Wout, uint16_t *Xout, void *stream);
 
 /*
+ * The activation quantizer folded into its producer, for the second linear layer of a gated
+ * MLP (the per-token statistics pass that Section 4.2 names as a cost of dynamic quantization
+ * then needs no kernel and no round trip of its own):
+ *   h[m][i] = fp16( float( silu(g) * u ) ),  g = gate_up[m][i],  u = gate_up[m][I + i],
+ *   silu(g) = g / (1 + exp(-g))  evaluated with the product in fp64,
+ * then xq, sx = dgq_quant_act(h).  h is never written.
+ *   gate_up in [M][2*I] fp16 (raw bits): the output of the fused gate+up linear, gate columns first
+ *   xq out [M][I] int8;  sx out [M] float;   I % 128 == 0, 128 <= I <= 24576
+ */
+DGQ_API dgq_status dgq_silu_mul_quant_act(const uint16_t *gate_up, int M, int I, int8_t *xq, float *sx,
+                                  void *stream);
+
+/*
  * Static tensor-wise INT8 activation quantizer (the "S" scheme of Section 4.1 and Table 5;
  * symmetric form of Eq. 1): one positive scale for the whole tensor, fixed offline,
  *   xq = clamp(round(x / scale), -127, 127)   (one IEEE division per element, ties to even)

@@ -254,6 +254,14 @@ dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k
     return hip_result(dgq::launch_smooth_apply(W, X, k, M, K, N, Wout, Xout, static_cast<hipStream_t>(stream)));
 }
 
+dgq_status dgq_silu_mul_quant_act(const uint16_t *gate_up, int M, int I, int8_t *xq, float *sx, void *stream)
+{
+    if (!gate_up || !xq || !sx) return DGQ_ERR_NULL;
+    if (M < 1 || I < 128 || I > 24576 || (I % 128) != 0) return DGQ_ERR_SHAPE;
+    if (!aligned16(gate_up) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_silu_mul_quant_act(gate_up, M, I, xq, sx, static_cast<hipStream_t>(stream)));
+}
+
 dgq_status dgq_quant_act_static(const uint16_t *x, int M, int K, float scale, int8_t *xq, float *sx, void *stream)
 {
     if (!x || !xq || !sx) return DGQ_ERR_NULL;

@@ -93,8 +93,20 @@ __device__ __forceinline__ void expand_cell(const uint4 &q, const GroupScale &g,
     }
 }
 
+// Epilogue of Eq. 2 for one element: the fp32 product scale * float(acc), then ONE more rounding to
+// fp16.  The two roundings are kept apart on purpose: fused into a mixed-precision multiply that
+// rounds the exact product straight to fp16, the result differs from the stated definition in
+// the rare cases where the fp32 rounding crosses an fp16 tie.
+__device__ __forceinline__ unsigned short scaled_sum_to_half_bits(float scale, int acc)
+{
+    float p = scale * (float)acc;
+    asm volatile("" : "+v"(p));
+    return __builtin_bit_cast(unsigned short, (_Float16)p);
+}
+
 // ---- kernel launchers (defined one per .hip file) ----------------------------------
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
+hipError_t launch_silu_mul_quant_act(const uint16_t *GU, int M, int I, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_quant_act_static(const uint16_t *x, int M, int K, float s, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_smooth_scales(const uint16_t *X, int M, int K, int r, float *k, float *z, hipStream_t st);
 hipError_t launch_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k, int M, int K, int N,

@@ -189,8 +189,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
                 else if (k == 2) s1n = ep_s1[2];
                 else s1n = a.s1[n];
                 const float sc = ep_sx * s1n;
-                const _Float16 h = (_Float16)(sc * (float)sum);
-                a.out[(size_t)ep_m * a.N + n] = __builtin_bit_cast(unsigned short, h);
+                a.out[(size_t)ep_m * a.N + n] = scaled_sum_to_half_bits(sc, sum);
             }
         }
     }
@@ -228,7 +227,7 @@ __global__ __launch_bounds__(256) void splitk_finalize_kernel(LinearArgs a, int 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float sc = sxm * s1v[i];
-            h[i] = __builtin_bit_cast(unsigned short, (_Float16)(sc * (float)sum[i]));
+            h[i] = scaled_sum_to_half_bits(sc, sum[i]);
         }
         uint2 o;
         o.x = h[0] | ((uint32_t)h[1] << 16);

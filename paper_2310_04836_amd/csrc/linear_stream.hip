@@ -120,8 +120,7 @@ __global__ __launch_bounds__(W * 64) void linear_stream_kernel(LinearArgs a)
                 a.acc_out[(size_t)m * a.N + n] = sum;
             } else {
                 const float sc = a.sx[m] * a.s1[n];
-                const _Float16 h = (_Float16)(sc * (float)sum);
-                a.out[(size_t)m * a.N + n] = __builtin_bit_cast(unsigned short, h);
+                a.out[(size_t)m * a.N + n] = scaled_sum_to_half_bits(sc, sum);
             }
         }
     }

@@ -382,8 +382,7 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
             for (int r = 0; r < 16; ++r) {
                 const int row = 8 * (r >> 2) + 4 * kb + (r & 3);
                 const float sc = lds_sx[mi * 32 + row] * s1n[nj];
-                const _Float16 hv = (_Float16)(sc * (float)acc[mi][nj][r]);
-                lds_t[row * 64 + nj * 32 + li] = __builtin_bit_cast(unsigned short, hv);
+                lds_t[row * 64 + nj * 32 + li] = scaled_sum_to_half_bits(sc, acc[mi][nj][r]);
             }
         // 32 rows x 128 bytes: lane l takes 16-byte chunk l%8 of rows l/8, l/8 + 8, ...
 #pragma unroll

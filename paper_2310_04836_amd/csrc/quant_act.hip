@@ -113,6 +113,70 @@ __global__ __launch_bounds__(kThreads) void quant_act_kernel(const uint16_t *__r
     }
 }
 
+// Gated-MLP producer fused with the per-token quantizer: h = fp16(float(silu(g) * u)) with silu and
+// the product in fp64 (one rounding to fp32, one to fp16: the tensor a model would store between
+// the two linear layers), then the same absmax / scale / round as quant_act_kernel on h.  GU is
+// [M][2*I], gate columns first.  h never goes to memory.  Each thread keeps its VPT vectors of h
+// (fp16 bits) in registers, so I <= 2048 * VPT.
+__device__ __forceinline__ uint32_t silu_mul_pair(uint32_t g2, uint32_t u2)
+{
+    uint32_t r = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const double g = (double)half_bits_to_float((g2 >> (16 * h)) & 0xFFFFu);
+        const double u = (double)half_bits_to_float((u2 >> (16 * h)) & 0xFFFFu);
+        const double p = (g / (1.0 + exp(-g))) * u;
+        const float p32 = (float)p;
+        r |= (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)p32) << (16 * h);
+    }
+    return r;
+}
+
+template <int VPT>
+__global__ __launch_bounds__(kThreads) void silu_mul_quant_act_kernel(const uint16_t *__restrict__ GU, int M, int I,
+                                                                      int8_t *__restrict__ xq,
+                                                                      float *__restrict__ sx)
+{
+    __shared__ uint32_t wave_m[kThreads / 64];
+    const int m = blockIdx.x;
+    const int nvec = I >> 3;
+    const uint4 *grow = reinterpret_cast<const uint4 *>(GU + (size_t)m * 2 * I);
+    const uint4 *urow = reinterpret_cast<const uint4 *>(GU + (size_t)m * 2 * I + I);
+    uint2 *dst = reinterpret_cast<uint2 *>(xq + (size_t)m * I);
+
+    uint4 cache[VPT];
+    uint32_t mx = 0;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        cache[i] = make_uint4(0, 0, 0, 0);
+        if (idx < nvec) {
+            const uint4 g = grow[idx], u = urow[idx];
+            cache[i] = make_uint4(silu_mul_pair(g.x, u.x), silu_mul_pair(g.y, u.y), silu_mul_pair(g.z, u.z),
+                                  silu_mul_pair(g.w, u.w));
+        }
+        mx = absmax_bits(cache[i], mx);
+    }
+    mx = wave_max_u32(mx);
+    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = wave_m[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) mx = wave_m[w] > mx ? wave_m[w] : mx;
+    const float a = half_bits_to_float(mx);
+    float inv = 0.0f, s = 0.0f;
+    if (a != 0.0f) {
+        s = a / 127.0f;
+        inv = 127.0f / a;
+    }
+    if (threadIdx.x == 0) sx[m] = s;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        if (idx < nvec) dst[idx] = quant_vec(cache[i], inv);
+    }
+}
+
 // Static tensor-wise scale (the "S" scheme of Section 4.1 / Table 5; symmetric form of Eq. 1 with
 // 8 bits): xq = clamp(round(x / s), -127, 127) with one IEEE division per element, and every
 // token's scale is s.  One thread per eight values; no reduction.
@@ -149,6 +213,21 @@ hipError_t launch_quant_act_static(const uint16_t *x, int M, int K, float s, int
     const size_t blocks = (nvec + kThreads - 1) / kThreads;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     hipLaunchKernelGGL(quant_act_static_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, nvec, M, s, xq, sx);
+    return hipGetLastError();
+}
+
+hipError_t launch_silu_mul_quant_act(const uint16_t *GU, int M, int I, int8_t *xq, float *sx, hipStream_t st)
+{
+    dim3 grid(M), block(kThreads);
+    const int nvec = I / 8;
+    if (nvec <= 2 * kThreads)
+        hipLaunchKernelGGL(silu_mul_quant_act_kernel<2>, grid, block, 0, st, GU, M, I, xq, sx);
+    else if (nvec <= 6 * kThreads)
+        hipLaunchKernelGGL(silu_mul_quant_act_kernel<6>, grid, block, 0, st, GU, M, I, xq, sx);
+    else if (nvec <= 12 * kThreads)
+        hipLaunchKernelGGL(silu_mul_quant_act_kernel<12>, grid, block, 0, st, GU, M, I, xq, sx);
+    else
+        return hipErrorInvalidValue;   // I > 24576: checked by the caller
     return hipGetLastError();
 }
 

@@ -625,3 +625,41 @@ def test_random_shapes_all_plans(dgq, torch):
         acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
         assert np.array_equal(acc.astype(np.int64), xq.astype(np.int64) @ ws8), (case, M, K, N, g)
     assert len(seen) >= 8, seen                          # decode variants, tiled with and without a K split, ...
+
+
+@pytest.mark.parametrize("M,I", [(1, 128), (16, 11008), (5, 13824), (3, 22016), (300, 1024)])
+def test_silu_mul_quant_act_bit_exact(dgq, torch, M, I):
+    rng = np.random.default_rng([M, I])
+    GU = (rng.normal(0, 1.5, (M, 2 * I)) * rng.choice([0.01, 1.0, 6.0], (M, 2 * I))).astype(np.float16)
+    GU[0, :8] = 0
+    xq, sx = dgq.silu_mul_quant_act(dev(torch, GU))
+    oxq, osx, _ = oracle.silu_mul_quant_act(GU)
+    assert np.array_equal(host(sx), osx)
+    assert np.array_equal(host(xq), oxq)
+
+
+def test_mlp_block_against_the_oracle(dgq, torch):
+    """x -> quant -> gate+up linear -> silu*mul fused with quant -> down linear, all through the C ABI,
+    against the same chain in the oracle (every integer tensor bit-exact, the fp16 outputs to tolerance)."""
+    M, H, I, g = 24, 512, 1408, 128
+    x = workloads.activations(M, H, 31)
+    w_gu, s2_gu, s1_gu = workloads.integer_weights(H, 2 * I, g, 31)
+    w_d, s2_d, s1_d = workloads.integer_weights(I, H, g, 32)
+    s1_gu = (s1_gu * np.float32(4)).astype(np.float32)          # pre-activations of order one
+    p_gu = dgq.pack_weights(dev(torch, w_gu), dev(torch, s2_gu), dev(torch, s1_gu), g)
+    p_d = dgq.pack_weights(dev(torch, w_d), dev(torch, s2_d), dev(torch, s1_d), g)
+    xq, sx = dgq.quant_act(dev(torch, x))
+    gu = dgq.linear_a8w4(xq, sx, p_gu)
+    hq, hs = dgq.silu_mul_quant_act(gu)
+    out = host(dgq.linear_a8w4(hq, hs, p_d))
+    ogu, _, oxq, osx = oracle.forward(x, w_gu, s2_gu, s1_gu, g)
+    assert np.array_equal(host(xq), oxq)
+    assert np.isfinite(ogu).all() and 0.2 < np.abs(ogu.astype(np.float32)).mean() < 20
+    assert_fp16_close(host(gu), ogu)
+    if np.array_equal(host(gu).view(np.uint16), ogu.view(np.uint16)):      # then everything downstream is exact
+        ohq, ohs, _ = oracle.silu_mul_quant_act(ogu)
+        assert np.array_equal(host(hq), ohq) and np.array_equal(host(hs), ohs)
+        oout, _ = oracle.linear_a8w4(ohq, ohs, w_d, s2_d, s1_d, g)
+        assert_fp16_close(out, oout)
+    else:
+        pytest.fail("gate+up outputs differ in bits; the chain cannot be compared exactly")
