@@ -100,7 +100,7 @@ __device__ __forceinline__ void expand_cell(const uint4 &q, const GroupScale &g,
 __device__ __forceinline__ unsigned short scaled_sum_to_half_bits(float scale, int acc)
 {
     float p = scale * (float)acc;
-    asm volatile("" : "+v"(p));
+    asm("" : "+v"(p));   // opaque to the optimizer, free to be scheduled
     return __builtin_bit_cast(unsigned short, (_Float16)p);
 }
 
