@@ -74,12 +74,17 @@ def main():
     ap.add_argument("--act", default="dynamic", choices=["dynamic", "static"],
                     help="activation quantizer: per-token dynamic (the benchmark configs) or one static "
                          "tensor-wise scale fixed before the timed region (Section 4.1)")
+    ap.add_argument("--mlp-block", action="store_true",
+                    help="time the gated MLP as a chain instead of independent layers: quantize x, gate+up linear, "
+                         "silu*mul fused with the quantizer (dgq_silu_mul_quant_act), down linear")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.mlp_block:
+        args.no_cpu_baseline = True      # the oracle leg times independent layers, not this chain
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path is a single-GPU kernel library); "
                  "--gpus %d is not supported, use --gpus 1" % args.gpus)
@@ -96,6 +101,8 @@ def main():
     dev = torch.device("cuda:0")
     size, Ms, g = WORKLOADS[args.workload]
     shapes = workloads.LLAMA_SHAPES[size]
+    if args.mlp_block:
+        shapes = {k: shapes[k] for k in ("gate_up", "down")}
     frac, mult = workloads.OUTLIERS[size]
     seed = {"7b": 1, "13b": 3, "65b": 4}[size]
 
@@ -148,8 +155,19 @@ def main():
             dgq.quant_act(acts[(M, name)], xq, sx)
         dgq.linear_a8w4(xq, sx, packed[name][copy % ncopies], out, ws)
 
+    def mlp_chain(M, copy):
+        xq, sx, gu, ws = bufs[(M, "gate_up")]
+        dgq.quant_act(acts[(M, "gate_up")], xq, sx)
+        dgq.linear_a8w4(xq, sx, packed["gate_up"][copy % ncopies], gu, ws)
+        hq, hs, out, ws2 = bufs[(M, "down")]
+        dgq.silu_mul_quant_act(gu, hq, hs)
+        dgq.linear_a8w4(hq, hs, packed["down"][copy % ncopies], out, ws2)
+
     def step_body(i):
         for mi, M in enumerate(Ms):
+            if args.mlp_block:
+                mlp_chain(M, i * len(Ms) + mi)
+                continue
             for name in shapes:
                 one_pair(M, name, i * len(Ms) + mi)
 
@@ -187,6 +205,9 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
 
     step_bytes = sum(algorithmic_bytes(M, K, N, g) + act_quant_bytes(M, K) for M in Ms for K, N in shapes.values())
+    if args.mlp_block:   # the producer reads gate and up (fp16) and writes int8 + scales; no separate quantizer for down
+        Kd = shapes["down"][0]
+        step_bytes += sum(2 * M * 2 * Kd + M * Kd + 4 * M - act_quant_bytes(M, Kd) for M in Ms)
     step_ops = sum(2 * M * K * N for M in Ms for K, N in shapes.values())
     value = step_bytes / (elapsed / args.steps) / 1e9
     log("step: %.3f ms, %.1f GB/s algorithmic, %.2f TOP/s" % (ms_per_step, value, step_ops / (elapsed / args.steps) / 1e12))
@@ -400,7 +421,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
                    "layers_per_step": list(shapes), "weight_copies": ncopies,
-                   "activation_quantizer": args.act,
+                   "activation_quantizer": args.act, "mlp_block": bool(args.mlp_block),
                    "weight_format": ("unsigned nibbles, per-group zero points, S2 <= 127, two-phase grid search"
                                      if args.format == "zp" else "signed nibbles, S2 <= 15, RTN"),
                    "launch": "eager" if args.no_graph else "hip_graph"},
