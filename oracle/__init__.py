@@ -45,6 +45,7 @@ def _L():
         _lib.dgq_oracle_pack_zp.restype = ctypes.c_long
         _lib.dgq_oracle_quant_act_static.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_float, ctypes.c_void_p]
         _lib.dgq_oracle_smooth_scales.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+        _lib.dgq_oracle_rmsnorm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
         _lib.dgq_oracle_quantize_grid.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                   ctypes.c_int, ctypes.c_float, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -320,3 +321,20 @@ def silu_mul_quant_act(GU):
     h = silu_mul(GU)
     xq, sx = quant_act(h)
     return xq, sx, h
+
+
+def rmsnorm(x, gamma, eps: float):
+    """y = fp16(float(x / sqrt(mean x^2 + eps) * gamma)), evaluated in fp64.  Returns float16 [M, K]."""
+    xf, gf = _c(x, np.float32), _c(gamma, np.float32)
+    M, K = xf.shape
+    assert gf.shape == (K,)
+    y = np.empty((M, K), np.float32)
+    _L().dgq_oracle_rmsnorm(_p(xf), _p(gf), M, K, ctypes.c_float(eps), _p(y))
+    return y.astype(np.float16)
+
+
+def rmsnorm_quant_act(x, gamma, eps: float):
+    """RMSNorm fused with the per-token quantizer.  Returns (xq int8, sx float32, y float16)."""
+    y = rmsnorm(x, gamma, eps)
+    xq, sx = quant_act(y)
+    return xq, sx, y

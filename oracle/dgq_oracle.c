@@ -632,3 +632,22 @@ void dgq_oracle_silu_mul(const float *GU, int M, int I, float *h)
         }
     }
 }
+
+/*
+ * RMSNorm fused with the per-token quantizer (producer of the qkv and gate+up linears of a LLaMA
+ * block; same motive as dgq_oracle_silu_mul):
+ *     y[m][k] = fp16( float( x * (1 / sqrt(mean_k x^2 + eps)) * gamma[k] ) )
+ * with the mean of squares, the reciprocal square root and both products in fp64 (the mean summed
+ * in increasing k), rounded once to fp32 and once to fp16; the caller quantizes y per token.
+ */
+void dgq_oracle_rmsnorm(const float *x, const float *gamma, int M, int K, float eps, float *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int k = 0; k < K; ++k) ss += (double)x[(size_t)m * K + k] * (double)x[(size_t)m * K + k];
+        const double r = 1.0 / sqrt(ss / (double)K + (double)eps);
+        for (int k = 0; k < K; ++k)
+            y[(size_t)m * K + k] = round_to_half((float)((double)x[(size_t)m * K + k] * r * (double)gamma[k]));
+    }
+}

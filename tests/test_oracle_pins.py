@@ -401,3 +401,21 @@ def test_silu_mul_equals_numpy_fp64_then_two_roundings():
     g, u = GU[:, :256].astype(np.float64), GU[:, 256:].astype(np.float64)
     ref = ((g / (1.0 + np.exp(-g))) * u).astype(np.float32).astype(np.float16)
     assert np.array_equal(oracle.silu_mul(GU).view(np.uint16), ref.view(np.uint16))
+
+
+def test_rmsnorm_hand_values_and_numpy_fp64():
+    # a row of +-3 has mean square 9: y = x / 3 * gamma exactly (eps = 0)
+    x = np.array([[3, -3, 3, -3]], np.float16)
+    y = oracle.rmsnorm(x, np.array([1, 2, 0.5, 4], np.float16), 0.0)
+    assert y.tolist() == [[1.0, -2.0, 0.5, -4.0]]
+    rng = np.random.default_rng(15)
+    x = (rng.normal(0, 1, (6, 384)) * rng.choice([0.05, 1, 30], (6, 1))).astype(np.float16)
+    gamma = rng.normal(1, 0.2, 384).astype(np.float16)
+    x64, g64 = x.astype(np.float64), gamma.astype(np.float64)
+    eps = 1e-5
+    ref = (x64 / np.sqrt((x64 ** 2).mean(axis=1, keepdims=True) + np.float64(np.float32(eps))) * g64)
+    ref = ref.astype(np.float32).astype(np.float16)
+    got = oracle.rmsnorm(x, gamma, eps)
+    # numpy's pairwise mean and x/sqrt differ from 1/sqrt and a running sum in the last fp64 bits only:
+    # after two roundings at most a handful of ties can differ, and on this data none does
+    assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
