@@ -75,8 +75,8 @@ def main():
                     help="activation quantizer: per-token dynamic (the benchmark configs) or one static "
                          "tensor-wise scale fixed before the timed region (Section 4.1)")
     ap.add_argument("--mlp-block", action="store_true",
-                    help="time the gated MLP as a chain instead of independent layers: quantize x, gate+up linear, "
-                         "silu*mul fused with the quantizer (dgq_silu_mul_quant_act), down linear")
+                    help="time the gated MLP as a chain instead of independent layers: RMSNorm fused with the quantizer, "
+                         "gate+up linear, silu*mul fused with the quantizer, down linear")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-breakdown", action="store_true")
@@ -155,9 +155,11 @@ def main():
             dgq.quant_act(acts[(M, name)], xq, sx)
         dgq.linear_a8w4(xq, sx, packed[name][copy % ncopies], out, ws)
 
+    gamma = torch.ones(shapes["gate_up"][0], dtype=torch.float16, device=dev) if args.mlp_block else None
+
     def mlp_chain(M, copy):
         xq, sx, gu, ws = bufs[(M, "gate_up")]
-        dgq.quant_act(acts[(M, "gate_up")], xq, sx)
+        dgq.rmsnorm_quant_act(acts[(M, "gate_up")], gamma, 1e-5, xq, sx)
         dgq.linear_a8w4(xq, sx, packed["gate_up"][copy % ncopies], gu, ws)
         hq, hs, out, ws2 = bufs[(M, "down")]
         dgq.silu_mul_quant_act(gu, hq, hs)

@@ -160,7 +160,14 @@ DGQ_API dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const 
  * then xq, sx = dgq_quant_act(h).  h is never written.
  *   gate_up in [M][2*I] fp16 (raw bits): the output of the fused gate+up linear, gate columns first
  *   xq out [M][I] int8;  sx out [M] float;   I % 128 == 0, 128 <= I <= 24576
+ *
+ * dgq_rmsnorm_quant_act does the same for the producer of a block's first linears (qkv, gate+up):
+ *   y[m][k] = fp16( float( x * (1 / sqrt(mean_k x^2 + eps)) * gamma[k] ) )   evaluated in fp64,
+ *   then xq, sx = dgq_quant_act(y).   x in [M][K] fp16, gamma in [K] fp16, 0 <= eps < 1
+ *   (DGQ_ERR_RANGE otherwise), K % 128 == 0, 128 <= K <= 24576.
  */
+DGQ_API dgq_status dgq_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps,
+                                 int8_t *xq, float *sx, void *stream);
 DGQ_API dgq_status dgq_silu_mul_quant_act(const uint16_t *gate_up, int M, int I, int8_t *xq, float *sx,
                                   void *stream);
 

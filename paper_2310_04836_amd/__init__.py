@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "PackedWeight", "STREAM_MAX_M",
+    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -52,6 +52,7 @@ def _load() -> ctypes.CDLL:
     L.dgq_quant_act.argtypes = [vp, i, i, vp, vp, vp]
     L.dgq_quant_act_static.argtypes = [vp, i, i, ctypes.c_float, vp, vp, vp]
     L.dgq_silu_mul_quant_act.argtypes = [vp, i, i, vp, vp, vp]
+    L.dgq_rmsnorm_quant_act.argtypes = [vp, vp, i, i, ctypes.c_float, vp, vp, vp]
     L.dgq_smooth_scales.argtypes = [vp, i, i, ctypes.c_float, vp, vp, sz, vp]
     L.dgq_smooth_apply.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
@@ -68,7 +69,7 @@ def _load() -> ctypes.CDLL:
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
                  "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan", "dgq_packed_sizes_zp", "dgq_pack_weights_zp",
-                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid", "dgq_quant_act_static", "dgq_smooth_scales", "dgq_smooth_apply", "dgq_silu_mul_quant_act"):
+                 "dgq_unpack_weights_zp", "dgq_linear_a8w4_zp", "dgq_linear_a8w4_zp_acc", "dgq_quantize_weights_grid", "dgq_quant_act_static", "dgq_smooth_scales", "dgq_smooth_apply", "dgq_silu_mul_quant_act", "dgq_rmsnorm_quant_act"):
         getattr(L, name).restype = i
     return L
 
@@ -263,6 +264,18 @@ def silu_mul_quant_act(gate_up: torch.Tensor, xq: torch.Tensor = None, sx: torch
     if sx is None:
         sx = torch.empty(M, dtype=torch.float32, device=gate_up.device)
     _check(lib.dgq_silu_mul_quant_act(_ptr(gate_up), M, I2 // 2, _ptr(xq), _ptr(sx), _stream()), "dgq_silu_mul_quant_act")
+    return xq, sx
+
+
+def rmsnorm_quant_act(x: torch.Tensor, gamma: torch.Tensor, eps: float, xq: torch.Tensor = None, sx: torch.Tensor = None):
+    """dgq_rmsnorm_quant_act: per-token quantized RMSNorm(x) * gamma: (xq int8 [M,K], sx float32 [M])."""
+    _dev(x, torch.float16, "x"); _dev(gamma, torch.float16, "gamma")
+    M, K = x.shape
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if sx is None:
+        sx = torch.empty(M, dtype=torch.float32, device=x.device)
+    _check(lib.dgq_rmsnorm_quant_act(_ptr(x), _ptr(gamma), M, K, eps, _ptr(xq), _ptr(sx), _stream()), "dgq_rmsnorm_quant_act")
     return xq, sx
 
 

@@ -254,6 +254,17 @@ dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k
     return hip_result(dgq::launch_smooth_apply(W, X, k, M, K, N, Wout, Xout, static_cast<hipStream_t>(stream)));
 }
 
+dgq_status dgq_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps, int8_t *xq,
+                                 float *sx, void *stream)
+{
+    if (!x || !gamma || !xq || !sx) return DGQ_ERR_NULL;
+    if (M < 1 || K < 128 || K > 24576 || (K % 128) != 0) return DGQ_ERR_SHAPE;
+    if (!(eps >= 0.0f) || !(eps < 1.0f)) return DGQ_ERR_RANGE;
+    if (!aligned16(x) || !aligned16(gamma) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u))
+        return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_rmsnorm_quant_act(x, gamma, M, K, eps, xq, sx, static_cast<hipStream_t>(stream)));
+}
+
 dgq_status dgq_silu_mul_quant_act(const uint16_t *gate_up, int M, int I, int8_t *xq, float *sx, void *stream)
 {
     if (!gate_up || !xq || !sx) return DGQ_ERR_NULL;

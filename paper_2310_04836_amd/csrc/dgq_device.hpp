@@ -106,6 +106,8 @@ __device__ __forceinline__ unsigned short scaled_sum_to_half_bits(float scale, i
 
 // ---- kernel launchers (defined one per .hip file) ----------------------------------
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
+hipError_t launch_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps, int8_t *xq,
+                                    float *sx, hipStream_t st);
 hipError_t launch_silu_mul_quant_act(const uint16_t *GU, int M, int I, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_quant_act_static(const uint16_t *x, int M, int K, float s, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_smooth_scales(const uint16_t *X, int M, int K, int r, float *k, float *z, hipStream_t st);

@@ -177,6 +177,97 @@ __global__ __launch_bounds__(kThreads) void silu_mul_quant_act_kernel(const uint
     }
 }
 
+// RMSNorm fused with the per-token quantizer: y = fp16(float(x * r * gamma)), r = 1/sqrt(mean x^2 + eps),
+// everything up to the two roundings in fp64.  The sum of squares is added in fp64 by a tree over
+// threads; that order differs from a running sum only in the last bits of a double, far below what
+// survives the rounding to fp32 and fp16.  y is kept in registers as fp16 bits (K <= 2048 * VPT).
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <int VPT>
+__global__ __launch_bounds__(kThreads) void rmsnorm_quant_act_kernel(const uint16_t *__restrict__ x,
+                                                                     const uint16_t *__restrict__ gamma, int M, int K,
+                                                                     float eps, int8_t *__restrict__ xq,
+                                                                     float *__restrict__ sx)
+{
+    __shared__ double wave_s[kThreads / 64];
+    __shared__ uint32_t wave_m[kThreads / 64];
+    const int m = blockIdx.x;
+    const int nvec = K >> 3;
+    const uint4 *row = reinterpret_cast<const uint4 *>(x + (size_t)m * K);
+    const uint4 *grow = reinterpret_cast<const uint4 *>(gamma);
+    uint2 *dst = reinterpret_cast<uint2 *>(xq + (size_t)m * K);
+
+    uint4 cache[VPT];
+    double ss = 0.0;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        cache[i] = idx < nvec ? row[idx] : make_uint4(0, 0, 0, 0);
+        const uint32_t w[4] = {cache[i].x, cache[i].y, cache[i].z, cache[i].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const double lo = (double)half_bits_to_float(w[k] & 0xFFFFu), hi = (double)half_bits_to_float(w[k] >> 16);
+            ss += lo * lo;
+            ss += hi * hi;
+        }
+    }
+    ss = wave_sum_f64(ss);
+    if ((threadIdx.x & 63) == 0) wave_s[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = wave_s[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) ss += wave_s[w];
+    const double r = 1.0 / sqrt(ss / (double)K + (double)eps);
+
+    uint32_t mx = 0;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        if (idx < nvec) {
+            const uint4 g = grow[idx];
+            const uint32_t w[4] = {cache[i].x, cache[i].y, cache[i].z, cache[i].w};
+            const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+            uint32_t y[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                y[k] = 0;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const double xv = (double)half_bits_to_float((w[k] >> (16 * h)) & 0xFFFFu);
+                    const double gv = (double)half_bits_to_float((gw[k] >> (16 * h)) & 0xFFFFu);
+                    const float p32 = (float)(xv * r * gv);
+                    y[k] |= (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)p32) << (16 * h);
+                }
+            }
+            cache[i] = make_uint4(y[0], y[1], y[2], y[3]);
+        }
+        mx = absmax_bits(cache[i], mx);
+    }
+    mx = wave_max_u32(mx);
+    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = wave_m[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / 64; ++w) mx = wave_m[w] > mx ? wave_m[w] : mx;
+    const float a = half_bits_to_float(mx);
+    float inv = 0.0f, s = 0.0f;
+    if (a != 0.0f) {
+        s = a / 127.0f;
+        inv = 127.0f / a;
+    }
+    if (threadIdx.x == 0) sx[m] = s;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int idx = threadIdx.x + i * kThreads;
+        if (idx < nvec) dst[idx] = quant_vec(cache[i], inv);
+    }
+}
+
 // Static tensor-wise scale (the "S" scheme of Section 4.1 / Table 5; symmetric form of Eq. 1 with
 // 8 bits): xq = clamp(round(x / s), -127, 127) with one IEEE division per element, and every
 // token's scale is s.  One thread per eight values; no reduction.
@@ -213,6 +304,22 @@ hipError_t launch_quant_act_static(const uint16_t *x, int M, int K, float s, int
     const size_t blocks = (nvec + kThreads - 1) / kThreads;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     hipLaunchKernelGGL(quant_act_static_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, nvec, M, s, xq, sx);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps, int8_t *xq,
+                                    float *sx, hipStream_t st)
+{
+    dim3 grid(M), block(kThreads);
+    const int nvec = K / 8;
+    if (nvec <= 2 * kThreads)
+        hipLaunchKernelGGL(rmsnorm_quant_act_kernel<2>, grid, block, 0, st, x, gamma, M, K, eps, xq, sx);
+    else if (nvec <= 6 * kThreads)
+        hipLaunchKernelGGL(rmsnorm_quant_act_kernel<6>, grid, block, 0, st, x, gamma, M, K, eps, xq, sx);
+    else if (nvec <= 12 * kThreads)
+        hipLaunchKernelGGL(rmsnorm_quant_act_kernel<12>, grid, block, 0, st, x, gamma, M, K, eps, xq, sx);
+    else
+        return hipErrorInvalidValue;   // K > 24576: checked by the caller
     return hipGetLastError();
 }
 

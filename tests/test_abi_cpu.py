@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 25 and len(set(names)) == 25
+    assert len(names) == 26 and len(set(names)) == 26
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -108,6 +108,9 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_silu_mul_quant_act(good, 1, 100, good, good, None) == -2
     assert L.dgq_silu_mul_quant_act(good, 1, 24704, good, good, None) == -2
     assert L.dgq_silu_mul_quant_act(odd, 1, 128, good, good, None) == -3
+    assert L.dgq_rmsnorm_quant_act(good, good, 1, 128, f(-1e-5), good, good, None) == -4
+    assert L.dgq_rmsnorm_quant_act(good, None, 1, 128, f(1e-5), good, good, None) == -1
+    assert L.dgq_rmsnorm_quant_act(good, good, 1, 24704, f(1e-5), good, good, None) == -2
     # measurement aids
     assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
     assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2

@@ -663,3 +663,13 @@ def test_mlp_block_against_the_oracle(dgq, torch):
         assert_fp16_close(out, oout)
     else:
         pytest.fail("gate+up outputs differ in bits; the chain cannot be compared exactly")
+
+
+@pytest.mark.parametrize("M,K", [(1, 128), (16, 4096), (5, 5120), (3, 8192), (300, 1024), (2, 22016)])
+def test_rmsnorm_quant_act_bit_exact(dgq, torch, M, K):
+    x = workloads.activations(M, K, M + K)
+    gamma = np.random.default_rng(K).normal(1, 0.3, K).astype(np.float16)
+    xq, sx = dgq.rmsnorm_quant_act(dev(torch, x), dev(torch, gamma), 1e-5)
+    oxq, osx, _ = oracle.rmsnorm_quant_act(x, gamma, 1e-5)
+    assert np.array_equal(host(sx), osx)
+    assert np.array_equal(host(xq), oxq)
