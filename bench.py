@@ -3,7 +3,9 @@
 
 A "step" is one pass of the whole hot path (per-token activation quantization, then the
 fused expand + INT8 GEMM + scale epilogue) over one batch of synthetic input, for every
-(M, layer shape) pair of the chosen workload.  Inputs are resident in HBM before the timed
+(M, layer shape) pair of the chosen workload.  By default each pair is one library call
+(dgq_quant_linear_a8w4), which is a single kernel where the decode kernel can quantize its
+own activations and the two kernels otherwise; --quant separate makes the two calls.  Inputs are resident in HBM before the timed
 region.  Packed weights exist in several copies that the steps rotate through, so that the
 weights of a launch are not left in the 256 MB last-level cache by the previous one.
 
@@ -39,7 +41,8 @@ WORKLOADS = {
 # (FETCH_SIZE reads 0.5 GiB per GiB read: x2.0; WRITE_SIZE x1.0).  Figures and commands are in
 # profiles/; a workload that has not been profiled reports null.
 TRAFFIC_BYTES = {
-    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14135.6 + 175.0) * 1024,
+    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"): (2.0 * 14430.5 + 62.5) * 1024,
+    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14126.0 + 175.0) * 1024,
     ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"): (2.0 * 75912.5 + 34112.0) * 1024,
 }
 
@@ -56,10 +59,12 @@ def act_quant_bytes(M, K):
 SCALE_BYTES = 1   # bytes per (group, column) in the scale array: 1 = S2, 2 = (S2, ZP); set by --format
 
 
-def algorithmic_bytes(M, K, N, g):
+def algorithmic_bytes(M, K, N, g, in_kernel_quant=False):
     """Bytes one linear launch must move: packed weights + group scales (and zero points) + channel
-    scales, quantized activations + token scales, fp16 output."""
-    return K * N // 2 + SCALE_BYTES * (K // g) * N + 4 * N + M * K + 4 * M + 2 * M * N
+    scales, quantized activations + token scales (fp16 activations if the kernel quantizes them
+    itself), fp16 output."""
+    x_bytes = 2 * M * K if in_kernel_quant else M * K + 4 * M
+    return K * N // 2 + SCALE_BYTES * (K // g) * N + 4 * N + x_bytes + 2 * M * N
 
 
 def main():
@@ -74,6 +79,10 @@ def main():
     ap.add_argument("--act", default="dynamic", choices=["dynamic", "static"],
                     help="activation quantizer: per-token dynamic (the benchmark configs) or one static "
                          "tensor-wise scale fixed before the timed region (Section 4.1)")
+    ap.add_argument("--quant", default="fused", choices=["fused", "separate"],
+                    help="dynamic quantizer: fused = dgq_quant_linear_a8w4, one call per layer (one kernel where a "
+                         "workgroup of the decode kernel covers all of K, else the two kernels); separate = "
+                         "dgq_quant_act then dgq_linear_a8w4")
     ap.add_argument("--mlp-block", action="store_true",
                     help="time the gated MLP as a chain instead of independent layers: RMSNorm fused with the quantizer, "
                          "gate+up linear, silu*mul fused with the quantizer, down linear")
@@ -85,6 +94,8 @@ def main():
     args = ap.parse_args()
     if args.mlp_block:
         args.no_cpu_baseline = True      # the oracle leg times independent layers, not this chain
+    if args.act == "static" or args.mlp_block:
+        args.quant = "separate"          # those quantizers are kernels of their own
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path is a single-GPU kernel library); "
                  "--gpus %d is not supported, use --gpus 1" % args.gpus)
@@ -136,7 +147,7 @@ def main():
     for M in Ms:
         for name, (K, N) in shapes.items():
             acts[(M, name)] = torch.from_numpy(workloads.activations(M, K, seed + M, frac, mult)).to(dev)
-            wsb = dgq.linear_workspace_bytes(M, N, K, g)
+            wsb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g))
             bufs[(M, name)] = (torch.empty((M, K), dtype=torch.int8, device=dev),
                                torch.empty(M, dtype=torch.float32, device=dev),
                                torch.empty((M, N), dtype=torch.float16, device=dev),
@@ -147,8 +158,15 @@ def main():
 
     static_scale = {k: float(v.float().abs().max().item() / 127.0) for k, v in acts.items()} if args.act == "static" else {}
 
+    # pairs for which the one-call form is a single kernel that quantizes its own activations
+    in_kernel = {(M, name): args.quant == "fused" and dgq.quant_linear_plan(M, N, K, g).startswith("quant_linear")
+                 for M in Ms for name, (K, N) in shapes.items()}
+
     def one_pair(M, name, copy):
         xq, sx, out, ws = bufs[(M, name)]
+        if args.quant == "fused":
+            dgq.quant_linear_a8w4(acts[(M, name)], packed[name][copy % ncopies], out, None, ws)
+            return
         if args.act == "static":
             dgq.quant_act_static(acts[(M, name)], static_scale[(M, name)], xq, sx)
         else:
@@ -206,7 +224,12 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
 
-    step_bytes = sum(algorithmic_bytes(M, K, N, g) + act_quant_bytes(M, K) for M in Ms for K, N in shapes.values())
+    def pair_bytes(M, name):
+        K, N = shapes[name]
+        if in_kernel[(M, name)]:
+            return algorithmic_bytes(M, K, N, g, True)
+        return algorithmic_bytes(M, K, N, g) + act_quant_bytes(M, K)
+    step_bytes = sum(pair_bytes(M, name) for M in Ms for name in shapes)
     if args.mlp_block:   # the producer reads gate and up (fp16) and writes int8 + scales; no separate quantizer for down
         Kd = shapes["down"][0]
         step_bytes += sum(2 * M * 2 * Kd + M * Kd + 4 * M - act_quant_bytes(M, Kd) for M in Ms)
@@ -222,7 +245,10 @@ def main():
 
         def body():
             for c in range(launches):
-                dgq.linear_a8w4(xq, sx, packed[name][c], out, ws)
+                if in_kernel[(M, name)]:
+                    dgq.quant_linear_a8w4(acts[(M, name)], packed[name][c], out, None, ws)
+                else:
+                    dgq.linear_a8w4(xq, sx, packed[name][c], out, ws)
         if args.no_graph:
             run = body
         else:
@@ -247,16 +273,16 @@ def main():
     for M in Ms:
         for name, (K, N) in shapes.items():
             pair_sec[(M, name)] = time_linear(M, name, reps_pair)
-            sym = dgq.linear_plan(M, N, K, g)
+            sym = dgq.quant_linear_plan(M, N, K, g) if in_kernel[(M, name)] else dgq.linear_plan(M, N, K, g)
             if args.format == "zp":      # same plan, the kernels of the zero-point form
                 sym = sym.replace("_kernel<", "_zp_kernel<")
             groups.setdefault(sym, []).append((M, name))
     kernel_name = max(groups, key=lambda k: sum(pair_sec[p] for p in groups[k]))
     dpairs = groups[kernel_name]
     dsec = sum(pair_sec[p] for p in dpairs) / len(dpairs)
-    dbytes = sum(algorithmic_bytes(M, *shapes[name], g) for M, name in dpairs) / len(dpairs)
+    dbytes = sum(algorithmic_bytes(M, *shapes[name], g, in_kernel[(M, name)]) for M, name in dpairs) / len(dpairs)
     dops = sum(2 * M * shapes[name][0] * shapes[name][1] for M, name in dpairs) / len(dpairs)
-    hbm_bound = not kernel_name.startswith("linear_tiled")
+    hbm_bound = "linear_tiled" not in kernel_name
     if hbm_bound:
         roofline = {"bound": "hbm", "achieved": dbytes / dsec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
@@ -291,8 +317,8 @@ def main():
                 fsec = 1e-3 * e0.elapsed_time(e1) / reps
                 del wh
                 a16_ms += fsec * 1e3
-                b = algorithmic_bytes(M, K, N, g)
-                row = {"shape": name, "M": M, "K": K, "N": N, "us": round(sec * 1e6, 2),
+                b = algorithmic_bytes(M, K, N, g, in_kernel[(M, name)])
+                row = {"shape": name, "quantizes_in_kernel": in_kernel[(M, name)], "M": M, "K": K, "N": N, "us": round(sec * 1e6, 2),
                        "GBps": round(b / sec / 1e9, 1), "hbm_frac": round(b / sec / 1e9 / HBM_PEAK_GBS, 4),
                        "TOPS": round(2 * M * K * N / sec / 1e12, 2),
                        "mfma_frac": round(2 * M * K * N / sec / 1e12 / INT8_PEAK_TOPS, 4),
@@ -424,6 +450,9 @@ def main():
         "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
                    "layers_per_step": list(shapes), "weight_copies": ncopies,
                    "activation_quantizer": args.act, "mlp_block": bool(args.mlp_block),
+                   "quantizer_call": ("one call with the linear (dgq_quant_linear_a8w4); in-kernel for %d of %d launches"
+                                      % (sum(in_kernel.values()), len(in_kernel))) if args.quant == "fused"
+                                     else "separate kernel before each linear",
                    "weight_format": ("unsigned nibbles, per-group zero points, S2 <= 127, two-phase grid search"
                                      if args.format == "zp" else "signed nibbles, S2 <= 15, RTN"),
                    "launch": "eager" if args.no_graph else "hip_graph"},

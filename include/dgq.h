@@ -284,6 +284,35 @@ DGQ_API dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight,
 DGQ_API int dgq_force_path(int path);
 
 /*
+ * dgq_quant_act followed by dgq_linear_a8w4 (dgq_linear_a8w4_zp) as one call: the per-token
+ * dynamic quantizer of Section 3.1 / 4.1 in front of all three lines of Eq. 2,
+ *   out = linear_a8w4(quant_act(x)),
+ * with the same bits as the two calls.
+ *   x          in  [M][K] fp16 (raw bits)
+ *   qweight, scales (scales_zp), s1, out, M, N, K, group: as for dgq_linear_a8w4(_zp)
+ *   sx_out     out [M] float, optional (may be NULL): the token scales the quantizer derived
+ *   workspace  scratch of at least dgq_quant_linear_workspace_bytes(); may be NULL when
+ *              that is 0
+ * For M <= 16, K <= 12288 and M * (K + 16) <= 49152 (up to four tokens of a LLaMA-7B layer)
+ * ONE kernel does both: every workgroup of the weight-streaming kernel needs whole token rows
+ * anyway, so its threads share out the quantizer's work while the first weight loads are in
+ * flight and hand the INT8 rows on through LDS; xq and sx never go through memory and the
+ * second launch disappears.  Every workgroup repeats the quantizer, which is why this is limited
+ * to small M * K.  Otherwise the call enqueues the two kernels with xq and sx placed in the
+ * workspace.  dgq_quant_linear_plan names the GEMM kernel as
+ * dgq_linear_plan does ("quant_linear_decode_kernel<2, 2, 128>" for the one-kernel form).
+ * Errors as for dgq_quant_act and dgq_linear_a8w4.
+ */
+DGQ_API dgq_status dgq_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
+DGQ_API dgq_status dgq_quant_linear_a8w4(const uint16_t *x, const void *qweight, const void *scales,
+                                 const float *s1, uint16_t *out, float *sx_out, int M, int N, int K,
+                                 int group, void *workspace, size_t workspace_bytes, void *stream);
+DGQ_API dgq_status dgq_quant_linear_a8w4_zp(const uint16_t *x, const void *qweight, const void *scales_zp,
+                                    const float *s1, uint16_t *out, float *sx_out, int M, int N, int K,
+                                    int group, void *workspace, size_t workspace_bytes, void *stream);
+DGQ_API dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes);
+
+/*
  * Measurement aid (host function, nothing launched): writes into buf (at least 96 bytes)
  * the name, with template arguments, of the GEMM kernel that dgq_linear_a8w4 would launch
  * for this problem under the current dgq_force_path() setting, e.g.

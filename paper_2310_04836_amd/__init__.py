@@ -66,6 +66,13 @@ def _load() -> ctypes.CDLL:
     L.dgq_probe_read.argtypes = [vp, sz, vp, i, vp]
     L.dgq_probe_mfma.argtypes = [vp, sz, i, vp, i, vp]
     L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
+    L.dgq_quant_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
+    L.dgq_quant_linear_workspace_bytes.argtypes = [i, i, i, i, psz]
+    L.dgq_quant_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_quant_linear_a8w4_zp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    for name in ("dgq_quant_linear_plan", "dgq_quant_linear_workspace_bytes", "dgq_quant_linear_a8w4",
+                 "dgq_quant_linear_a8w4_zp"):
+        getattr(L, name).restype = i
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
                  "dgq_probe_read", "dgq_probe_mfma", "dgq_linear_plan", "dgq_packed_sizes_zp", "dgq_pack_weights_zp",
@@ -307,6 +314,43 @@ def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch
     _check(fn(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
               M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
     return out
+
+
+def quant_linear_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    """dgq_quant_linear_workspace_bytes."""
+    n = ctypes.c_size_t(0)
+    _check(lib.dgq_quant_linear_workspace_bytes(M, N, K, group, ctypes.byref(n)), "dgq_quant_linear_workspace_bytes")
+    return n.value
+
+
+def quant_linear_a8w4(x: torch.Tensor, pw: PackedWeight, out: torch.Tensor = None, sx_out: torch.Tensor = None,
+                      workspace: torch.Tensor = None) -> torch.Tensor:
+    """dgq_quant_linear_a8w4: fp16 [M,N] = linear_a8w4(quant_act(x)) as one call (one kernel for small M)."""
+    _dev(x, torch.float16, "x")
+    if sx_out is not None:
+        _dev(sx_out, torch.float32, "sx_out")
+    M, K = x.shape
+    if K != pw.K:
+        raise ValueError("x has K=%d but the packed weight has K=%d" % (K, pw.K))
+    if sx_out is not None and sx_out.numel() != M:
+        raise ValueError("sx_out must hold M floats")
+    if out is None:
+        out = torch.empty((M, pw.N), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        nbytes = quant_linear_workspace_bytes(M, pw.N, K, pw.group)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=x.device) if nbytes else None
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = lib.dgq_quant_linear_a8w4_zp if pw.zp_form else lib.dgq_quant_linear_a8w4
+    _check(fn(_ptr(x), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out), _ptr(sx_out),
+              M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_quant_linear_a8w4")
+    return out
+
+
+def quant_linear_plan(M: int, N: int, K: int, group: int) -> str:
+    """dgq_quant_linear_plan: name of the GEMM kernel dgq_quant_linear_a8w4 would launch."""
+    buf = ctypes.create_string_buffer(128)
+    _check(lib.dgq_quant_linear_plan(M, N, K, group, buf, 128), "dgq_quant_linear_plan")
+    return buf.value.decode()
 
 
 def linear_plan(M: int, N: int, K: int, group: int) -> str:

@@ -68,6 +68,49 @@ dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_byte
     }
 }
 
+// The one-call form quantizes inside the decode kernel when one workgroup covers all of K.
+bool quantizes_in_kernel(int M, int K, int forced)
+{
+    if (pick_path(M, forced) != kPathStream) return false;
+    return dgq::decode_plan(K).ksplit == 1 && (long long)M * (K + 16) <= dgq::kQuantDecodeStageBytes;
+}
+
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+dgq_status quant_linear(const uint16_t *x, const void *qweight, const void *scales, int zp_form, const float *s1,
+                        uint16_t *out, float *sx_out, int M, int N, int K, int group, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    if (!x || !qweight || !scales || !s1 || !out) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (!aligned16(x) || !aligned16(qweight) || !aligned16(scales) || !aligned16(out) ||
+        (reinterpret_cast<uintptr_t>(s1) & 3u) || (reinterpret_cast<uintptr_t>(sx_out) & 3u))
+        return DGQ_ERR_ALIGN;
+    const int forced = g_force_path.load(std::memory_order_relaxed);
+    if ((forced == kPathStream || forced == kPathStreamGeneric) && M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (quantizes_in_kernel(M, K, forced)) {
+        dgq::LinearArgs a{nullptr, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
+                          s1, out, nullptr, M, N, K, group, zp_form, x, sx_out};
+        return hip_result(dgq::launch_linear_decode(a, nullptr, st));
+    }
+    // two launches, xq and sx in the workspace: [xq: M*K][sx: 4*M][what the linear needs]
+    const size_t xq_bytes = round256((size_t)M * K), sx_bytes = round256((size_t)M * sizeof(float));
+    if (!workspace || workspace_bytes < xq_bytes + sx_bytes) return DGQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DGQ_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace);
+    int8_t *xq = reinterpret_cast<int8_t *>(ws);
+    float *sx = sx_out ? sx_out : reinterpret_cast<float *>(ws + xq_bytes);
+    dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
+                      s1, out, nullptr, M, N, K, group, zp_form, nullptr, nullptr};
+    const int path = pick_path(M, forced);
+    if (path == kPathStreamGeneric && zp_form) return DGQ_ERR_SHAPE;
+    if (workspace_bytes < xq_bytes + sx_bytes + workspace_needed(path, M, N, K)) return DGQ_ERR_WORKSPACE;
+    if (dgq_status q = hip_result(dgq::launch_quant_act(x, M, K, xq, sx, st))) return q;
+    return run_linear(a, ws + xq_bytes + sx_bytes, workspace_bytes - xq_bytes - sx_bytes, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -308,6 +351,47 @@ dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight, const v
                                   void *stream)
 {
     return linear_acc(xq, qweight, scales_zp, 1, acc_out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes)
+{
+    if (!bytes) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    const int forced = g_force_path.load(std::memory_order_relaxed);
+    if (quantizes_in_kernel(M, K, forced))
+        *bytes = 0;
+    else
+        *bytes = round256((size_t)M * K) + round256((size_t)M * sizeof(float)) +
+                 workspace_needed(pick_path(M, forced), M, N, K);
+    return DGQ_OK;
+}
+
+dgq_status dgq_quant_linear_a8w4(const uint16_t *x, const void *qweight, const void *scales, const float *s1,
+                                 uint16_t *out, float *sx_out, int M, int N, int K, int group, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    return quant_linear(x, qweight, scales, 0, s1, out, sx_out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_quant_linear_a8w4_zp(const uint16_t *x, const void *qweight, const void *scales_zp, const float *s1,
+                                    uint16_t *out, float *sx_out, int M, int N, int K, int group, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    return quant_linear(x, qweight, scales_zp, 1, s1, out, sx_out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes)
+{
+    if (!buf) return DGQ_ERR_NULL;
+    if (M < 1 || buf_bytes < 96) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (quantizes_in_kernel(M, K, g_force_path.load(std::memory_order_relaxed))) {
+        const dgq::DecodePlan p = dgq::decode_plan(K);
+        std::snprintf(buf, buf_bytes, "quant_linear_decode_kernel<%d, %d, %d>", p.spw, p.pf, group);
+        return DGQ_OK;
+    }
+    return dgq_linear_plan(M, N, K, group, buf, buf_bytes);
 }
 
 dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes)

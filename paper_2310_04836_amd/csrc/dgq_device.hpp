@@ -104,6 +104,77 @@ __device__ __forceinline__ unsigned short scaled_sum_to_half_bits(float scale, i
     return __builtin_bit_cast(unsigned short, (_Float16)p);
 }
 
+// ---- per-token activation quantizer arithmetic (Section 3.1, symmetric, 8 bits) -------
+// Shared by the stand-alone quantizer kernels and by the decode kernel that quantizes its own
+// activations, so that both produce the same bytes: the absolute maximum a of a token is taken
+// on fp16 bit patterns (integer order = numeric order for non-negative values), the caller forms
+// sx = a / 127 and inv = 127 / a (one IEEE division each), and every element becomes
+// clamp(rint(float(x) * inv), -127, 127).
+__device__ __forceinline__ uint32_t absmax_bits(const uint4 &v, uint32_t m)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
+        m = lo > m ? lo : m;
+        m = hi > m ? hi : m;
+    }
+    return m;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+
+__device__ __forceinline__ uint32_t quant_one(uint32_t hbits, float inv)
+{
+    float q = rintf(half_bits_to_float(hbits) * inv);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (uint32_t)((int)q) & 0xFFu;
+}
+
+__device__ __forceinline__ uint2 quant_vec(const uint4 &v, float inv)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        b[2 * i] = quant_one(w[i] & 0xFFFFu, inv);
+        b[2 * i + 1] = quant_one(w[i] >> 16, inv);
+    }
+    uint2 r;
+    r.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+    r.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
+    return r;
+}
+
+// The same bytes as quant_vec for finite inputs, in about a quarter of the instructions, for
+// the decode kernel in which every workgroup quantizes all tokens again.  |x * inv| never
+// exceeds 127 * (1 + 2^-23) because |x| <= a and inv = fl(127 / a), so the clamp is idle; adding
+// 1.5 * 2^23 to the fp32 product rounds it to the nearest integer, ties to even, exactly as
+// rintf does, and leaves that integer's two's complement in the low mantissa bits.
+__device__ __forceinline__ uint32_t quant_bits_fast(uint32_t hbits, float inv)
+{
+    const float t = half_bits_to_float(hbits) * inv;
+    const float r = t + 12582912.0f;
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ uint2 quant_vec_fast(const uint4 &v, float inv)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        b[2 * i] = quant_bits_fast(w[i] & 0xFFFFu, inv);
+        b[2 * i + 1] = quant_bits_fast(w[i] >> 16, inv);
+    }
+    uint2 r;
+    r.x = (b[0] & 0xFFu) | ((b[1] & 0xFFu) << 8) | ((b[2] & 0xFFu) << 16) | (b[3] << 24);
+    r.y = (b[4] & 0xFFu) | ((b[5] & 0xFFu) << 8) | ((b[6] & 0xFFu) << 16) | (b[7] << 24);
+    return r;
+}
+
 // ---- kernel launchers (defined one per .hip file) ----------------------------------
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps, int8_t *xq,
@@ -134,12 +205,18 @@ struct LinearArgs {
     int32_t *acc_out;      // null in fp16 mode
     int M, N, K, group;
     int zp;                // form of `scales`: 0 = S2 bytes (zero point 8), 1 = (S2, ZP) byte pairs
+    // Only for the decode kernel that quantizes its own activations (then xq and sx are null):
+    const uint16_t *x16;   // fp16 bits [M][K]
+    float *sx_out;         // optional: the token scales it derived, [M]
 };
 // Largest M the weight-streaming kernels take.
 constexpr int kStreamMaxM = 64;
 // Decode kernel (one 16-token tile, activations resident in registers).
 constexpr int kDecodeMaxM = 16;
 constexpr int kDecodeMaxStepsPerWave = 6;  // 8 would spill at 128 VGPRs
+// The variant that quantizes its own activations stages xq[M][K] in LDS that the column tiles
+// use afterwards (48 KiB), and every workgroup repeats the quantizer: only for small M * K.
+constexpr int kQuantDecodeStageBytes = 49152;
 struct DecodePlan {
     int spw;     // steps of 128 k per wavefront (template SPW)
     int pf;      // column tiles prefetched ahead (template PF)

@@ -18,6 +18,14 @@
 //   - If K is too long for 16 wavefronts x SPW steps, several workgroups split K and write
 //     raw INT32 partial tiles to the workspace; a small second kernel adds them and runs
 //     the epilogue.
+//   - FQ variant: the kernel is handed the fp16 activations and runs the per-token quantizer
+//     (Section 3.1, symmetric 8 bits) itself.  A workgroup that is not split over K needs every
+//     token's whole row anyway, so while its first weight loads are in flight its 1024 threads
+//     share the M*K values out evenly, take the token maxima with LDS atomics, round to INT8
+//     and leave the bytes in LDS (in the buffers the column tiles use later), from where every
+//     wavefront fetches its slice.  Neither xq nor sx goes through memory and the separate
+//     quantizer launch disappears.  Same arithmetic as quant_act_kernel, hence the same bits.
+//     Every workgroup repeats the quantizer, so this pays only for small M*K.
 #include "dgq_device.hpp"
 
 namespace dgq {
@@ -27,14 +35,22 @@ constexpr int kWaves = 16;
 // A workgroup keeps the finished INT32 tiles of all its column tiles in LDS and stores
 // them after the weight loop, so that the loop itself contains no global stores.
 constexpr int kMaxTilesPerWg = 32;
+struct DecodeLds {
+    int red[2][kWaves][256];           // partial tiles of the 16 wavefronts, double buffered
+    int sums[kMaxTilesPerWg][256];     // finished INT32 tiles
+};
+static_assert(sizeof(DecodeLds::red) / 2 + sizeof(DecodeLds::sums) == kQuantDecodeStageBytes, "staging area");
 
 // ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes (compile-time).
-template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP>
+// FQ: activations arrive as fp16 and are quantized here (needs ksplit == 1, no ACC, no PARTIAL).
+template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP, bool FQ>
 __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int32_t *partial)
 {
-    __shared__ int red[2][kWaves][256];
-    __shared__ int sums[kMaxTilesPerWg][256];
-
+    static_assert(!FQ || (!ACC && !PARTIAL), "the quantizing variant writes fp16 only");
+    // One block, so that red[1] and sums are contiguous (the FQ variant stages INT8 rows there).
+    __shared__ DecodeLds lds;
+    int (&red)[2][kWaves][256] = lds.red;
+    int (&sums)[kMaxTilesPerWg][256] = lds.sums;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15;
@@ -64,7 +80,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
     const int ep_m = 4 * ((ep_x & 63) >> 4) + (ep_x >> 6);
     float ep_sx = 0.0f, ep_s1[kEarly] = {0.0f, 0.0f, 0.0f};
     if (!ACC && !PARTIAL && ep_m < a.M) {
-        ep_sx = a.sx[ep_m];
+        if (!FQ) ep_sx = a.sx[ep_m];
 #pragma unroll
         for (int k = 0; k < kEarly; ++k) {
             const int ti = (threadIdx.x >> 8) + 4 * k;
@@ -72,18 +88,111 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
         }
     }
 
+    // FQ (called once by every wavefront, at a point all of them reach): the per-token quantizer
+    // run by the whole workgroup, then this wavefront's slice fetched from LDS.
+    //   part[16][64]  token maxima per lane slot (fp16 bit patterns), in red[0]: a lane only ever
+    //                 updates its own slot, so the LDS atomics of a wavefront do not serialize
+    //   tinv, tsx     127/a and a/127 per token, behind part in red[0]
+    //   stage         xq[M][K + 16], in red[1] and sums (kQuantDecodeStageBytes).  The 16 bytes
+    //                 between rows move each token to the next four LDS banks, so that the 16
+    //                 lanes that read the same k of 16 tokens do not collide.
+    // Nothing here collides with the column tiles: a wavefront writes red[0] and reads or writes
+    // red[1] and sums only behind barriers that come after its last access below.
+    constexpr int kVec = FQ ? kQuantDecodeStageBytes / 8 / (kWaves * 64) : 1;   // 8-value vectors per thread
+    const int vpr = a.K >> 3;                                                  // vectors per row
+    const int nvec = a.M * vpr;
+    uint4 v[kVec];
+    int tok[kVec];
+    if constexpr (FQ) {
+        // The fp16 loads go out before the first weight loads, so that waiting for them leaves
+        // the weight loads in flight.
+        const float inv_vpr = 1.0f / (float)vpr;
+        const uint4 *xv = reinterpret_cast<const uint4 *>(a.x16);
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+            const int idx = threadIdx.x + i * (kWaves * 64);
+            v[i] = idx < nvec ? xv[idx] : make_uint4(0, 0, 0, 0);
+            // idx / vpr without an integer division: (idx + 0.5) / vpr is at least 0.5 / vpr away
+            // from an integer, far more than the rounding of this product (idx < 2^13, vpr < 2^13)
+            tok[i] = (int)(((float)idx + 0.5f) * inv_vpr);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    auto quantize_rows = [&](uint4 (&xa)[SPW][2]) {
+        uint32_t *part = reinterpret_cast<uint32_t *>(&red[0][0][0]);
+        float *tinv = reinterpret_cast<float *>(&red[0][4][0]);
+        float *tsx = tinv + 16;
+        uint8_t *stage = reinterpret_cast<uint8_t *>(&red[1][0][0]);
+        part[threadIdx.x] = 0;                                             // 16 tokens x 64 slots
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+            const int idx = threadIdx.x + i * (kWaves * 64);
+            if (idx < nvec) atomicMax(&part[tok[i] * 64 + lane], absmax_bits(v[i], 0));
+        }
+        __syncthreads();
+        {   // wavefront w finishes token w
+            // maximum over the wavefront with data-parallel-primitive moves (no LDS round trips):
+            // within quads, within rows of 16, then row to row; lane 63 ends up with the result.
+            // A lane whose source is masked off receives 0, the identity of an unsigned maximum.
+            uint32_t mx = part[threadIdx.x];
+#define DGQ_DPP_MAX(CTRL, ROWS)                                                                          \
+    do {                                                                                                 \
+        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx, (CTRL), (ROWS), 0xF, false); \
+        mx = o > mx ? o : mx;                                                                            \
+    } while (0)
+            DGQ_DPP_MAX(0xB1, 0xF);    // quad_perm [1,0,3,2]
+            DGQ_DPP_MAX(0x4E, 0xF);    // quad_perm [2,3,0,1]
+            DGQ_DPP_MAX(0x124, 0xF);   // row_ror 4
+            DGQ_DPP_MAX(0x128, 0xF);   // row_ror 8
+            DGQ_DPP_MAX(0x142, 0xA);   // row_bcast 15 into rows 1 and 3
+            DGQ_DPP_MAX(0x143, 0xC);   // row_bcast 31 into rows 2 and 3
+#undef DGQ_DPP_MAX
+            if (lane == 63) {
+                const float am = half_bits_to_float(mx);
+                tinv[wave] = am != 0.0f ? 127.0f / am : 0.0f;
+                tsx[wave] = am != 0.0f ? am / 127.0f : 0.0f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) {
+            const int idx = threadIdx.x + i * (kWaves * 64);
+            if (idx < nvec)
+                *reinterpret_cast<uint2 *>(stage + tok[i] * (a.K + 16) + (idx - tok[i] * vpr) * 8) =
+                    quant_vec_fast(v[i], tinv[tok[i]]);
+        }
+        ep_sx = tsx[ep_m];
+        if (a.sx_out && blockIdx.x == 0 && threadIdx.x < 256 && (ep_x & 15) == 0 && ep_m < a.M)
+            a.sx_out[ep_m] = ep_sx;
+        __syncthreads();
+        if (nst > 0) {
+            const int m = j < a.M ? j : a.M - 1;
+            const uint4 *sp = reinterpret_cast<const uint4 *>(stage + m * (a.K + 16) + kb * 32);
+#pragma unroll
+            for (int i = 0; i < SPW; ++i) {
+                const int sidx = i < nst ? sb + i : sb;
+                xa[i][0] = sp[sidx * 8];
+                xa[i][1] = sp[sidx * 8 + 1];
+                if (i >= nst) xa[i][0] = xa[i][1] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    uint4 xa[SPW][2];
+
     if (nst > 0) {
         // activations of this slice: loaded once, kept in registers; slots past the end of
         // a short slice hold zeros, so whatever weights they are multiplied with add nothing
-        uint4 xa[SPW][2];
-        const int m = j < a.M ? j : a.M - 1;
-        const uint4 *ap = reinterpret_cast<const uint4 *>(a.xq + (size_t)m * a.K + kb * 32);
+        if constexpr (!FQ) {
+            const int m = j < a.M ? j : a.M - 1;
+            const uint4 *ap = reinterpret_cast<const uint4 *>(a.xq + (size_t)m * a.K + kb * 32);
 #pragma unroll
-        for (int i = 0; i < SPW; ++i) {
-            const int s = i < nst ? sb + i : sb;
-            xa[i][0] = ap[(size_t)s * 8];
-            xa[i][1] = ap[(size_t)s * 8 + 1];
-            if (i >= nst) xa[i][0] = xa[i][1] = make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < SPW; ++i) {
+                const int s = i < nst ? sb + i : sb;
+                xa[i][0] = ap[(size_t)s * 8];
+                xa[i][1] = ap[(size_t)s * 8 + 1];
+                if (i >= nst) xa[i][0] = xa[i][1] = make_uint4(0, 0, 0, 0);
+            }
         }
 
         // per-slot element offsets inside one column tile (a short slice re-reads step sb)
@@ -117,6 +226,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if constexpr (FQ) quantize_rows(xa);
 
 #define DGQ_TILE(P, IT)                                                                              \
     do {                                                                                             \
@@ -160,6 +270,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
 #undef DGQ_LOAD_SLOT
     } else {
         // wavefronts without a slice of K: keep the barrier count and help with the reduction
+        if constexpr (FQ) quantize_rows(xa);
         for (int it = 0; it < my_tiles; ++it) {
             __syncthreads();
             if (threadIdx.x < 256) {
@@ -198,12 +309,23 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
 __global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, int ksplit, int32_t *partial)
 {
-    decode_body<SPW, PF, G, ACC, PARTIAL, false>(a, ksplit, partial);
+    decode_body<SPW, PF, G, ACC, PARTIAL, false, false>(a, ksplit, partial);
 }
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
 __global__ __launch_bounds__(kWaves * 64) void linear_decode_zp_kernel(LinearArgs a, int ksplit, int32_t *partial)
 {
-    decode_body<SPW, PF, G, ACC, PARTIAL, true>(a, ksplit, partial);
+    decode_body<SPW, PF, G, ACC, PARTIAL, true, false>(a, ksplit, partial);
+}
+// fp16 activations in, quantized by the kernel itself (one workgroup sees the whole of K)
+template <int SPW, int PF, int G>
+__global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_kernel(LinearArgs a)
+{
+    decode_body<SPW, PF, G, false, false, false, true>(a, 1, nullptr);
+}
+template <int SPW, int PF, int G>
+__global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_zp_kernel(LinearArgs a)
+{
+    decode_body<SPW, PF, G, false, false, true, true>(a, 1, nullptr);
 }
 
 // Adds the K-split partial tiles and runs the epilogue; four consecutive columns per thread
@@ -259,6 +381,16 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
     dim3 grid(cols * ksplit), block(kWaves * 64);
     int32_t *partial = static_cast<int32_t *>(workspace);
     const bool acc = a.acc_out != nullptr;
+    if (a.x16) {
+        {
+        if (ksplit > 1 || acc || (long long)a.M * (a.K + 16) > kQuantDecodeStageBytes) return hipErrorInvalidValue;
+        if (a.zp)
+            hipLaunchKernelGGL((quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a);
+        else
+            hipLaunchKernelGGL((quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a);
+        return hipGetLastError();
+        }
+    }
     if (ksplit > 1) {
         if (a.zp)
             hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);

@@ -23,45 +23,6 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return v;
 }
 
-__device__ __forceinline__ uint32_t absmax_bits(const uint4 &v, uint32_t m)
-{
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t lo = w[i] & 0x7FFFu, hi = (w[i] >> 16) & 0x7FFFu;
-        m = lo > m ? lo : m;
-        m = hi > m ? hi : m;
-    }
-    return m;
-}
-
-__device__ __forceinline__ float half_bits_to_float(uint32_t h)
-{
-    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
-}
-
-__device__ __forceinline__ uint32_t quant_one(uint32_t hbits, float inv)
-{
-    float q = rintf(half_bits_to_float(hbits) * inv);
-    q = fminf(fmaxf(q, -127.0f), 127.0f);
-    return (uint32_t)((int)q) & 0xFFu;
-}
-
-__device__ __forceinline__ uint2 quant_vec(const uint4 &v, float inv)
-{
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t b[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        b[2 * i] = quant_one(w[i] & 0xFFFFu, inv);
-        b[2 * i + 1] = quant_one(w[i] >> 16, inv);
-    }
-    uint2 r;
-    r.x = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
-    r.y = b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24);
-    return r;
-}
-
 // VPT > 0: each thread caches VPT vectors (K <= 2048 * VPT).  VPT == 0: any K, the row is read
 // twice (the second read hits in cache).
 template <int VPT>

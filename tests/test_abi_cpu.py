@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 26 and len(set(names)) == 26
+    assert len(names) == 30 and len(set(names)) == 30
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -111,11 +111,37 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_rmsnorm_quant_act(good, good, 1, 128, f(-1e-5), good, good, None) == -4
     assert L.dgq_rmsnorm_quant_act(good, None, 1, 128, f(1e-5), good, good, None) == -1
     assert L.dgq_rmsnorm_quant_act(good, good, 1, 24704, f(1e-5), good, good, None) == -2
+    # quantizer + linear as one call
+    n = ctypes.c_size_t(7)
+    assert L.dgq_quant_linear_workspace_bytes(4, 4096, 11008, 128, ctypes.byref(n)) == 0 and n.value == 0
+    assert L.dgq_quant_linear_workspace_bytes(16, 4096, 2944, 128, ctypes.byref(n)) == 0 and n.value == 0
+    assert L.dgq_quant_linear_workspace_bytes(16, 4096, 4096, 128, ctypes.byref(n)) == 0
+    assert n.value == 16 * 4096 + 256                       # two kernels: xq and sx in the workspace
+    assert L.dgq_quant_linear_workspace_bytes(64, 8192, 8192, 128, ctypes.byref(n)) == 0
+    assert n.value == 64 * 8192 + 256 + 4 * 64 * 8192 * 4   # plus the K-split partial sums
+    assert L.dgq_quant_linear_workspace_bytes(0, 4096, 4096, 128, ctypes.byref(n)) == -2
+    assert L.dgq_quant_linear_a8w4(None, good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -1
+    assert L.dgq_quant_linear_a8w4(good, good, good, good, good, None, 1, 16, 100, 128, None, 0, None) == -2
+    assert L.dgq_quant_linear_a8w4(odd, good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -3
+    assert L.dgq_quant_linear_a8w4(good, good, good, good, good, None, 32, 16, 128, 128, None, 0, None) == -5
+    assert L.dgq_quant_linear_a8w4_zp(good, good, good, good, good, None, 32, 16, 128, 128, good, 100, None) == -5
     # measurement aids
     assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
     assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2
     assert L.dgq_probe_mfma(good, 4096, 0, good, 1, None) == -2
     assert L.dgq_probe_mfma(odd, 4096, 1, good, 1, None) == -3
+
+
+def test_quant_linear_plan_names(dgq):
+    # one kernel while a workgroup covers K with at most four steps per wavefront
+    assert dgq.quant_linear_plan(1, 12288, 4096, 128) == "quant_linear_decode_kernel<2, 2, 128>"
+    assert dgq.quant_linear_plan(4, 4096, 11008, 128) == "quant_linear_decode_kernel<6, 1, 128>"
+    assert dgq.quant_linear_plan(5, 8192, 8192, 64) == "quant_linear_decode_kernel<4, 1, 64>"
+    assert dgq.quant_linear_plan(6, 8192, 8192, 64) == "linear_decode_kernel<4, 1, 64, false, false>"   # 6 * 8208 bytes
+    assert dgq.quant_linear_plan(16, 4096, 4096, 128) == "linear_decode_kernel<2, 2, 128, false, false>"
+    assert dgq.quant_linear_plan(2, 8192, 22016, 128) == "linear_decode_kernel<6, 1, 128, false, true>"  # K split
+    assert dgq.quant_linear_plan(17, 4096, 4096, 128) == dgq.linear_plan(17, 4096, 4096, 128)
+    assert dgq.quant_linear_workspace_bytes(4, 12288, 4096, 128) == 0
 
 
 def test_linear_plan_names(dgq):

@@ -673,3 +673,84 @@ def test_rmsnorm_quant_act_bit_exact(dgq, torch, M, K):
     oxq, osx, _ = oracle.rmsnorm_quant_act(x, gamma, 1e-5)
     assert np.array_equal(host(sx), osx)
     assert np.array_equal(host(xq), oxq)
+
+
+# ----------------------------------------------------------------------------
+# quantizer + linear as one call (one kernel while M * (K + 16) <= 48 KiB and K is not split)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("M,K,N,g", [
+    (1, 128, 16, 128), (3, 1024, 272, 64), (16, 2048, 512, 128),      # one step per wavefront, idle wavefronts
+    (1, 4096, 12288, 128), (7, 4096, 1040, 128), (16, 2944, 272, 128),  # two steps; 23 steps: a short wavefront
+    (5, 5120, 528, 64), (8, 6016, 256, 64),                           # three steps (40 and 47 steps)
+    (2, 8192, 1024, 128), (5, 8192, 8192, 64),                        # four steps
+    (7, 6400, 304, 128),                                              # 50 steps: last wavefront short
+    (4, 11008, 4096, 128), (1, 12288, 64, 128),                       # six steps
+    (16, 4096, 12288, 128), (6, 8192, 512, 64),                       # rows do not fit the staging area: two launches
+    (12, 22016, 512, 128),                                            # K split over workgroups: two launches
+    (40, 1408, 272, 128), (130, 1024, 528, 64),                       # M > 16: two launches, tiled GEMM
+])
+def test_quant_linear_one_call(dgq, torch, M, K, N, g):
+    """Same bits as dgq_quant_act + dgq_linear_a8w4, and the oracle's integers behind them."""
+    x = workloads.activations(M, K, seed=M + K)
+    if M > 2:
+        x[1, :] = 0                                                   # a zero token: scale 0, zeros out
+    W = workloads.weights(K, N, seed=N)
+    w4, s2, s1 = dgq.quantize_weights_rtn(dev(torch, W), g)
+    pw = dgq.pack_weights(w4, s2, s1, g)
+    xd = dev(torch, x)
+    xq, sx = dgq.quant_act(xd)
+    two = host(dgq.linear_a8w4(xq, sx, pw))
+    sx_out = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
+    one = host(dgq.quant_linear_a8w4(xd, pw, sx_out=sx_out))
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+    assert np.array_equal(host(sx_out), host(sx))
+    cols = _cols(N, 24, seed=M) if N > 64 else np.arange(N)
+    oout, _, _, osx = oracle.forward(x, host(w4)[:, cols], host(s2)[:, cols], host(s1)[cols], g)
+    assert np.array_equal(host(sx_out), osx)
+    assert_fp16_close(one[:, cols], oout)
+    # without the optional output
+    again = host(dgq.quant_linear_a8w4(xd, pw))
+    assert np.array_equal(again.view(np.uint16), one.view(np.uint16))
+
+
+def test_quant_linear_one_call_zero_point_form(dgq, torch):
+    M, K, N, g = 11, 4096, 528, 64
+    x = workloads.activations(M, K, seed=3)
+    W = workloads.weights(K, N, seed=4)
+    u4, zp, s2, s1 = dgq.quantize_weights_grid(dev(torch, W), g, 21, 0.025)
+    pw = dgq.pack_weights_zp(u4, s2, zp, s1, g)
+    xd = dev(torch, x)
+    xq, sx = dgq.quant_act(xd)
+    two = host(dgq.linear_a8w4(xq, sx, pw))
+    one = host(dgq.quant_linear_a8w4(xd, pw))
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+    oout = oracle.linear_a8w4_zp(host(xq), host(sx), host(u4), host(s2), host(zp), host(s1), g)[0]
+    assert_fp16_close(one, oout)
+
+
+def test_quant_linear_one_call_extreme_rows(dgq, torch):
+    """Ties, the largest fp16, denormal rows and a lone nonzero: the in-kernel quantizer takes
+    the same decisions as the stand-alone one (and as the oracle's)."""
+    M, K, N, g = 6, 1024, 64, 128
+    rng = np.random.default_rng(21)
+    x = np.zeros((M, K), dtype=np.float16)
+    x[0] = rng.integers(-127, 128, K).astype(np.float16) * np.float16(0.5)      # products on .5 ties
+    x[0, 0] = 63.5
+    x[1] = rng.standard_normal(K).astype(np.float16)
+    x[1, 5] = 65504.0
+    x[2] = (rng.integers(-40, 41, K) * 5.96e-8).astype(np.float16)               # fp16 denormals only
+    x[3, 777] = -3.0                                                             # one nonzero element
+    x[4] = rng.standard_normal(K).astype(np.float16) * np.float16(1e-3)
+    w4, s2, s1 = workloads.integer_weights(K, N, g, 5)
+    pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+    xd = dev(torch, x)
+    xq, sx = dgq.quant_act(xd)
+    oxq, osx = oracle.quant_act(x)
+    assert np.array_equal(host(xq), oxq) and np.array_equal(host(sx), osx)
+    sx_out = torch.empty(M, dtype=torch.float32, device="cuda")
+    one = host(dgq.quant_linear_a8w4(xd, pw, sx_out=sx_out))
+    two = host(dgq.linear_a8w4(xq, sx, pw))
+    assert np.array_equal(host(sx_out), osx)
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+    oout, _ = oracle.linear_a8w4(oxq, osx, w4, s2, s1, g)
+    assert_fp16_close(one, oout)
