@@ -186,3 +186,16 @@ def test_force_path_selector(dgq):
         assert dgq.force_path(2) == 1
     finally:
         dgq.force_path(old)
+
+
+def test_token_index_without_division_matches_integer_division():
+    """The decode kernel that quantizes its own activations finds the token of 8-value vector idx as
+    int((idx + 0.5) * (1 / vpr)) in fp32 (vpr = K / 8 vectors per row).  Exhaustive over every K the
+    kernel accepts and every index its staging area can hold."""
+    import numpy as np
+    for K in range(128, 12288 + 1, 128):
+        vpr = K // 8
+        inv = np.float32(1.0) / np.float32(vpr)
+        idx = np.arange(0, 49152 // 8, dtype=np.int32)
+        tok = ((idx.astype(np.float32) + np.float32(0.5)) * inv).astype(np.int32)
+        assert np.array_equal(tok, idx // vpr), K
