@@ -199,3 +199,26 @@ def test_token_index_without_division_matches_integer_division():
         idx = np.arange(0, 49152 // 8, dtype=np.int32)
         tok = ((idx.astype(np.float32) + np.float32(0.5)) * inv).astype(np.int32)
         assert np.array_equal(tok, idx // vpr), K
+
+
+def test_fast_rounding_of_the_in_kernel_quantizer_equals_rint_and_clamp():
+    """That kernel rounds with fl32(fl32(x * inv) + 1.5 * 2^23) and takes the low byte instead of
+    clamp(rint(fl32(x * inv)), -127, 127).  Checked in numpy fp32 for every finite fp16 x with
+    |x| <= a, for several hundred row maxima a spread over the whole fp16 range (denormals and
+    65504 included)."""
+    import numpy as np
+    allh = np.arange(0, 0x7C00, dtype=np.uint16).view(np.float16)         # every non-negative finite fp16
+    rng = np.random.default_rng(5)
+    picks = np.unique(np.concatenate([[1, 2, 3, 0x03FF, 0x0400, 0x3C00, 0x7BFF],
+                                      rng.integers(1, 0x7C00, 400)])).astype(np.uint16)
+    magic = np.float32(12582912.0)
+    for abits in picks:
+        a = np.float32(np.uint16(abits).view(np.float16))
+        inv = np.float32(127.0) / a
+        x = allh[:int(abits) + 1].astype(np.float32)
+        x = np.concatenate([x, -x])
+        t = x * inv                                                       # fp32 product, rounded once
+        ref = np.clip(np.rint(t), -127, 127).astype(np.int32)
+        fast = ((t + magic).view(np.uint32) & 0xFF).astype(np.uint8).view(np.int8).astype(np.int32)
+        assert np.array_equal(ref, fast), hex(int(abits))
+        assert np.abs(ref).max() == 127
