@@ -284,6 +284,9 @@ def _forward_case(dgq, torch, M, K, N, g, seed, frac=0.01, mult=20.0, cols=None)
     xq, sx = dgq.quant_act(dev(torch, x))
     out = host(dgq.linear_a8w4(xq, sx, pw))
     acc = host(dgq.linear_a8w4_acc(xq, pw))
+    # the same path as ONE call (what bench.py times by default): the same bits
+    one = host(dgq.quant_linear_a8w4(dev(torch, x), pw))
+    assert np.array_equal(one.view(np.uint16), out.view(np.uint16))
     if cols is not None:           # oracle on a sample of output channels
         W = np.ascontiguousarray(W[:, cols])
         out, acc = out[:, cols], acc[:, cols]
