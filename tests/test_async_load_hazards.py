@@ -21,7 +21,7 @@ SRC = os.path.join(ROOT, "paper_2310_04836_amd", "csrc", "linear_tiled.hip")
 
 def _regs(tok):
     tok = tok.split(" ")[0]
-    m = re.match(r"[va]\[(\d+):(\d+)\]$", tok)
+    m = re.match(r"v\[(\d+):(\d+)\]$", tok)   # accumulation registers a[...] are another file; no load targets them
     if m:
         return set(range(int(m.group(1)), int(m.group(2)) + 1))
     m = re.match(r"v(\d+)$", tok)
@@ -45,12 +45,21 @@ def _step(t, pending, problems, name):
     hit = any(rs & touched for rs in pending)
     if op.startswith("global_load_lds"):
         pending.append(frozenset())
-    elif op.startswith("global_load") or op.startswith("buffer_load"):
+    elif op.startswith("global_load") or op.startswith("buffer_load") or op.startswith("scratch_load"):
         pending.append(frozenset(_regs(toks[0])))
-    elif op.startswith("global_store") or op.startswith("global_atomic"):
+    elif op.startswith("global_store") or op.startswith("global_atomic") or op.startswith("scratch_store"):
         pending.append(frozenset())            # stores also occupy a vmcnt slot on this target
     if hit:
         problems.add("%s: %s" % (name, t))
+
+
+def _canon(pending):
+    """State key: the oldest entries that name no register (stores, copies into LDS) can be dropped;
+    a wait counts from the youngest end, so they never decide which register loads remain."""
+    k = 0
+    while k < len(pending) and not pending[k]:
+        k += 1
+    return tuple(pending[k:])
 
 
 def check_asm(text, kernel_substr):
@@ -76,7 +85,7 @@ def check_asm(text, kernel_substr):
             while i < len(body):
                 l = body[i]
                 if is_label[i] and not first:
-                    work.append((i, tuple(pending)))   # a block start: expanded once per state
+                    work.append((i, _canon(pending)))   # a block start: expanded once per state
                     break
                 first = False
                 if l.startswith(".") or l.endswith(":"):
@@ -85,11 +94,11 @@ def check_asm(text, kernel_substr):
                 if l.startswith("s_endpgm"):
                     break
                 if l.startswith("s_branch"):
-                    work.append((labels[l.split()[-1]], tuple(pending)))
+                    work.append((labels[l.split()[-1]], _canon(pending)))
                     break
                 if l.startswith("s_cbranch"):
-                    work.append((labels[l.split()[-1]], tuple(pending)))
-                    work.append((i + 1, tuple(pending)))
+                    work.append((labels[l.split()[-1]], _canon(pending)))
+                    work.append((i + 1, _canon(pending)))
                     break
                 _step(l, pending, problems, name)
                 i += 1
