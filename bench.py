@@ -83,9 +83,10 @@ def main():
                     help="dynamic quantizer: fused = dgq_quant_linear_a8w4, one call per layer (one kernel where a "
                          "workgroup of the decode kernel covers all of K, else the two kernels); separate = "
                          "dgq_quant_act then dgq_linear_a8w4")
-    ap.add_argument("--mlp-block", action="store_true",
-                    help="time the gated MLP as a chain instead of independent layers: RMSNorm fused with the quantizer, "
-                         "gate+up linear, silu*mul fused with the quantizer, down linear")
+    ap.add_argument("--mlp-block", nargs="?", const="fused", default=None, choices=["fused", "separate"],
+                    help="time the gated MLP as a chain instead of independent layers: RMSNorm + quantizer + gate+up "
+                         "linear (one call; 'separate': dgq_rmsnorm_quant_act then dgq_linear_a8w4), silu*mul fused "
+                         "with the quantizer, down linear")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-breakdown", action="store_true")
@@ -147,7 +148,8 @@ def main():
     for M in Ms:
         for name, (K, N) in shapes.items():
             acts[(M, name)] = torch.from_numpy(workloads.activations(M, K, seed + M, frac, mult)).to(dev)
-            wsb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g))
+            wsb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g),
+                      dgq.rmsnorm_quant_linear_workspace_bytes(M, N, K, g))
             bufs[(M, name)] = (torch.empty((M, K), dtype=torch.int8, device=dev),
                                torch.empty(M, dtype=torch.float32, device=dev),
                                torch.empty((M, N), dtype=torch.float16, device=dev),
@@ -177,8 +179,11 @@ def main():
 
     def mlp_chain(M, copy):
         xq, sx, gu, ws = bufs[(M, "gate_up")]
-        dgq.rmsnorm_quant_act(acts[(M, "gate_up")], gamma, 1e-5, xq, sx)
-        dgq.linear_a8w4(xq, sx, packed["gate_up"][copy % ncopies], gu, ws)
+        if args.mlp_block == "fused":    # RMSNorm, quantizer and gate+up as one call (one kernel for small M)
+            dgq.rmsnorm_quant_linear_a8w4(acts[(M, "gate_up")], gamma, 1e-5, packed["gate_up"][copy % ncopies], gu, None, ws)
+        else:
+            dgq.rmsnorm_quant_act(acts[(M, "gate_up")], gamma, 1e-5, xq, sx)
+            dgq.linear_a8w4(xq, sx, packed["gate_up"][copy % ncopies], gu, ws)
         hq, hs, out, ws2 = bufs[(M, "down")]
         dgq.silu_mul_quant_act(gu, hq, hs)
         dgq.linear_a8w4(hq, hs, packed["down"][copy % ncopies], out, ws2)
@@ -449,7 +454,7 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
                    "layers_per_step": list(shapes), "weight_copies": ncopies,
-                   "activation_quantizer": args.act, "mlp_block": bool(args.mlp_block),
+                   "activation_quantizer": args.act, "mlp_block": args.mlp_block or False,
                    "quantizer_call": ("one call with the linear (dgq_quant_linear_a8w4); in-kernel for %d of %d launches"
                                       % (sum(in_kernel.values()), len(in_kernel))) if args.quant == "fused"
                                      else "separate kernel before each linear",

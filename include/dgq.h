@@ -313,6 +313,30 @@ DGQ_API dgq_status dgq_quant_linear_a8w4_zp(const uint16_t *x, const void *qweig
 DGQ_API dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes);
 
 /*
+ * dgq_rmsnorm_quant_act followed by dgq_linear_a8w4 (dgq_linear_a8w4_zp) as one call: the
+ * producer of a transformer block's first linears (qkv, gate+up), the per-token quantizer and
+ * Eq. 2,
+ *   out = linear_a8w4(quant_act(rmsnorm(x) * gamma)),
+ * with y = fp16(float(x * (1 / sqrt(mean_k x^2 + eps)) * gamma[k])) evaluated in fp64 as in
+ * dgq_rmsnorm_quant_act.  Arguments as for dgq_quant_linear_a8w4, plus
+ *   gamma  in [K] fp16 (raw bits), 16-byte aligned;   0 <= eps < 1 (DGQ_ERR_RANGE otherwise)
+ * K <= 24576.  One kernel under the conditions of dgq_quant_linear_a8w4 and K <= 8192 (the
+ * hidden sizes of LLaMA-7B to 65B); otherwise the two kernels, with xq and sx in the workspace
+ * (dgq_rmsnorm_quant_linear_workspace_bytes).  In the one-kernel form the sums of squares are added
+ * in an order that is not fixed; that moves the fp64 factor in its last bits, far below what
+ * survives the rounding to fp32 and fp16.
+ */
+DGQ_API dgq_status dgq_rmsnorm_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
+DGQ_API dgq_status dgq_rmsnorm_quant_linear_a8w4(const uint16_t *x, const uint16_t *gamma, float eps,
+                                         const void *qweight, const void *scales, const float *s1,
+                                         uint16_t *out, float *sx_out, int M, int N, int K, int group,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+DGQ_API dgq_status dgq_rmsnorm_quant_linear_a8w4_zp(const uint16_t *x, const uint16_t *gamma, float eps,
+                                            const void *qweight, const void *scales_zp, const float *s1,
+                                            uint16_t *out, float *sx_out, int M, int N, int K, int group,
+                                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid (host function, nothing launched): writes into buf (at least 96 bytes)
  * the name, with template arguments, of the GEMM kernel that dgq_linear_a8w4 would launch
  * for this problem under the current dgq_force_path() setting, e.g.

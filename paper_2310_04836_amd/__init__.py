@@ -68,10 +68,14 @@ def _load() -> ctypes.CDLL:
     L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
     L.dgq_quant_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
     L.dgq_quant_linear_workspace_bytes.argtypes = [i, i, i, i, psz]
+    L.dgq_rmsnorm_quant_linear_workspace_bytes.argtypes = [i, i, i, i, psz]
     L.dgq_quant_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_quant_linear_a8w4_zp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_rmsnorm_quant_linear_a8w4.argtypes = [vp, vp, ctypes.c_float, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_rmsnorm_quant_linear_a8w4_zp.argtypes = [vp, vp, ctypes.c_float, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     for name in ("dgq_quant_linear_plan", "dgq_quant_linear_workspace_bytes", "dgq_quant_linear_a8w4",
-                 "dgq_quant_linear_a8w4_zp"):
+                 "dgq_quant_linear_a8w4_zp", "dgq_rmsnorm_quant_linear_a8w4", "dgq_rmsnorm_quant_linear_a8w4_zp",
+                 "dgq_rmsnorm_quant_linear_workspace_bytes"):
         getattr(L, name).restype = i
     for name in ("dgq_packed_sizes", "dgq_linear_workspace_bytes", "dgq_pack_weights", "dgq_unpack_weights",
                  "dgq_quantize_weights_rtn", "dgq_quant_act", "dgq_linear_a8w4", "dgq_linear_a8w4_acc",
@@ -343,6 +347,38 @@ def quant_linear_a8w4(x: torch.Tensor, pw: PackedWeight, out: torch.Tensor = Non
     fn = lib.dgq_quant_linear_a8w4_zp if pw.zp_form else lib.dgq_quant_linear_a8w4
     _check(fn(_ptr(x), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out), _ptr(sx_out),
               M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_quant_linear_a8w4")
+    return out
+
+
+def rmsnorm_quant_linear_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    """dgq_rmsnorm_quant_linear_workspace_bytes."""
+    n = ctypes.c_size_t(0)
+    _check(lib.dgq_rmsnorm_quant_linear_workspace_bytes(M, N, K, group, ctypes.byref(n)),
+           "dgq_rmsnorm_quant_linear_workspace_bytes")
+    return n.value
+
+
+def rmsnorm_quant_linear_a8w4(x: torch.Tensor, gamma: torch.Tensor, eps: float, pw: PackedWeight,
+                              out: torch.Tensor = None, sx_out: torch.Tensor = None,
+                              workspace: torch.Tensor = None) -> torch.Tensor:
+    """dgq_rmsnorm_quant_linear_a8w4: fp16 [M,N] = linear_a8w4(quant_act(rmsnorm(x) * gamma)) as one call."""
+    _dev(x, torch.float16, "x"); _dev(gamma, torch.float16, "gamma")
+    if sx_out is not None:
+        _dev(sx_out, torch.float32, "sx_out")
+    M, K = x.shape
+    if K != pw.K or gamma.numel() != K:
+        raise ValueError("x has K=%d, gamma %d elements, the packed weight K=%d" % (K, gamma.numel(), pw.K))
+    if sx_out is not None and sx_out.numel() != M:
+        raise ValueError("sx_out must hold M floats")
+    if out is None:
+        out = torch.empty((M, pw.N), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        nbytes = rmsnorm_quant_linear_workspace_bytes(M, pw.N, K, pw.group)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=x.device) if nbytes else None
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = lib.dgq_rmsnorm_quant_linear_a8w4_zp if pw.zp_form else lib.dgq_rmsnorm_quant_linear_a8w4
+    _check(fn(_ptr(x), _ptr(gamma), eps, _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out), _ptr(sx_out),
+              M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_rmsnorm_quant_linear_a8w4")
     return out
 
 

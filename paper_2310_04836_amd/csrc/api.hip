@@ -77,22 +77,25 @@ bool quantizes_in_kernel(int M, int K, int forced)
 
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-dgq_status quant_linear(const uint16_t *x, const void *qweight, const void *scales, int zp_form, const float *s1,
-                        uint16_t *out, float *sx_out, int M, int N, int K, int group, void *workspace,
-                        size_t workspace_bytes, void *stream)
+// gamma != nullptr: RMSNorm (with eps) in front of the quantizer
+dgq_status quant_linear(const uint16_t *x, const uint16_t *gamma, float eps, const void *qweight, const void *scales,
+                        int zp_form, const float *s1, uint16_t *out, float *sx_out, int M, int N, int K, int group,
+                        void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!x || !qweight || !scales || !s1 || !out) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
-    if (!aligned16(x) || !aligned16(qweight) || !aligned16(scales) || !aligned16(out) ||
+    if (gamma && K > 24576) return DGQ_ERR_SHAPE;
+    if (gamma && (!(eps >= 0.0f) || !(eps < 1.0f))) return DGQ_ERR_RANGE;
+    if (!aligned16(x) || !aligned16(qweight) || !aligned16(scales) || !aligned16(out) || !aligned16(gamma) ||
         (reinterpret_cast<uintptr_t>(s1) & 3u) || (reinterpret_cast<uintptr_t>(sx_out) & 3u))
         return DGQ_ERR_ALIGN;
     const int forced = g_force_path.load(std::memory_order_relaxed);
     if ((forced == kPathStream || forced == kPathStreamGeneric) && M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (quantizes_in_kernel(M, K, forced)) {
+    if (quantizes_in_kernel(M, K, forced) && (!gamma || dgq::decode_plan(K).spw <= dgq::kRmsDecodeMaxStepsPerWave)) {
         dgq::LinearArgs a{nullptr, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
-                          s1, out, nullptr, M, N, K, group, zp_form, x, sx_out};
+                          s1, out, nullptr, M, N, K, group, zp_form, x, sx_out, gamma, eps};
         return hip_result(dgq::launch_linear_decode(a, nullptr, st));
     }
     // two launches, xq and sx in the workspace: [xq: M*K][sx: 4*M][what the linear needs]
@@ -103,11 +106,13 @@ dgq_status quant_linear(const uint16_t *x, const void *qweight, const void *scal
     int8_t *xq = reinterpret_cast<int8_t *>(ws);
     float *sx = sx_out ? sx_out : reinterpret_cast<float *>(ws + xq_bytes);
     dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
-                      s1, out, nullptr, M, N, K, group, zp_form, nullptr, nullptr};
+                      s1, out, nullptr, M, N, K, group, zp_form, nullptr, nullptr, nullptr, 0.0f};
     const int path = pick_path(M, forced);
     if (path == kPathStreamGeneric && zp_form) return DGQ_ERR_SHAPE;
     if (workspace_bytes < xq_bytes + sx_bytes + workspace_needed(path, M, N, K)) return DGQ_ERR_WORKSPACE;
-    if (dgq_status q = hip_result(dgq::launch_quant_act(x, M, K, xq, sx, st))) return q;
+    const hipError_t qe = gamma ? dgq::launch_rmsnorm_quant_act(x, gamma, M, K, eps, xq, sx, st)
+                                : dgq::launch_quant_act(x, M, K, xq, sx, st);
+    if (dgq_status q = hip_result(qe)) return q;
     return run_linear(a, ws + xq_bytes + sx_bytes, workspace_bytes - xq_bytes - sx_bytes, stream);
 }
 
@@ -353,13 +358,13 @@ dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight, const v
     return linear_acc(xq, qweight, scales_zp, 1, acc_out, M, N, K, group, workspace, workspace_bytes, stream);
 }
 
-dgq_status dgq_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes)
+static dgq_status quant_linear_workspace(int M, int N, int K, int group, bool rms, size_t *bytes)
 {
     if (!bytes) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
     const int forced = g_force_path.load(std::memory_order_relaxed);
-    if (quantizes_in_kernel(M, K, forced))
+    if (quantizes_in_kernel(M, K, forced) && (!rms || dgq::decode_plan(K).spw <= dgq::kRmsDecodeMaxStepsPerWave))
         *bytes = 0;
     else
         *bytes = round256((size_t)M * K) + round256((size_t)M * sizeof(float)) +
@@ -367,18 +372,49 @@ dgq_status dgq_quant_linear_workspace_bytes(int M, int N, int K, int group, size
     return DGQ_OK;
 }
 
+dgq_status dgq_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes)
+{
+    return quant_linear_workspace(M, N, K, group, false, bytes);
+}
+
+dgq_status dgq_rmsnorm_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes)
+{
+    return quant_linear_workspace(M, N, K, group, true, bytes);
+}
+
 dgq_status dgq_quant_linear_a8w4(const uint16_t *x, const void *qweight, const void *scales, const float *s1,
                                  uint16_t *out, float *sx_out, int M, int N, int K, int group, void *workspace,
                                  size_t workspace_bytes, void *stream)
 {
-    return quant_linear(x, qweight, scales, 0, s1, out, sx_out, M, N, K, group, workspace, workspace_bytes, stream);
+    return quant_linear(x, nullptr, 0.0f, qweight, scales, 0, s1, out, sx_out, M, N, K, group, workspace,
+                        workspace_bytes, stream);
+}
+
+dgq_status dgq_rmsnorm_quant_linear_a8w4(const uint16_t *x, const uint16_t *gamma, float eps, const void *qweight,
+                                         const void *scales, const float *s1, uint16_t *out, float *sx_out, int M,
+                                         int N, int K, int group, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!gamma) return DGQ_ERR_NULL;
+    return quant_linear(x, gamma, eps, qweight, scales, 0, s1, out, sx_out, M, N, K, group, workspace,
+                        workspace_bytes, stream);
+}
+
+dgq_status dgq_rmsnorm_quant_linear_a8w4_zp(const uint16_t *x, const uint16_t *gamma, float eps, const void *qweight,
+                                            const void *scales_zp, const float *s1, uint16_t *out, float *sx_out,
+                                            int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
+                                            void *stream)
+{
+    if (!gamma) return DGQ_ERR_NULL;
+    return quant_linear(x, gamma, eps, qweight, scales_zp, 1, s1, out, sx_out, M, N, K, group, workspace,
+                        workspace_bytes, stream);
 }
 
 dgq_status dgq_quant_linear_a8w4_zp(const uint16_t *x, const void *qweight, const void *scales_zp, const float *s1,
                                     uint16_t *out, float *sx_out, int M, int N, int K, int group, void *workspace,
                                     size_t workspace_bytes, void *stream)
 {
-    return quant_linear(x, qweight, scales_zp, 1, s1, out, sx_out, M, N, K, group, workspace, workspace_bytes, stream);
+    return quant_linear(x, nullptr, 0.0f, qweight, scales_zp, 1, s1, out, sx_out, M, N, K, group, workspace,
+                        workspace_bytes, stream);
 }
 
 dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes)

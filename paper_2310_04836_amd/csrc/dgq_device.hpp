@@ -208,6 +208,8 @@ struct LinearArgs {
     // Only for the decode kernel that quantizes its own activations (then xq and sx are null):
     const uint16_t *x16;   // fp16 bits [M][K]
     float *sx_out;         // optional: the token scales it derived, [M]
+    const uint16_t *gamma; // optional, fp16 bits [K]: RMS-normalise x and multiply by gamma first
+    float eps;             // added to the mean square
 };
 // Largest M the weight-streaming kernels take.
 constexpr int kStreamMaxM = 64;
@@ -217,6 +219,9 @@ constexpr int kDecodeMaxStepsPerWave = 6;  // 8 would spill at 128 VGPRs
 // The variant that quantizes its own activations stages xq[M][K] in LDS that the column tiles
 // use afterwards (48 KiB), and every workgroup repeats the quantizer: only for small M * K.
 constexpr int kQuantDecodeStageBytes = 49152;
+// With RMSNorm in front the kernel also holds a gamma vector per activation vector: up to four
+// steps per wavefront (K <= 8192, the hidden sizes that feed a block's first linears).
+constexpr int kRmsDecodeMaxStepsPerWave = 4;
 struct DecodePlan {
     int spw;     // steps of 128 k per wavefront (template SPW)
     int pf;      // column tiles prefetched ahead (template PF)

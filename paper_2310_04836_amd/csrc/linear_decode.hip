@@ -43,10 +43,13 @@ static_assert(sizeof(DecodeLds::red) / 2 + sizeof(DecodeLds::sums) == kQuantDeco
 
 // ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes (compile-time).
 // FQ: activations arrive as fp16 and are quantized here (needs ksplit == 1, no ACC, no PARTIAL).
-template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP, bool FQ>
+// RMS (with FQ): the fp16 input is RMS-normalised and multiplied by gamma first, as
+// rmsnorm_quant_act_kernel does it (fp64 up to the rounding to fp32 and then fp16).
+template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP, bool FQ, bool RMS = false>
 __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int32_t *partial)
 {
     static_assert(!FQ || (!ACC && !PARTIAL), "the quantizing variant writes fp16 only");
+    static_assert(!RMS || FQ, "the normalising variant is a quantizing variant");
     // One block, so that red[1] and sums are contiguous (the FQ variant stages INT8 rows there).
     __shared__ DecodeLds lds;
     int (&red)[2][kWaves][256] = lds.red;
@@ -102,6 +105,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
     const int vpr = a.K >> 3;                                                  // vectors per row
     const int nvec = a.M * vpr;
     uint4 v[kVec];
+    uint4 gv[RMS ? kVec : 1];
     int tok[kVec];
     if constexpr (FQ) {
         // The fp16 loads go out before the first weight loads, so that waiting for them leaves
@@ -115,6 +119,8 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
             // idx / vpr without an integer division: (idx + 0.5) / vpr is at least 0.5 / vpr away
             // from an integer, far more than the rounding of this product (idx < 2^13, vpr < 2^13)
             tok[i] = (int)(((float)idx + 0.5f) * inv_vpr);
+            if constexpr (RMS)
+                gv[i] = idx < nvec ? reinterpret_cast<const uint4 *>(a.gamma)[idx - tok[i] * vpr] : make_uint4(0, 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -123,6 +129,78 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
         float *tinv = reinterpret_cast<float *>(&red[0][4][0]);
         float *tsx = tinv + 16;
         uint8_t *stage = reinterpret_cast<uint8_t *>(&red[1][0][0]);
+        if constexpr (RMS) {
+            // y = fp16(float(x * r * gamma)), r = 1 / sqrt(mean(x^2) + eps), all in fp64 up to the two
+            // roundings.  Sums of squares go the way of the maxima below: one LDS slot per token
+            // and lane (ssp, upper half of red[0]), then wavefront w adds up token w.  The order
+            // of the additions is not fixed; it moves r in the last bits of a double, far below
+            // what survives the roundings.
+            double *ssp = reinterpret_cast<double *>(&red[0][8][0]);
+            double *tr = reinterpret_cast<double *>(&red[0][4][64]);
+            ssp[threadIdx.x] = 0.0;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kVec; ++i) {
+                const int idx = threadIdx.x + i * (kWaves * 64);
+                if (idx < nvec) {
+                    const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+                    double ss = 0.0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const double lo = (double)half_bits_to_float(w[k] & 0xFFFFu), hi = (double)half_bits_to_float(w[k] >> 16);
+                        ss += lo * lo;
+                        ss += hi * hi;
+                    }
+                    atomicAdd(&ssp[tok[i] * 64 + lane], ss);
+                }
+            }
+            __syncthreads();
+            {
+                // sum over the wavefront with data-parallel-primitive moves of both halves of the
+                // double (same lane pattern as the maximum below; a masked-off source gives +0.0);
+                // lane 63 ends up with the total
+                double ss = ssp[threadIdx.x];
+#define DGQ_DPP_ADD(CTRL, ROWS)                                                                            \
+    do {                                                                                                   \
+        const uint2 b_ = __builtin_bit_cast(uint2, ss);                                                    \
+        uint2 o_;                                                                                          \
+        o_.x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b_.x, (CTRL), (ROWS), 0xF, false);            \
+        o_.y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b_.y, (CTRL), (ROWS), 0xF, false);            \
+        ss += __builtin_bit_cast(double, o_);                                                              \
+    } while (0)
+                DGQ_DPP_ADD(0xB1, 0xF);    // quad_perm [1,0,3,2]
+                DGQ_DPP_ADD(0x4E, 0xF);    // quad_perm [2,3,0,1]
+                DGQ_DPP_ADD(0x124, 0xF);   // row_ror 4
+                DGQ_DPP_ADD(0x128, 0xF);   // row_ror 8
+                DGQ_DPP_ADD(0x142, 0xA);   // row_bcast 15 into rows 1 and 3
+                DGQ_DPP_ADD(0x143, 0xC);   // row_bcast 31 into rows 2 and 3
+#undef DGQ_DPP_ADD
+                if (lane == 63) tr[wave] = 1.0 / sqrt(ss / (double)a.K + (double)a.eps);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kVec; ++i) {
+                const int idx = threadIdx.x + i * (kWaves * 64);
+                if (idx < nvec) {
+                    const double r = tr[tok[i]];
+                    const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+                    const uint32_t gw[4] = {gv[i].x, gv[i].y, gv[i].z, gv[i].w};
+                    uint32_t y[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        y[k] = 0;
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            const double xd = (double)half_bits_to_float((w[k] >> (16 * h)) & 0xFFFFu);
+                            const double gd = (double)half_bits_to_float((gw[k] >> (16 * h)) & 0xFFFFu);
+                            const float p32 = (float)(xd * r * gd);
+                            y[k] |= (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)p32) << (16 * h);
+                        }
+                    }
+                    v[i] = make_uint4(y[0], y[1], y[2], y[3]);
+                }
+            }
+        }
         part[threadIdx.x] = 0;                                             // 16 tokens x 64 slots
         __syncthreads();
 #pragma unroll
@@ -327,6 +405,17 @@ __global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_zp_kernel(Lin
 {
     decode_body<SPW, PF, G, false, false, true, true>(a, 1, nullptr);
 }
+// the same with RMSNorm in front of the quantizer
+template <int SPW, int PF, int G>
+__global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_kernel(LinearArgs a)
+{
+    decode_body<SPW, PF, G, false, false, false, true, true>(a, 1, nullptr);
+}
+template <int SPW, int PF, int G>
+__global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_zp_kernel(LinearArgs a)
+{
+    decode_body<SPW, PF, G, false, false, true, true, true>(a, 1, nullptr);
+}
 
 // Adds the K-split partial tiles and runs the epilogue; four consecutive columns per thread
 // (N is a multiple of 16, so a group of four never crosses a row).
@@ -382,14 +471,21 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
     int32_t *partial = static_cast<int32_t *>(workspace);
     const bool acc = a.acc_out != nullptr;
     if (a.x16) {
-        {
         if (ksplit > 1 || acc || (long long)a.M * (a.K + 16) > kQuantDecodeStageBytes) return hipErrorInvalidValue;
-        if (a.zp)
+        if (a.gamma) {
+            if constexpr (SPW > kRmsDecodeMaxStepsPerWave) {
+                return hipErrorInvalidValue;
+            } else if (a.zp) {
+                hipLaunchKernelGGL((rmsnorm_quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a);
+            } else {
+                hipLaunchKernelGGL((rmsnorm_quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a);
+            }
+        } else if (a.zp) {
             hipLaunchKernelGGL((quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a);
-        else
+        } else {
             hipLaunchKernelGGL((quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a);
-        return hipGetLastError();
         }
+        return hipGetLastError();
     }
     if (ksplit > 1) {
         if (a.zp)

@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 30 and len(set(names)) == 30
+    assert len(names) == 33 and len(set(names)) == 33
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -125,6 +125,14 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_quant_linear_a8w4(odd, good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -3
     assert L.dgq_quant_linear_a8w4(good, good, good, good, good, None, 32, 16, 128, 128, None, 0, None) == -5
     assert L.dgq_quant_linear_a8w4_zp(good, good, good, good, good, None, 32, 16, 128, 128, good, 100, None) == -5
+    # RMSNorm + quantizer + linear as one call
+    assert L.dgq_rmsnorm_quant_linear_workspace_bytes(4, 4096, 4096, 128, ctypes.byref(n)) == 0 and n.value == 0
+    assert L.dgq_rmsnorm_quant_linear_workspace_bytes(4, 4096, 11008, 128, ctypes.byref(n)) == 0
+    assert n.value == 4 * 11008 + 256                      # more than four steps per wavefront: two kernels
+    assert L.dgq_rmsnorm_quant_linear_a8w4(good, None, f(1e-5), good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -1
+    assert L.dgq_rmsnorm_quant_linear_a8w4(good, good, f(-1.0), good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -4
+    assert L.dgq_rmsnorm_quant_linear_a8w4(good, odd, f(1e-5), good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -3
+    assert L.dgq_rmsnorm_quant_linear_a8w4_zp(good, good, f(1e-5), good, good, good, good, None, 32, 16, 128, 128, None, 0, None) == -5
     # measurement aids
     assert L.dgq_probe_mfma(None, 4096, 1, good, 1, None) == -1
     assert L.dgq_probe_mfma(good, 64, 1, good, 1, None) == -2

@@ -757,3 +757,49 @@ def test_quant_linear_one_call_extreme_rows(dgq, torch):
     assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
     oout, _ = oracle.linear_a8w4(oxq, osx, w4, s2, s1, g)
     assert_fp16_close(one, oout)
+
+
+@pytest.mark.parametrize("M,K,N,g", [
+    (1, 128, 16, 128), (3, 1024, 272, 64),                            # one step per wavefront
+    (1, 4096, 22016, 128), (4, 4096, 12288, 128), (11, 4096, 528, 64),  # LLaMA-7B hidden size
+    (2, 5120, 1040, 128), (9, 5120, 256, 64),                         # 13B
+    (1, 8192, 1024, 128), (5, 8192, 512, 64),                         # 65B
+    (4, 11008, 256, 128),                                             # more than four steps per wavefront: two launches
+    (16, 4096, 512, 128), (40, 1408, 272, 128),                       # rows too many: two launches
+])
+def test_rmsnorm_quant_linear_one_call(dgq, torch, M, K, N, g):
+    """RMSNorm + quantizer + linear as one call: the token scales are the oracle's, the output has the
+    bits of the three-step path (dgq_rmsnorm_quant_act, dgq_linear_a8w4) and meets the oracle's."""
+    x = workloads.activations(M, K, seed=2 * M + K)
+    if M > 2:
+        x[1, :] = 0                                                   # mean square 0: y = 0, scale 0
+    gamma = np.random.default_rng(K + 1).normal(1, 0.3, K).astype(np.float16)
+    W = workloads.weights(K, N, seed=N + 1)
+    w4, s2, s1 = dgq.quantize_weights_rtn(dev(torch, W), g)
+    pw = dgq.pack_weights(w4, s2, s1, g)
+    xd, gd = dev(torch, x), dev(torch, gamma)
+    xq, sx = dgq.rmsnorm_quant_act(xd, gd, 1e-5)
+    two = host(dgq.linear_a8w4(xq, sx, pw))
+    sx_out = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
+    one = host(dgq.rmsnorm_quant_linear_a8w4(xd, gd, 1e-5, pw, sx_out=sx_out))
+    oxq, osx, _ = oracle.rmsnorm_quant_act(x, gamma, 1e-5)
+    assert np.array_equal(host(sx_out), osx) and np.array_equal(host(sx), osx)
+    assert np.array_equal(host(xq), oxq)
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+    cols = _cols(N, 24, seed=M) if N > 64 else np.arange(N)
+    oout, _ = oracle.linear_a8w4(oxq, osx, host(w4)[:, cols], host(s2)[:, cols], host(s1)[cols], g)
+    assert_fp16_close(one[:, cols], oout)
+
+
+def test_rmsnorm_quant_linear_one_call_zero_point_form(dgq, torch):
+    M, K, N, g = 3, 4096, 272, 128
+    x = workloads.activations(M, K, seed=8)
+    gamma = np.random.default_rng(2).normal(1, 0.3, K).astype(np.float16)
+    W = workloads.weights(K, N, seed=9)
+    u4, zp, s2, s1 = dgq.quantize_weights_grid(dev(torch, W), g, 21, 0.025)
+    pw = dgq.pack_weights_zp(u4, s2, zp, s1, g)
+    xd, gd = dev(torch, x), dev(torch, gamma)
+    xq, sx = dgq.rmsnorm_quant_act(xd, gd, 1e-6)
+    two = host(dgq.linear_a8w4(xq, sx, pw))
+    one = host(dgq.rmsnorm_quant_linear_a8w4(xd, gd, 1e-6, pw))
+    assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
