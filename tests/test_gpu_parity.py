@@ -803,3 +803,68 @@ def test_rmsnorm_quant_linear_one_call_zero_point_form(dgq, torch):
     two = host(dgq.linear_a8w4(xq, sx, pw))
     one = host(dgq.rmsnorm_quant_linear_a8w4(xd, gd, 1e-6, pw))
     assert np.array_equal(one.view(np.uint16), two.view(np.uint16))
+
+
+# ----------------------------------------------------------------------------
+# the launch form bench.py times: calls recorded in a HIP graph and replayed
+# ----------------------------------------------------------------------------
+def test_graph_replays_equal_eager_results(dgq, torch):
+    """Every kind of launch the library makes (decode kernel with and without its K split and
+    second kernel, the kernels that quantize for themselves, tiled kernel with and without K split,
+    stand-alone quantizers) recorded once and replayed three times on changing inputs, with eager
+    work and synchronisation between the replays; every replay must reproduce the eager result."""
+    g = 128
+    cases = [(4, 4096, 272), (3, 22016, 256), (16, 4096, 528), (64, 8192, 512), (130, 1024, 528)]
+    packed, xs, outs, outs1, outsr, wss, gammas = [], [], [], [], [], [], []
+    for i, (M, K, N) in enumerate(cases):
+        W = workloads.weights(K, N, seed=40 + i)
+        w4, s2, s1 = dgq.quantize_weights_rtn(dev(torch, W), g)
+        packed.append(dgq.pack_weights(w4, s2, s1, g))
+        xs.append(torch.empty((M, K), dtype=torch.float16, device="cuda"))
+        gammas.append(dev(torch, np.random.default_rng(i).normal(1, 0.2, K).astype(np.float16)))
+        outs.append(torch.empty((M, N), dtype=torch.float16, device="cuda"))
+        outs1.append(torch.empty((M, N), dtype=torch.float16, device="cuda"))
+        outsr.append(torch.empty((M, N), dtype=torch.float16, device="cuda"))
+        nb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g),
+                 dgq.rmsnorm_quant_linear_workspace_bytes(M, N, K, g), 16)
+        wss.append(torch.empty(nb, dtype=torch.uint8, device="cuda"))
+    bufs = [(torch.empty((M, K), dtype=torch.int8, device="cuda"), torch.empty(M, dtype=torch.float32, device="cuda"))
+            for M, K, N in cases]
+
+    def step():
+        for i in range(len(cases)):
+            xq, sx = bufs[i]
+            dgq.quant_act(xs[i], xq, sx)
+            dgq.linear_a8w4(xq, sx, packed[i], outs[i], wss[i])
+            dgq.quant_linear_a8w4(xs[i], packed[i], outs1[i], None, wss[i])
+            dgq.rmsnorm_quant_linear_a8w4(xs[i], gammas[i], 1e-5, packed[i], outsr[i], None, wss[i])
+
+    def fill(seed):
+        for i, (M, K, N) in enumerate(cases):
+            xs[i].copy_(dev(torch, workloads.activations(M, K, seed=seed + i)))
+
+    fill(100)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                    # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        fill(200 + 10 * rep)
+        step()                                    # eager, on the new inputs
+        torch.cuda.synchronize()
+        want = [(o.clone(), o1.clone(), orr.clone()) for o, o1, orr in zip(outs, outs1, outsr)]
+        for o, o1, orr in zip(outs, outs1, outsr):
+            o.zero_(); o1.zero_(); orr.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(len(cases)):
+            assert torch.equal(outs[i].view(torch.int16), want[i][0].view(torch.int16)), (rep, cases[i], "two calls")
+            assert torch.equal(outs1[i].view(torch.int16), want[i][1].view(torch.int16)), (rep, cases[i], "one call")
+            assert torch.equal(outsr[i].view(torch.int16), want[i][2].view(torch.int16)), (rep, cases[i], "rmsnorm")
+            assert torch.equal(outs[i].view(torch.int16), outs1[i].view(torch.int16))
