@@ -35,6 +35,14 @@ constexpr int kWaves = 16;
 // A workgroup keeps the finished INT32 tiles of all its column tiles in LDS and stores
 // them after the weight loop, so that the loop itself contains no global stores.
 constexpr int kMaxTilesPerWg = 32;
+// Launch geometry worked out on the host: workgroup wg of K part kpart is block
+// (wg << ks_shift) + kpart and walks column tiles wg, wg + cols, ...
+struct DecodeGrid {
+    int cols;        // workgroups per K part
+    int ks_shift;    // log2 of the number of K parts
+    int tiles_base;  // every workgroup has this many column tiles ...
+    int tiles_rem;   // ... and the first tiles_rem one more
+};
 struct DecodeLds {
     int red[2][kWaves][256];           // partial tiles of the 16 wavefronts, double buffered
     int sums[kMaxTilesPerWg][256];     // finished INT32 tiles
@@ -46,8 +54,12 @@ static_assert(sizeof(DecodeLds::red) / 2 + sizeof(DecodeLds::sums) == kQuantDeco
 // RMS (with FQ): the fp16 input is RMS-normalised and multiplied by gamma first, as
 // rmsnorm_quant_act_kernel does it (fp64 up to the rounding to fp32 and then fp16).
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP, bool FQ, bool RMS = false>
-__device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int32_t *partial)
+__device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGrid &grid, int32_t *partial)
 {
+    // Everything before the first load is one wavefront executing straight-line scalar code at a
+    // few cycles per instruction, so it is kept short: no run-time integer divisions (the host
+    // passes quotients and remainders), and the K split is a constant 1 where there is none.
+    const int ks_shift = PARTIAL ? grid.ks_shift : 0;   // the K split is a power of two
     static_assert(!FQ || (!ACC && !PARTIAL), "the quantizing variant writes fp16 only");
     static_assert(!RMS || FQ, "the normalising variant is a quantizing variant");
     // One block, so that red[1] and sums are contiguous (the FQ variant stages INT8 rows there).
@@ -59,37 +71,39 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
     const int j = lane & 15;
     const int kb = lane >> 4;
     const int steps = a.K >> 7;
-    const int tiles = a.N >> 4;
     const ScaleForm sf = scale_form(ZP ? 1 : 0);  // scale words hold 4 groups (S2 bytes) or 2 (S2, ZP pairs)
     const int gqn = ((a.K / G) + (1 << sf.fsh) - 1) >> sf.fsh;
 
     // This workgroup's part of K; wavefront w takes steps [p0 + w*SPW, p0 + (w+1)*SPW) of it.
     // Only the last active wavefront can be short; wavefronts past the end only help reduce.
-    const int kpart = blockIdx.x % ksplit;
-    const int wg = blockIdx.x / ksplit;
-    const int wg_stride = gridDim.x / ksplit;
-    const int p0 = (steps * kpart) / ksplit;
-    const int p1 = (steps * (kpart + 1)) / ksplit;
+    const int wg_stride = grid.cols;
+    const int kpart = (int)blockIdx.x & ((1 << ks_shift) - 1);
+    const int wg = (int)blockIdx.x >> ks_shift;
+    const int p0 = (steps * kpart) >> ks_shift;
+    const int p1 = (steps * (kpart + 1)) >> ks_shift;
     const int active_waves = (p1 - p0 + SPW - 1) / SPW;  // <= kWaves, checked on the host
     const int sb = p0 + wave * SPW;
     const int nst = sb < p1 ? (p1 - sb < SPW ? p1 - sb : SPW) : 0;
-    const int my_tiles = wg < tiles ? (tiles - wg + wg_stride - 1) / wg_stride : 0;
+    const int my_tiles = grid.tiles_base + (wg < grid.tiles_rem ? 1 : 0);   // tiles wg, wg + cols, ...
 
-    // Epilogue operands, fetched now so that the end of the kernel does not wait on memory.
-    // In the epilogue thread x handles element x%256 of tiles x/256, x/256 + 4, ...: a fixed
-    // token, and one output channel per tile.
+    // Epilogue operands, fetched early so that the end of the kernel does not wait on memory, but
+    // behind the first weight loads (every wavefront calls this once).  In the epilogue thread x
+    // handles element x%256 of tiles x/256, x/256 + 4, ...: a fixed token, and one output
+    // channel per tile.
     constexpr int kEarly = 3;
     const int ep_x = threadIdx.x & 255;
     const int ep_m = 4 * ((ep_x & 63) >> 4) + (ep_x >> 6);
     float ep_sx = 0.0f, ep_s1[kEarly] = {0.0f, 0.0f, 0.0f};
-    if (!ACC && !PARTIAL && ep_m < a.M) {
-        if (!FQ) ep_sx = a.sx[ep_m];
+    auto load_epilogue_operands = [&]() {
+        if (!ACC && !PARTIAL && ep_m < a.M) {
+            if (!FQ) ep_sx = a.sx[ep_m];
 #pragma unroll
-        for (int k = 0; k < kEarly; ++k) {
-            const int ti = (threadIdx.x >> 8) + 4 * k;
-            if (ti < my_tiles) ep_s1[k] = a.s1[(wg + ti * wg_stride) * 16 + (ep_x & 15)];
+            for (int k = 0; k < kEarly; ++k) {
+                const int ti = (threadIdx.x >> 8) + 4 * k;
+                if (ti < my_tiles) ep_s1[k] = a.s1[(wg + ti * wg_stride) * 16 + (ep_x & 15)];
+            }
         }
-    }
+    };
 
     // FQ (called once by every wavefront, at a point all of them reach): the per-token quantizer
     // run by the whole workgroup, then this wavefront's slice fetched from LDS.
@@ -269,8 +283,11 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
                 const int s = i < nst ? sb + i : sb;
                 xa[i][0] = ap[(size_t)s * 8];
                 xa[i][1] = ap[(size_t)s * 8 + 1];
-                if (i >= nst) xa[i][0] = xa[i][1] = make_uint4(0, 0, 0, 0);
             }
+            // (slots past the end of a short slice are zeroed after the first weight loads have
+            // been issued: anything that touches xa here would wait for these loads first and
+            // hold the weight stream back by a memory latency)
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // per-slot element offsets inside one column tile (a short slice re-reads step sb)
@@ -293,6 +310,17 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
     } while (0)
 
         // prologue: PF tiles in flight (tiles past the end re-read the first tile, unused)
+        // FQ: a CU cannot take all these requests at once, so a wavefront spends about as long
+        // issuing them as the data need to arrive, and the quantizer, which every wavefront must
+        // reach, would only start then.  A workgroup with a single column tile has nothing that
+        // hides this: there the quantizer runs after the first half of the slots and the rest
+        // is requested behind it.  With more tiles the requests all go out first (measured: the
+        // early quantizer costs those shapes 0.1-0.3 us, and saves the others 0.2-1.2 us).
+        constexpr int kSlotsBeforeQuantizer = (PF * SPW + 1) / 2;
+        // (kernels with one tile of requests in flight, the long-K ones, always take the early
+        // form, and so do the kernels that normalise first: a second copy of the quantizer would
+        // make them spill registers)
+        const bool quantize_early = PF == 1 || RMS || my_tiles <= 1;
 #pragma unroll
         for (int p = 0; p < PF; ++p) {
             const int t = p < my_tiles ? wg + p * wg_stride : wg;
@@ -302,9 +330,29 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
                 // issue order = consumption order, so that waiting for the oldest slot
                 // leaves all younger loads in flight
                 __builtin_amdgcn_sched_barrier(0);
+                if constexpr (FQ) {
+                    if (p * SPW + i + 1 == kSlotsBeforeQuantizer && quantize_early) {
+                        load_epilogue_operands();
+                        __builtin_amdgcn_sched_barrier(0);
+                        quantize_rows(xa);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
         }
-        if constexpr (FQ) quantize_rows(xa);
+        if constexpr (FQ) {
+            if (!quantize_early) {
+                load_epilogue_operands();
+                __builtin_amdgcn_sched_barrier(0);
+                quantize_rows(xa);
+            }
+        } else {
+            load_epilogue_operands();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < SPW; ++i)
+                if (i >= nst) xa[i][0] = xa[i][1] = make_uint4(0, 0, 0, 0);
+        }
 
 #define DGQ_TILE(P, IT)                                                                              \
     do {                                                                                             \
@@ -348,6 +396,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
 #undef DGQ_LOAD_SLOT
     } else {
         // wavefronts without a slice of K: keep the barrier count and help with the reduction
+        load_epilogue_operands();
         if constexpr (FQ) quantize_rows(xa);
         for (int it = 0; it < my_tiles; ++it) {
             __syncthreads();
@@ -385,36 +434,36 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, int ksplit, int
 }
 
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
-__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, int ksplit, int32_t *partial)
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, DecodeGrid grid, int32_t *partial)
 {
-    decode_body<SPW, PF, G, ACC, PARTIAL, false, false>(a, ksplit, partial);
+    decode_body<SPW, PF, G, ACC, PARTIAL, false, false>(a, grid, partial);
 }
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
-__global__ __launch_bounds__(kWaves * 64) void linear_decode_zp_kernel(LinearArgs a, int ksplit, int32_t *partial)
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid, int32_t *partial)
 {
-    decode_body<SPW, PF, G, ACC, PARTIAL, true, false>(a, ksplit, partial);
+    decode_body<SPW, PF, G, ACC, PARTIAL, true, false>(a, grid, partial);
 }
 // fp16 activations in, quantized by the kernel itself (one workgroup sees the whole of K)
 template <int SPW, int PF, int G>
-__global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_kernel(LinearArgs a)
+__global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, false, true>(a, 1, nullptr);
+    decode_body<SPW, PF, G, false, false, false, true>(a, grid, nullptr);
 }
 template <int SPW, int PF, int G>
-__global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_zp_kernel(LinearArgs a)
+__global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, true, true>(a, 1, nullptr);
+    decode_body<SPW, PF, G, false, false, true, true>(a, grid, nullptr);
 }
 // the same with RMSNorm in front of the quantizer
 template <int SPW, int PF, int G>
-__global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_kernel(LinearArgs a)
+__global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, false, true, true>(a, 1, nullptr);
+    decode_body<SPW, PF, G, false, false, false, true, true>(a, grid, nullptr);
 }
 template <int SPW, int PF, int G>
-__global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_zp_kernel(LinearArgs a)
+__global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, true, true, true>(a, 1, nullptr);
+    decode_body<SPW, PF, G, false, false, true, true, true>(a, grid, nullptr);
 }
 
 // Adds the K-split partial tiles and runs the epilogue; four consecutive columns per thread
@@ -468,6 +517,10 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
     if (cols * kMaxTilesPerWg < tiles) cols = (tiles + kMaxTilesPerWg - 1) / kMaxTilesPerWg;
     if (cols > tiles) cols = tiles;
     dim3 grid(cols * ksplit), block(kWaves * 64);
+    int ks_shift = 0;
+    while ((1 << ks_shift) < ksplit) ++ks_shift;
+    if ((1 << ks_shift) != ksplit) return hipErrorInvalidValue;   // decode_plan only makes powers of two
+    const DecodeGrid dg{cols, ks_shift, tiles / cols, tiles % cols};
     int32_t *partial = static_cast<int32_t *>(workspace);
     const bool acc = a.acc_out != nullptr;
     if (a.x16) {
@@ -476,32 +529,32 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
             if constexpr (SPW > kRmsDecodeMaxStepsPerWave) {
                 return hipErrorInvalidValue;
             } else if (a.zp) {
-                hipLaunchKernelGGL((rmsnorm_quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a);
+                hipLaunchKernelGGL((rmsnorm_quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a, dg);
             } else {
-                hipLaunchKernelGGL((rmsnorm_quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a);
+                hipLaunchKernelGGL((rmsnorm_quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a, dg);
             }
         } else if (a.zp) {
-            hipLaunchKernelGGL((quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a);
+            hipLaunchKernelGGL((quant_linear_decode_zp_kernel<SPW, PF, G>), grid, block, 0, st, a, dg);
         } else {
-            hipLaunchKernelGGL((quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a);
+            hipLaunchKernelGGL((quant_linear_decode_kernel<SPW, PF, G>), grid, block, 0, st, a, dg);
         }
         return hipGetLastError();
     }
     if (ksplit > 1) {
         if (a.zp)
-            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, dg, partial);
         else
-            hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, ksplit, partial);
+            hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, dg, partial);
         return launch_splitk_finalize(a, ksplit, partial, st);
     } else if (a.zp) {
         if (acc)
-            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, 1, partial);
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, dg, partial);
         else
-            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, 1, partial);
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, dg, partial);
     } else if (acc) {
-        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, 1, partial);
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, dg, partial);
     } else {
-        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, 1, partial);
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, dg, partial);
     }
     return hipGetLastError();
 }
