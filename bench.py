@@ -41,8 +41,8 @@ WORKLOADS = {
 # (FETCH_SIZE reads 0.5 GiB per GiB read: x2.0; WRITE_SIZE x1.0).  Figures and commands are in
 # profiles/; a workload that has not been profiled reports null.
 TRAFFIC_BYTES = {
-    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"): (2.0 * 14430.5 + 62.5) * 1024,
-    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14126.0 + 175.0) * 1024,
+    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"): (2.0 * 14569.5 + 62.5) * 1024,
+    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14182.3 + 175.0) * 1024,
     ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"): (2.0 * 75912.5 + 34112.0) * 1024,
 }
 
