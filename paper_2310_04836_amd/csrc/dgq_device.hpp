@@ -175,6 +175,26 @@ __device__ __forceinline__ uint2 quant_vec_fast(const uint4 &v, float inv)
     return r;
 }
 
+// Maximum of an unsigned value over the 64 lanes of a wavefront with data-parallel-primitive
+// moves (no LDS round trips): within quads, within rows of 16, then row to row.  LANE 63 holds
+// the result; a lane whose source is masked off receives 0, the identity of the maximum.
+__device__ __forceinline__ uint32_t wave_max_u32_lane63(uint32_t mx)
+{
+#define DGQ_DPP_MAX(CTRL, ROWS)                                                                          \
+    do {                                                                                                 \
+        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx, (CTRL), (ROWS), 0xF, false); \
+        mx = o > mx ? o : mx;                                                                            \
+    } while (0)
+    DGQ_DPP_MAX(0xB1, 0xF);    // quad_perm [1,0,3,2]
+    DGQ_DPP_MAX(0x4E, 0xF);    // quad_perm [2,3,0,1]
+    DGQ_DPP_MAX(0x124, 0xF);   // row_ror 4
+    DGQ_DPP_MAX(0x128, 0xF);   // row_ror 8
+    DGQ_DPP_MAX(0x142, 0xA);   // row_bcast 15 into rows 1 and 3
+    DGQ_DPP_MAX(0x143, 0xC);   // row_bcast 31 into rows 2 and 3
+#undef DGQ_DPP_MAX
+    return mx;
+}
+
 // ---- kernel launchers (defined one per .hip file) ----------------------------------
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps, int8_t *xq,

@@ -224,22 +224,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGri
         }
         __syncthreads();
         {   // wavefront w finishes token w
-            // maximum over the wavefront with data-parallel-primitive moves (no LDS round trips):
-            // within quads, within rows of 16, then row to row; lane 63 ends up with the result.
-            // A lane whose source is masked off receives 0, the identity of an unsigned maximum.
-            uint32_t mx = part[threadIdx.x];
-#define DGQ_DPP_MAX(CTRL, ROWS)                                                                          \
-    do {                                                                                                 \
-        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mx, (CTRL), (ROWS), 0xF, false); \
-        mx = o > mx ? o : mx;                                                                            \
-    } while (0)
-            DGQ_DPP_MAX(0xB1, 0xF);    // quad_perm [1,0,3,2]
-            DGQ_DPP_MAX(0x4E, 0xF);    // quad_perm [2,3,0,1]
-            DGQ_DPP_MAX(0x124, 0xF);   // row_ror 4
-            DGQ_DPP_MAX(0x128, 0xF);   // row_ror 8
-            DGQ_DPP_MAX(0x142, 0xA);   // row_bcast 15 into rows 1 and 3
-            DGQ_DPP_MAX(0x143, 0xC);   // row_bcast 31 into rows 2 and 3
-#undef DGQ_DPP_MAX
+            const uint32_t mx = wave_max_u32_lane63(part[threadIdx.x]);
             if (lane == 63) {
                 const float am = half_bits_to_float(mx);
                 tinv[wave] = am != 0.0f ? 127.0f / am : 0.0f;

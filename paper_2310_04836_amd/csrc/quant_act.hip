@@ -4,24 +4,14 @@
 // One 256-thread workgroup per token.  The row is read once as 128-bit vectors of eight
 // fp16 values and kept in registers; the absolute maximum is taken on the raw bit patterns
 // (for non-negative fp16 numbers the integer order of the bits is the numeric order), reduced
-// across the wavefront with lane exchanges and across the four wavefronts through LDS; then
-// every value is scaled, rounded to nearest-even and stored as eight packed bytes.
+// across the wavefront with data-parallel-primitive moves and across the four wavefronts through
+// LDS; then every value is scaled, rounded to nearest-even and stored as eight packed bytes.
 #include "dgq_device.hpp"
 
 namespace dgq {
 namespace {
 
 constexpr int kThreads = 256;
-
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
-        v = o > v ? o : v;
-    }
-    return v;
-}
 
 // VPT > 0: each thread caches VPT vectors (K <= 2048 * VPT).  VPT == 0: any K, the row is read
 // twice (the second read hits in cache).
@@ -48,8 +38,8 @@ __global__ __launch_bounds__(kThreads) void quant_act_kernel(const uint16_t *__r
     } else {
         for (int idx = threadIdx.x; idx < nvec; idx += kThreads) mx = absmax_bits(row[idx], mx);
     }
-    mx = wave_max_u32(mx);
-    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = mx;
+    mx = wave_max_u32_lane63(mx);
+    if ((threadIdx.x & 63) == 63) wave_m[threadIdx.x >> 6] = mx;
     __syncthreads();
     mx = wave_m[0];
 #pragma unroll
@@ -118,8 +108,8 @@ __global__ __launch_bounds__(kThreads) void silu_mul_quant_act_kernel(const uint
         }
         mx = absmax_bits(cache[i], mx);
     }
-    mx = wave_max_u32(mx);
-    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = mx;
+    mx = wave_max_u32_lane63(mx);
+    if ((threadIdx.x & 63) == 63) wave_m[threadIdx.x >> 6] = mx;
     __syncthreads();
     mx = wave_m[0];
 #pragma unroll
@@ -209,8 +199,8 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quant_act_kernel(const uint1
         }
         mx = absmax_bits(cache[i], mx);
     }
-    mx = wave_max_u32(mx);
-    if ((threadIdx.x & 63) == 0) wave_m[threadIdx.x >> 6] = mx;
+    mx = wave_max_u32_lane63(mx);
+    if ((threadIdx.x & 63) == 63) wave_m[threadIdx.x >> 6] = mx;
     __syncthreads();
     mx = wave_m[0];
 #pragma unroll
