@@ -868,3 +868,38 @@ def test_graph_replays_equal_eager_results(dgq, torch):
             assert torch.equal(outs1[i].view(torch.int16), want[i][1].view(torch.int16)), (rep, cases[i], "one call")
             assert torch.equal(outsr[i].view(torch.int16), want[i][2].view(torch.int16)), (rep, cases[i], "rmsnorm")
             assert torch.equal(outs[i].view(torch.int16), outs1[i].view(torch.int16))
+
+
+def test_random_shapes_one_call_forms(dgq, torch):
+    """Thirty seeded random decode-size problems (every steps-per-wavefront variant, both group sizes,
+    both operand forms, staging area from nearly empty to just too small): the one-call forms give the
+    bits of the separate calls, with and without RMSNorm in front."""
+    rng = np.random.default_rng(77)
+    fused = 0
+    for case in range(30):
+        M = int(rng.integers(1, 17)) if case % 5 else int(rng.choice([17, 40]))
+        K = 128 * int(rng.integers(1, 97)) if case % 3 else 128 * int(rng.integers(1, 33))
+        N = 16 * int(rng.integers(1, 70))
+        g = int(rng.choice([64, 128]))
+        x = workloads.activations(M, K, seed=1000 + case)
+        gamma = rng.normal(1, 0.3, K).astype(np.float16)
+        if case % 2:
+            u4, s2, zp, s1 = _zp_operands(K, N, g, case)
+            pw = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), g)
+        else:
+            w4, s2, s1 = workloads.integer_weights(K, N, g, case)
+            pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
+        s1d = pw.s1
+        s1d.mul_(1e-3)                                   # keep the fp16 outputs finite
+        xd, gd = dev(torch, x), dev(torch, gamma)
+        fused += dgq.quant_linear_plan(M, N, K, g).startswith("quant_linear")
+        xq, sx = dgq.quant_act(xd)
+        two = host(dgq.linear_a8w4(xq, sx, pw))
+        one = host(dgq.quant_linear_a8w4(xd, pw))
+        assert np.array_equal(one.view(np.uint16), two.view(np.uint16)), (case, M, K, N, g)
+        assert np.isfinite(one).all()
+        yq, sy = dgq.rmsnorm_quant_act(xd, gd, 1e-5)
+        two = host(dgq.linear_a8w4(yq, sy, pw))
+        one = host(dgq.rmsnorm_quant_linear_a8w4(xd, gd, 1e-5, pw))
+        assert np.array_equal(one.view(np.uint16), two.view(np.uint16)), (case, M, K, N, g, "rmsnorm")
+    assert 8 <= fused <= 26, fused                       # both the one-kernel and the two-kernel form occur
