@@ -268,5 +268,21 @@ def test_smooth_scales_properties_and_product_is_preserved():
     assert np.array_equal(Wo, (W * k[:, None]).astype(np.float16)) and np.array_equal(Xo[:, k == 1], X[:, k == 1].astype(np.float16))
 
 
+def test_smooth_apply_hand_values():
+    """Section 3.4: the scale leaves the activations (X / k) and enters the weights (k * W).  Hand values with a
+    channel whose scale is above 1, so that a swapped direction, a transposed index or a missing rounding shows:
+    channel 1 has k = 4: X 6 -> 1.5, W 0.25 -> 1.0; channel 2 has k = 3: X 1 -> 1/3 (rounded once to fp16)."""
+    k = np.array([1.0, 4.0, 3.0], np.float32)
+    X = np.array([[2.0, 6.0, 1.0], [-8.0, -0.5, 9.0]], np.float32)
+    W = np.array([[5.0, -7.0], [0.25, 0.5], [-1.0, 0.125]], np.float32)
+    Wo, Xo = oracle.smooth_apply(W, X, k)
+    assert Wo.dtype == np.float16 and Xo.dtype == np.float16
+    assert Xo.tolist() == [[2.0, 1.5, float(np.float16(1.0 / 3.0))], [-8.0, -0.125, 3.0]]
+    assert Wo.tolist() == [[5.0, -7.0], [1.0, 2.0], [-3.0, 0.375]]
+    # the product of Eq. 2's operands is what the transfer preserves (here exactly: all factors are small integers
+    # over powers of two except the thirds, which are left out)
+    assert np.array_equal(Xo[:, :2].astype(np.float64) @ Wo[:2].astype(np.float64), X[:, :2].astype(np.float64) @ W[:2].astype(np.float64))
+
+
 def test_smooth_scales_without_activations_is_the_identity():
     assert (oracle.smooth_scales(np.zeros((2, 256), np.float32)) == 1).all()
