@@ -325,52 +325,13 @@ def test_epilogue_scales_fp16_rounding(dgq, torch):
     assert_fp16_close(out, oout)
 
 
-# ----------------------------------------------------------------------------
-# full-size LLaMA shapes, in the launch configuration the benchmark times
-# ----------------------------------------------------------------------------
 def _cols(N, n=48, seed=0):
     rng = np.random.default_rng(seed)
     c = np.unique(np.concatenate([[0, 15, 16, N - 1], rng.choice(N, n, replace=False)]))
     return c
 
 
-@pytest.mark.parametrize("shape", ["qkv", "o", "gate_up", "down"])
-def test_llama7b_decode_shapes(dgq, torch, shape):
-    K, N = workloads.LLAMA_SHAPES["7b"][shape]
-    for M in (1, 4, 16):
-        _forward_case(dgq, torch, M, K, N, 128, seed=1, cols=_cols(N, seed=M))
-
-
-@pytest.mark.parametrize("shape", ["qkv", "down"])
-def test_llama7b_prefill_shapes(dgq, torch, shape):
-    K, N = workloads.LLAMA_SHAPES["7b"][shape]
-    for M in (512, 2048):
-        _forward_case(dgq, torch, M, K, N, 128, seed=2, cols=_cols(N, 24, seed=M))
-
-
-def test_llama13b_shapes(dgq, torch):
-    K, N = workloads.LLAMA_SHAPES["13b"]["down"]
-    for M in (1, 16, 1024):
-        _forward_case(dgq, torch, M, K, N, 128, seed=3, cols=_cols(N, 24, seed=M))
-
-
-@pytest.mark.parametrize("g", [64, 128])
-def test_llama65b_shapes(dgq, torch, g):
-    K, N = workloads.LLAMA_SHAPES["65b"]["down"]
-    f, mlt = workloads.OUTLIERS["65b"]
-    for M in (1, 8, 64, 512):
-        _forward_case(dgq, torch, M, K, N, g, seed=4, frac=f, mult=mlt, cols=_cols(N, 16, seed=M))
-
-
-def test_llama65b_qkv_mid_and_large_m(dgq, torch):
-    """M = 64: 64-token tiles, six stages, K split two ways; M = 2048: the 128 x 512 tile (its grid of
-    16 x 48 fills the CUs in whole rounds)."""
-    K, N = workloads.LLAMA_SHAPES["65b"]["qkv"]
-    assert dgq.linear_plan(64, N, K, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
-    assert dgq.linear_plan(2048, N, K, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"
-    f, mlt = workloads.OUTLIERS["65b"]
-    for M in (64, 2048):
-        _forward_case(dgq, torch, M, K, N, 128, seed=5, frac=f, mult=mlt, cols=_cols(N, 16, seed=M))
+# (the full-size LLaMA shapes of the benchmark configurations are in test_gpu_configs.py)
 
 
 def test_tiled_path_activation_tensor_larger_than_4_gib(dgq, torch):
