@@ -15,15 +15,18 @@
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers unless a parameter says "host".
- *   - The caller owns every buffer; the library allocates nothing and returns no
- *     handles.  Its only state is the path selector of dgq_force_path().
+ *   - The caller owns every buffer; the library allocates nothing, returns no handles
+ *     and keeps no state that a call can change (the test hooks take the kernel path as
+ *     an argument).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and the call returns without synchronising.
  *   - Dense row-major tensors, no strides.  Device pointers must be 16-byte aligned.
  *   - Shape rules: M >= 1, K % 128 == 0, 128 <= K <= 131072 (INT32 sums cannot wrap),
  *     N % 16 == 0, group in {64, 128}.
- *   - Argument errors are found on the host and returned BEFORE anything is launched.
- *     A return value < 0 means nothing was enqueued.
+ *   - Argument errors (every status but DGQ_ERR_HIP) are found on the host and returned
+ *     BEFORE anything is launched.  DGQ_ERR_HIP reports a failed launch; where a call
+ *     enqueues two kernels (a quantizer in front of the linear, a K split with its second
+ *     pass) the first may already be enqueued when the second fails.
  *   - NaN/Inf activations give unspecified outputs, not an error.
  *   - Thread-safe; calls on the same buffers must be ordered by the caller.
  */
@@ -45,7 +48,7 @@ enum {
     DGQ_ERR_NULL = -1,      /* a required pointer is NULL                                  */
     DGQ_ERR_SHAPE = -2,     /* M, N, K or group breaks a shape rule                        */
     DGQ_ERR_ALIGN = -3,     /* a device pointer is not 16-byte aligned                     */
-    DGQ_ERR_RANGE = -4,     /* reserved for host-visible value-range errors                */
+    DGQ_ERR_RANGE = -4,     /* a scalar argument (eps, scale, pct, alpha grid, path) is out of range */
     DGQ_ERR_WORKSPACE = -5, /* workspace_bytes is smaller than dgq_linear_workspace_bytes  */
     DGQ_ERR_HIP = -6        /* a HIP call failed; see dgq_last_hip_error()                 */
 };
@@ -71,12 +74,14 @@ DGQ_API int dgq_layout_version(void);
 DGQ_API dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_bytes, size_t *scales_bytes);
 
 /*
- * Scratch needed by dgq_linear_a8w4 / dgq_linear_a8w4_acc for this problem (host
- * function).  May be 0, in which case `workspace` may be NULL.  Non-zero where several
- * workgroups split K and exchange INT32 partial sums: M <= 16 with very long K, and
- * 16 < M <= 256 for shapes with few output-channel tiles (at most 8 * M * N * 4 bytes).
+ * Scratch needed by dgq_linear_a8w4 for this problem (host function).  May be 0, in which
+ * case `workspace` may be NULL.  Non-zero where several workgroups split K and exchange
+ * INT32 partial sums: M <= 16 with very long K, and larger M for shapes with few tiles
+ * (at most 8 * M * N * 4 bytes).  dgq_linear_acc_workspace_bytes is the same for the test
+ * hooks dgq_linear_a8w4_acc / _zp_acc, which can force a kernel path (see there).
  */
 DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
+DGQ_API dgq_status dgq_linear_acc_workspace_bytes(int M, int N, int K, int group, int path, size_t *bytes);
 
 /*
  * Offline packing of the integer operands of Eq. 2 (W_u4 - ZP and S2) into the
@@ -89,6 +94,8 @@ DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, si
  *            number of inputs outside the ranges above (such a nibble is packed as 0,
  *            such a scale as 1).  Inside the ranges |S2 * w4| <= 120, so the paper's
  *            constraint W_s8 in [-128, 127] (beside Eq. 4) holds for every packed weight.
+ * The channel scale s1 of Eq. 2 is not an argument: it is used only by the epilogue, as a
+ * plain [N] float array that needs no packing, and goes straight to dgq_linear_a8w4.
  *
  * Format, version 1.  Stored nibble u = w4 + 8.  qweight is a sequence of 16-byte cells;
  * element (k, n) is in cell ((n/16)*(K/128) + k/128)*64 + ((k%128)/32)*16 + n%16, byte
@@ -203,9 +210,15 @@ DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void
 /*
  * Test hook: same kernels and main loop as dgq_linear_a8w4 but the epilogue stores the
  * raw INT32 sums X_s8 W_s8 (third line of Eq. 2 before scaling) to acc_out [M][N].
+ *   path  0 = the kernel dgq_linear_a8w4 chooses for this M; 1 = the weight-streaming
+ *         kernels; 2 = the tiled kernel; 3 = the weight-streaming kernel that re-reads
+ *         activations every step (never chosen by M; kept as an independent check, signed
+ *         nibbles only).  The weight-streaming kernels take M <= 64 (DGQ_ERR_SHAPE beyond);
+ *         any other value gives DGQ_ERR_RANGE.
+ *   workspace  at least dgq_linear_acc_workspace_bytes() for the same path
  */
 DGQ_API dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales,
-                               int32_t *acc_out, int M, int N, int K, int group,
+                               int32_t *acc_out, int M, int N, int K, int group, int path,
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -262,26 +275,15 @@ DGQ_API dgq_status dgq_unpack_weights_zp(const void *qweight, const void *scales
 /*
  * dgq_linear_a8w4 / dgq_linear_a8w4_acc for operands packed by dgq_pack_weights_zp: same
  * kernels (the zero point is one more byte in the scale word), same arguments, same workspace
- * rule.  Not available under dgq_force_path(3).
+ * rule.  path 3 of the test hook is not available for this form (DGQ_ERR_SHAPE).
  */
 DGQ_API dgq_status dgq_linear_a8w4_zp(const int8_t *xq, const float *sx, const void *qweight,
                               const void *scales_zp, const float *s1, uint16_t *out,
                               int M, int N, int K, int group,
                               void *workspace, size_t workspace_bytes, void *stream);
 DGQ_API dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight, const void *scales_zp,
-                                  int32_t *acc_out, int M, int N, int K, int group,
+                                  int32_t *acc_out, int M, int N, int K, int group, int path,
                                   void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Selects the GEMM path for later dgq_linear_a8w4* and dgq_linear_workspace_bytes calls of
- * this process (host, for tests and measurements): 0 = choose by M (default), 1 = the
- * weight-streaming kernels, 2 = the tiled kernel, 3 = the weight-streaming kernel that
- * re-reads activations every step (never chosen by M; kept as an independent check).  Returns the
- * previous value; an unknown value changes nothing and returns -1.  The weight-streaming
- * kernels accept M <= 64 only; forcing them for a larger M makes the linear calls return
- * DGQ_ERR_SHAPE.
- */
-DGQ_API int dgq_force_path(int path);
 
 /*
  * dgq_quant_act followed by dgq_linear_a8w4 (dgq_linear_a8w4_zp) as one call: the per-token
@@ -322,9 +324,8 @@ DGQ_API dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *b
  *   gamma  in [K] fp16 (raw bits), 16-byte aligned;   0 <= eps < 1 (DGQ_ERR_RANGE otherwise)
  * K <= 24576.  One kernel under the conditions of dgq_quant_linear_a8w4 and K <= 8192 (the
  * hidden sizes of LLaMA-7B to 65B); otherwise the two kernels, with xq and sx in the workspace
- * (dgq_rmsnorm_quant_linear_workspace_bytes).  In the one-kernel form the sums of squares are added
- * in an order that is not fixed; that moves the fp64 factor in its last bits, far below what
- * survives the rounding to fp32 and fp16.
+ * (dgq_rmsnorm_quant_linear_workspace_bytes).  Both forms add the squares in the same fixed order,
+ * so they give the same bits.
  */
 DGQ_API dgq_status dgq_rmsnorm_quant_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
 DGQ_API dgq_status dgq_rmsnorm_quant_linear_a8w4(const uint16_t *x, const uint16_t *gamma, float eps,
@@ -339,8 +340,7 @@ DGQ_API dgq_status dgq_rmsnorm_quant_linear_a8w4_zp(const uint16_t *x, const uin
 /*
  * Measurement aid (host function, nothing launched): writes into buf (at least 96 bytes)
  * the name, with template arguments, of the GEMM kernel that dgq_linear_a8w4 would launch
- * for this problem under the current dgq_force_path() setting, e.g.
- * "linear_decode_kernel<2, 2, 128, false, false>".  Profiler output can be matched to it.
+ * for this problem, e.g. "linear_decode_kernel<2, 2, 128, false, false>".  Profiler output can be matched to it.
  */
 DGQ_API dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf_bytes);
 

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "force_path", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
+    "linear_acc_workspace_bytes", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -42,10 +42,10 @@ def _load() -> ctypes.CDLL:
     L.dgq_status_string.argtypes = [i]
     L.dgq_last_hip_error.restype = i
     L.dgq_layout_version.restype = i
-    L.dgq_force_path.restype = i
-    L.dgq_force_path.argtypes = [i]
     L.dgq_packed_sizes.argtypes = [i, i, i, psz, psz]
     L.dgq_linear_workspace_bytes.argtypes = [i, i, i, i, psz]
+    L.dgq_linear_acc_workspace_bytes.argtypes = [i, i, i, i, i, psz]
+    L.dgq_linear_acc_workspace_bytes.restype = i
     L.dgq_pack_weights.argtypes = [vp, vp, i, i, i, vp, vp, vp, vp]
     L.dgq_unpack_weights.argtypes = [vp, vp, i, i, i, vp, vp]
     L.dgq_quantize_weights_rtn.argtypes = [vp, i, i, i, vp, vp, vp, vp]
@@ -56,13 +56,13 @@ def _load() -> ctypes.CDLL:
     L.dgq_smooth_scales.argtypes = [vp, i, i, ctypes.c_float, vp, vp, sz, vp]
     L.dgq_smooth_apply.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
-    L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
     L.dgq_quantize_weights_grid.argtypes = [vp, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
     L.dgq_packed_sizes_zp.argtypes = [i, i, i, psz, psz]
     L.dgq_pack_weights_zp.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, vp]
     L.dgq_unpack_weights_zp.argtypes = [vp, vp, i, i, i, vp, vp]
     L.dgq_linear_a8w4_zp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
-    L.dgq_linear_a8w4_zp_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_linear_a8w4_zp_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
     L.dgq_probe_read.argtypes = [vp, sz, vp, i, vp]
     L.dgq_probe_mfma.argtypes = [vp, sz, i, vp, i, vp]
     L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
@@ -109,12 +109,6 @@ def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
 
 def layout_version() -> int:
     return lib.dgq_layout_version()
-
-
-def force_path(path: int) -> int:
-    """0 = choose by M, 1 = weight-streaming kernels, 2 = tiled kernel, 3 = streaming kernel that
-    re-reads activations every step.  Returns the old value."""
-    return lib.dgq_force_path(path)
 
 
 def packed_sizes(K: int, N: int, group: int):
@@ -409,17 +403,27 @@ def probe_mfma(operands: torch.Tensor, iters: int, sink: torch.Tensor, workgroup
     return 2 * 32 * 32 * 32 * 8 * iters * 4 * workgroups
 
 
-def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor = None) -> torch.Tensor:
-    """dgq_linear_a8w4_acc: raw INT32 sums [M,N] of the same kernels (test hook)."""
+def linear_acc_workspace_bytes(M: int, N: int, K: int, group: int, path: int = 0) -> int:
+    """dgq_linear_acc_workspace_bytes."""
+    b = ctypes.c_size_t()
+    _check(lib.dgq_linear_acc_workspace_bytes(M, N, K, group, path, ctypes.byref(b)), "dgq_linear_acc_workspace_bytes")
+    return b.value
+
+
+def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor = None, path: int = 0) -> torch.Tensor:
+    """dgq_linear_a8w4_acc: raw INT32 sums [M,N] of the same kernels (test hook).  path: 0 = the kernel
+    dgq_linear_a8w4 chooses, 1 = weight-streaming kernels, 2 = tiled kernel, 3 = the streaming kernel that
+    re-reads activations every step."""
     _dev(xq, torch.int8, "xq")
     M, K = xq.shape
     if K != pw.K:
         raise ValueError("xq has K=%d but the packed weight has K=%d" % (K, pw.K))
     acc = torch.empty((M, pw.N), dtype=torch.int32, device=xq.device)
     if workspace is None:
-        workspace = _workspace(M, pw.N, K, pw.group, xq.device)
+        nbytes = linear_acc_workspace_bytes(M, pw.N, K, pw.group, path)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=xq.device) if nbytes else None
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     fn = lib.dgq_linear_a8w4_zp_acc if pw.zp_form else lib.dgq_linear_a8w4_acc
-    _check(fn(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group,
+    _check(fn(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group, path,
               _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4_acc")
     return acc

@@ -1,6 +1,5 @@
 // extern "C" boundary of libdgq.so: argument validation on the host, then one launcher.
 // Every check happens before anything is enqueued.
-#include <atomic>
 #include <cmath>
 #include <cstdio>
 
@@ -9,7 +8,6 @@
 namespace {
 
 thread_local int g_last_hip_error = 0;
-std::atomic<int> g_force_path{0};
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -49,9 +47,9 @@ size_t workspace_needed(int path, int M, int N, int K)
     return 0;
 }
 
-dgq_status run_linear(dgq::LinearArgs &a, void *workspace, size_t workspace_bytes, void *stream)
+dgq_status run_linear(dgq::LinearArgs &a, int forced, void *workspace, size_t workspace_bytes, void *stream)
 {
-    const int forced = g_force_path.load(std::memory_order_relaxed);
+    if (forced < kPathAuto || forced > kPathStreamGeneric) return DGQ_ERR_RANGE;
     if ((forced == kPathStream || forced == kPathStreamGeneric) && a.M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
     const int path = pick_path(a.M, forced);
     if (path == kPathStreamGeneric && a.zp) return DGQ_ERR_SHAPE;  // that kernel knows the constant zero point only
@@ -90,8 +88,7 @@ dgq_status quant_linear(const uint16_t *x, const uint16_t *gamma, float eps, con
     if (!aligned16(x) || !aligned16(qweight) || !aligned16(scales) || !aligned16(out) || !aligned16(gamma) ||
         (reinterpret_cast<uintptr_t>(s1) & 3u) || (reinterpret_cast<uintptr_t>(sx_out) & 3u))
         return DGQ_ERR_ALIGN;
-    const int forced = g_force_path.load(std::memory_order_relaxed);
-    if ((forced == kPathStream || forced == kPathStreamGeneric) && M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
+    const int forced = kPathAuto;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (quantizes_in_kernel(M, K, forced) && (!gamma || dgq::decode_plan(K).spw <= dgq::kRmsDecodeMaxStepsPerWave)) {
         dgq::LinearArgs a{nullptr, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
@@ -113,7 +110,7 @@ dgq_status quant_linear(const uint16_t *x, const uint16_t *gamma, float eps, con
     const hipError_t qe = gamma ? dgq::launch_rmsnorm_quant_act(x, gamma, M, K, eps, xq, sx, st)
                                 : dgq::launch_quant_act(x, M, K, xq, sx, st);
     if (dgq_status q = hip_result(qe)) return q;
-    return run_linear(a, ws + xq_bytes + sx_bytes, workspace_bytes - xq_bytes - sx_bytes, stream);
+    return run_linear(a, kPathAuto, ws + xq_bytes + sx_bytes, workspace_bytes - xq_bytes - sx_bytes, stream);
 }
 
 }  // namespace
@@ -138,12 +135,6 @@ int dgq_last_hip_error(void) { return g_last_hip_error; }
 
 int dgq_layout_version(void) { return DGQ_LAYOUT_VERSION; }
 
-int dgq_force_path(int path)
-{
-    if (path < 0 || path > 3) return -1;
-    return g_force_path.exchange(path);
-}
-
 dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_bytes, size_t *scales_bytes)
 {
     if (!qweight_bytes || !scales_bytes) return DGQ_ERR_NULL;
@@ -160,8 +151,19 @@ dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *by
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
     // Partial sums go through global memory when several workgroups split K: the decode kernel
-    // with a K too long for one workgroup, and the tiled kernel for M <= 64.
-    *bytes = workspace_needed(pick_path(M, g_force_path.load(std::memory_order_relaxed)), M, N, K);
+    // with a K too long for one workgroup, and the tiled kernel where its plan splits K.
+    *bytes = workspace_needed(pick_path(M, kPathAuto), M, N, K);
+    return DGQ_OK;
+}
+
+dgq_status dgq_linear_acc_workspace_bytes(int M, int N, int K, int group, int path, size_t *bytes)
+{
+    if (!bytes) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (path < kPathAuto || path > kPathStreamGeneric) return DGQ_ERR_RANGE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if ((path == kPathStream || path == kPathStreamGeneric) && M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
+    *bytes = workspace_needed(pick_path(M, path), M, N, K);
     return DGQ_OK;
 }
 
@@ -259,11 +261,11 @@ static dgq_status linear_fp16(const int8_t *xq, const float *sx, const void *qwe
         return DGQ_ERR_ALIGN;
     dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
                       s1, out, nullptr, M, N, K, group, zp_form};
-    return run_linear(a, workspace, workspace_bytes, stream);
+    return run_linear(a, kPathAuto, workspace, workspace_bytes, stream);
 }
 
 static dgq_status linear_acc(const int8_t *xq, const void *qweight, const void *scales, int zp_form,
-                             int32_t *acc_out, int M, int N, int K, int group, void *workspace,
+                             int32_t *acc_out, int M, int N, int K, int group, int path, void *workspace,
                              size_t workspace_bytes, void *stream)
 {
     if (!xq || !qweight || !scales || !acc_out) return DGQ_ERR_NULL;
@@ -272,7 +274,7 @@ static dgq_status linear_acc(const int8_t *xq, const void *qweight, const void *
     if (!aligned16(xq) || !aligned16(qweight) || !aligned16(scales) || !aligned16(acc_out)) return DGQ_ERR_ALIGN;
     dgq::LinearArgs a{xq, nullptr, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
                       nullptr, nullptr, acc_out, M, N, K, group, zp_form};
-    return run_linear(a, workspace, workspace_bytes, stream);
+    return run_linear(a, path, workspace, workspace_bytes, stream);
 }
 
 dgq_status dgq_smooth_scales(const uint16_t *X, int M, int K, float pct, float *k, void *workspace,
@@ -338,10 +340,10 @@ dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweigh
 }
 
 dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales, int32_t *acc_out,
-                               int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
+                               int M, int N, int K, int group, int path, void *workspace, size_t workspace_bytes,
                                void *stream)
 {
-    return linear_acc(xq, qweight, scales, 0, acc_out, M, N, K, group, workspace, workspace_bytes, stream);
+    return linear_acc(xq, qweight, scales, 0, acc_out, M, N, K, group, path, workspace, workspace_bytes, stream);
 }
 
 dgq_status dgq_linear_a8w4_zp(const int8_t *xq, const float *sx, const void *qweight, const void *scales_zp,
@@ -352,10 +354,10 @@ dgq_status dgq_linear_a8w4_zp(const int8_t *xq, const float *sx, const void *qwe
 }
 
 dgq_status dgq_linear_a8w4_zp_acc(const int8_t *xq, const void *qweight, const void *scales_zp, int32_t *acc_out,
-                                  int M, int N, int K, int group, void *workspace, size_t workspace_bytes,
+                                  int M, int N, int K, int group, int path, void *workspace, size_t workspace_bytes,
                                   void *stream)
 {
-    return linear_acc(xq, qweight, scales_zp, 1, acc_out, M, N, K, group, workspace, workspace_bytes, stream);
+    return linear_acc(xq, qweight, scales_zp, 1, acc_out, M, N, K, group, path, workspace, workspace_bytes, stream);
 }
 
 static dgq_status quant_linear_workspace(int M, int N, int K, int group, bool rms, size_t *bytes)
@@ -363,7 +365,7 @@ static dgq_status quant_linear_workspace(int M, int N, int K, int group, bool rm
     if (!bytes) return DGQ_ERR_NULL;
     if (M < 1) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
-    const int forced = g_force_path.load(std::memory_order_relaxed);
+    const int forced = kPathAuto;
     if (quantizes_in_kernel(M, K, forced) && (!rms || dgq::decode_plan(K).spw <= dgq::kRmsDecodeMaxStepsPerWave))
         *bytes = 0;
     else
@@ -422,7 +424,7 @@ dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *buf, size
     if (!buf) return DGQ_ERR_NULL;
     if (M < 1 || buf_bytes < 96) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
-    if (quantizes_in_kernel(M, K, g_force_path.load(std::memory_order_relaxed))) {
+    if (quantizes_in_kernel(M, K, kPathAuto)) {
         const dgq::DecodePlan p = dgq::decode_plan(K);
         std::snprintf(buf, buf_bytes, "quant_linear_decode_kernel<%d, %d, %d>", p.spw, p.pf, group);
         return DGQ_OK;
@@ -435,9 +437,7 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
     if (!buf) return DGQ_ERR_NULL;
     if (M < 1 || buf_bytes < 96) return DGQ_ERR_SHAPE;
     if (dgq_status st = check_shape(N, K, group)) return st;
-    const int forced = g_force_path.load(std::memory_order_relaxed);
-    if ((forced == kPathStream || forced == kPathStreamGeneric) && M > dgq::kStreamMaxM) return DGQ_ERR_SHAPE;
-    switch (pick_path(M, forced)) {
+    switch (pick_path(M, kPathAuto)) {
     case kPathStream: {
         const dgq::DecodePlan p = dgq::decode_plan(K);
         std::snprintf(buf, buf_bytes, "linear_decode_kernel<%d, %d, %d, false, %s>", p.spw, p.pf, group,

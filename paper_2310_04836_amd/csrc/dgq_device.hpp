@@ -195,6 +195,50 @@ __device__ __forceinline__ uint32_t wave_max_u32_lane63(uint32_t mx)
     return mx;
 }
 
+// ---- sum of squares of a token for RMSNorm, in ONE fixed order for every kernel -------------
+// Both kernels that normalise (the stand-alone producer and the decode kernel that normalises
+// and quantizes its own activations) add the squares of a row of K = 8 * nvec values like this,
+// all in fp64, so that they derive the same factor bit for bit:
+//   1. s_v      = the eight squares of 8-value vector v, added in element order starting from 0
+//   2. P[w][l]  = s_v for v = 64*w + l, 64*w + l + 256, ... (increasing v, starting from 0),
+//                 w = 0..3, l = 0..63
+//   3. W[w]     = the sum of P[w][0..63] by the lane-exchange tree of wave_sum_f64_lane63
+//   4. total    = ((W[0] + W[1]) + W[2]) + W[3]
+__device__ __forceinline__ double sum_squares_f64(const uint4 &v)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    double ss = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const double lo = (double)half_bits_to_float(w[k] & 0xFFFFu), hi = (double)half_bits_to_float(w[k] >> 16);
+        ss += lo * lo;
+        ss += hi * hi;
+    }
+    return ss;
+}
+// Sum over the 64 lanes with data-parallel-primitive moves of both halves of the double (same
+// lane pattern as wave_max_u32_lane63; a masked-off source contributes +0.0).  LANE 63 holds
+// the result.
+__device__ __forceinline__ double wave_sum_f64_lane63(double ss)
+{
+#define DGQ_DPP_ADD(CTRL, ROWS)                                                                            \
+    do {                                                                                                   \
+        const uint2 b_ = __builtin_bit_cast(uint2, ss);                                                    \
+        uint2 o_;                                                                                          \
+        o_.x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b_.x, (CTRL), (ROWS), 0xF, false);            \
+        o_.y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b_.y, (CTRL), (ROWS), 0xF, false);            \
+        ss += __builtin_bit_cast(double, o_);                                                              \
+    } while (0)
+    DGQ_DPP_ADD(0xB1, 0xF);    // quad_perm [1,0,3,2]
+    DGQ_DPP_ADD(0x4E, 0xF);    // quad_perm [2,3,0,1]
+    DGQ_DPP_ADD(0x124, 0xF);   // row_ror 4
+    DGQ_DPP_ADD(0x128, 0xF);   // row_ror 8
+    DGQ_DPP_ADD(0x142, 0xA);   // row_bcast 15 into rows 1 and 3
+    DGQ_DPP_ADD(0x143, 0xC);   // row_bcast 31 into rows 2 and 3
+#undef DGQ_DPP_ADD
+    return ss;
+}
+
 // ---- kernel launchers (defined one per .hip file) ----------------------------------
 hipError_t launch_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, hipStream_t st);
 hipError_t launch_rmsnorm_quant_act(const uint16_t *x, const uint16_t *gamma, int M, int K, float eps, int8_t *xq,

@@ -43,7 +43,7 @@ struct DecodeGrid {
     int tiles_base;  // every workgroup has this many column tiles ...
     int tiles_rem;   // ... and the first tiles_rem one more
 };
-struct DecodeLds {
+struct alignas(16) DecodeLds {
     int red[2][kWaves][256];           // partial tiles of the 16 wavefronts, double buffered
     int sums[kMaxTilesPerWg][256];     // finished INT32 tiles
 };
@@ -52,7 +52,8 @@ static_assert(sizeof(DecodeLds::red) / 2 + sizeof(DecodeLds::sums) == kQuantDeco
 // ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes (compile-time).
 // FQ: activations arrive as fp16 and are quantized here (needs ksplit == 1, no ACC, no PARTIAL).
 // RMS (with FQ): the fp16 input is RMS-normalised and multiplied by gamma first, as
-// rmsnorm_quant_act_kernel does it (fp64 up to the rounding to fp32 and then fp16).
+// rmsnorm_quant_act_kernel does it (fp64 up to the rounding to fp32 and then fp16, the squares
+// added in the same fixed order).
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP, bool FQ, bool RMS = false>
 __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGrid &grid, int32_t *partial)
 {
@@ -145,51 +146,29 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGri
         uint8_t *stage = reinterpret_cast<uint8_t *>(&red[1][0][0]);
         if constexpr (RMS) {
             // y = fp16(float(x * r * gamma)), r = 1 / sqrt(mean(x^2) + eps), all in fp64 up to the two
-            // roundings.  Sums of squares go the way of the maxima below: one LDS slot per token
-            // and lane (ssp, upper half of red[0]), then wavefront w adds up token w.  The order
-            // of the additions is not fixed; it moves r in the last bits of a double, far below
-            // what survives the roundings.
-            double *ssp = reinterpret_cast<double *>(&red[0][8][0]);
+            // roundings.  Every 8-value vector leaves the sum of its squares in an LDS slot of its
+            // own (ssq, in the staging area that the quantizer fills later; no atomics), and
+            // wavefront w adds up the slots of token w in the one fixed order that
+            // rmsnorm_quant_act_kernel uses too (see sum_squares_f64), so both give the same bits.
+            double *ssq = reinterpret_cast<double *>(stage);
             double *tr = reinterpret_cast<double *>(&red[0][4][64]);
-            ssp[threadIdx.x] = 0.0;
-            __syncthreads();
 #pragma unroll
             for (int i = 0; i < kVec; ++i) {
                 const int idx = threadIdx.x + i * (kWaves * 64);
-                if (idx < nvec) {
-                    const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-                    double ss = 0.0;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const double lo = (double)half_bits_to_float(w[k] & 0xFFFFu), hi = (double)half_bits_to_float(w[k] >> 16);
-                        ss += lo * lo;
-                        ss += hi * hi;
-                    }
-                    atomicAdd(&ssp[tok[i] * 64 + lane], ss);
-                }
+                if (idx < nvec) ssq[idx] = sum_squares_f64(v[i]);
             }
             __syncthreads();
-            {
-                // sum over the wavefront with data-parallel-primitive moves of both halves of the
-                // double (same lane pattern as the maximum below; a masked-off source gives +0.0);
-                // lane 63 ends up with the total
-                double ss = ssp[threadIdx.x];
-#define DGQ_DPP_ADD(CTRL, ROWS)                                                                            \
-    do {                                                                                                   \
-        const uint2 b_ = __builtin_bit_cast(uint2, ss);                                                    \
-        uint2 o_;                                                                                          \
-        o_.x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b_.x, (CTRL), (ROWS), 0xF, false);            \
-        o_.y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b_.y, (CTRL), (ROWS), 0xF, false);            \
-        ss += __builtin_bit_cast(double, o_);                                                              \
-    } while (0)
-                DGQ_DPP_ADD(0xB1, 0xF);    // quad_perm [1,0,3,2]
-                DGQ_DPP_ADD(0x4E, 0xF);    // quad_perm [2,3,0,1]
-                DGQ_DPP_ADD(0x124, 0xF);   // row_ror 4
-                DGQ_DPP_ADD(0x128, 0xF);   // row_ror 8
-                DGQ_DPP_ADD(0x142, 0xA);   // row_bcast 15 into rows 1 and 3
-                DGQ_DPP_ADD(0x143, 0xC);   // row_bcast 31 into rows 2 and 3
-#undef DGQ_DPP_ADD
-                if (lane == 63) tr[wave] = 1.0 / sqrt(ss / (double)a.K + (double)a.eps);
+            if (wave < a.M) {
+                const double *mine = ssq + wave * vpr;
+                double total = 0.0;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    double p = 0.0;
+                    for (int t = 64 * w + lane; t < vpr; t += 256) p += mine[t];
+                    p = wave_sum_f64_lane63(p);
+                    total = w == 0 ? p : total + p;
+                }
+                if (lane == 63) tr[wave] = 1.0 / sqrt(total / (double)a.K + (double)a.eps);
             }
             __syncthreads();
 #pragma unroll

@@ -129,16 +129,11 @@ __global__ __launch_bounds__(kThreads) void silu_mul_quant_act_kernel(const uint
 }
 
 // RMSNorm fused with the per-token quantizer: y = fp16(float(x * r * gamma)), r = 1/sqrt(mean x^2 + eps),
-// everything up to the two roundings in fp64.  The sum of squares is added in fp64 by a tree over
-// threads; that order differs from a running sum only in the last bits of a double, far below what
-// survives the rounding to fp32 and fp16.  y is kept in registers as fp16 bits (K <= 2048 * VPT).
-__device__ __forceinline__ double wave_sum_f64(double v)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
-
+// everything up to the two roundings in fp64.  The sum of squares is added in fp64 in the fixed order
+// described at sum_squares_f64 (shared with the decode kernel that normalises its own activations, so
+// both give the same bits); that order differs from a running sum only in the last bits of a double,
+// far below what survives the rounding to fp32 and fp16.  y is kept in registers as fp16 bits
+// (K <= 2048 * VPT).
 template <int VPT>
 __global__ __launch_bounds__(kThreads) void rmsnorm_quant_act_kernel(const uint16_t *__restrict__ x,
                                                                      const uint16_t *__restrict__ gamma, int M, int K,
@@ -159,16 +154,10 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quant_act_kernel(const uint1
     for (int i = 0; i < VPT; ++i) {
         const int idx = threadIdx.x + i * kThreads;
         cache[i] = idx < nvec ? row[idx] : make_uint4(0, 0, 0, 0);
-        const uint32_t w[4] = {cache[i].x, cache[i].y, cache[i].z, cache[i].w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const double lo = (double)half_bits_to_float(w[k] & 0xFFFFu), hi = (double)half_bits_to_float(w[k] >> 16);
-            ss += lo * lo;
-            ss += hi * hi;
-        }
+        ss += sum_squares_f64(cache[i]);     // the fixed order described at sum_squares_f64
     }
-    ss = wave_sum_f64(ss);
-    if ((threadIdx.x & 63) == 0) wave_s[threadIdx.x >> 6] = ss;
+    ss = wave_sum_f64_lane63(ss);
+    if ((threadIdx.x & 63) == 63) wave_s[threadIdx.x >> 6] = ss;
     __syncthreads();
     ss = wave_s[0];
 #pragma unroll

@@ -65,7 +65,7 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_quant_act(None, 1, 128, good, good, None) == -1
     assert L.dgq_quant_act(good, 1, 128, None, good, None) == -1
     assert L.dgq_linear_a8w4(good, good, good, good, None, good, 1, 16, 128, 128, None, 0, None) == -1
-    assert L.dgq_linear_a8w4_acc(good, good, good, None, 1, 16, 128, 128, None, 0, None) == -1
+    assert L.dgq_linear_a8w4_acc(good, good, good, None, 1, 16, 128, 128, 0, None, 0, None) == -1
     assert L.dgq_pack_weights(good, None, 128, 16, 128, good, good, None, None) == -1
     assert L.dgq_unpack_weights(good, good, 128, 16, 128, None, None) == -1
     assert L.dgq_quantize_weights_rtn(good, 128, 16, 128, good, good, None, None) == -1
@@ -75,7 +75,7 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4(good, good, good, good, good, good, 0, 16, 128, 128, None, 0, None) == -2
     assert L.dgq_linear_a8w4(good, good, good, good, good, good, 1, 16, 128, 96, None, 0, None) == -2
     assert L.dgq_linear_a8w4(good, good, good, good, good, good, 1, 20, 128, 128, None, 0, None) == -2
-    assert L.dgq_linear_a8w4_acc(good, good, good, good, 1, 16, 192, 64, None, 0, None) == -2
+    assert L.dgq_linear_a8w4_acc(good, good, good, good, 1, 16, 192, 64, 0, None, 0, None) == -2
     assert L.dgq_pack_weights(good, good, 128, 16, 100, good, good, None, None) == -2
     # alignment
     assert L.dgq_quant_act(odd, 1, 128, good, good, None) == -3
@@ -87,7 +87,7 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_pack_weights_zp(good, good, good, 128, 24, 128, good, good, None, None) == -2
     assert L.dgq_pack_weights_zp(good, odd, good, 128, 16, 128, good, good, None, None) == -3
     assert L.dgq_linear_a8w4_zp(good, good, good, None, good, good, 1, 16, 128, 128, None, 0, None) == -1
-    assert L.dgq_linear_a8w4_zp_acc(good, good, good, good, 0, 16, 128, 128, None, 0, None) == -2
+    assert L.dgq_linear_a8w4_zp_acc(good, good, good, good, 0, 16, 128, 128, 0, None, 0, None) == -2
     assert L.dgq_unpack_weights_zp(good, good, 128, 16, 32, good, None) == -2
     # grid-search quantizer: alpha grid and workspace are checked on the host
     import ctypes
@@ -172,11 +172,6 @@ def test_linear_plan_names(dgq):
     assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"
     assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
     assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 16 x 16 wide tiles
-    old = dgq.force_path(3)
-    try:
-        assert dgq.linear_plan(64, 8192, 8192, 128).startswith("linear_stream_kernel<4, 128, ")
-    finally:
-        dgq.force_path(old)
 
 
 def test_packed_sizes_zp(dgq):
@@ -184,16 +179,18 @@ def test_packed_sizes_zp(dgq):
     assert dgq.packed_sizes_zp(384, 48, 128) == (384 * 48 // 2, 3 * 2 * 64)     # 3 groups padded to 4
 
 
-def test_force_path_selector(dgq):
-    assert dgq.force_path(7) == -1
-    old = dgq.force_path(1)
-    try:
-        # the streaming path refuses M > 64 on the host
-        good = 0x10000
-        assert dgq.lib.dgq_linear_a8w4_acc(good, good, good, good, 65, 16, 128, 128, None, 0, None) == -2
-        assert dgq.force_path(2) == 1
-    finally:
-        dgq.force_path(old)
+def test_path_argument_of_the_test_hooks(dgq):
+    good = 0x10000
+    # an unknown path is a range error, the streaming paths refuse M > 64, both on the host
+    assert dgq.lib.dgq_linear_a8w4_acc(good, good, good, good, 8, 16, 128, 128, 7, None, 0, None) == -4
+    assert dgq.lib.dgq_linear_a8w4_acc(good, good, good, good, 65, 16, 128, 128, 1, None, 0, None) == -2
+    assert dgq.lib.dgq_linear_a8w4_zp_acc(good, good, good, good, 65, 16, 128, 128, 3, None, 0, None) == -2
+    # the workspace of a forced path is the one that path needs
+    assert dgq.linear_acc_workspace_bytes(64, 8192, 8192, 128, 0) == dgq.linear_workspace_bytes(64, 8192, 8192, 128)
+    assert dgq.linear_acc_workspace_bytes(8, 8192, 22016, 128, 1) == 2 * 8 * 8192 * 4
+    assert dgq.linear_acc_workspace_bytes(64, 8192, 8192, 128, 3) == 0
+    with pytest.raises(dgq.DGQError):
+        dgq.linear_acc_workspace_bytes(65, 8192, 8192, 128, 1)
 
 
 def test_token_index_without_division_matches_integer_division():

@@ -123,11 +123,7 @@ def _acc_case(dgq, torch, M, K, N, g, seed, path=0, onehot=False):
     else:
         xq, _ = workloads.integer_activations(M, K, seed)
     pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
-    old = dgq.force_path(path)
-    try:
-        acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
-    finally:
-        dgq.force_path(old)
+    acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw, path=path))
     ws8, _ = oracle.expand(w4, s2, g)
     if onehot:
         # closed form: a one-hot token reads out one row of W_s8
@@ -252,11 +248,7 @@ def test_both_paths_and_split_factors_agree(dgq, torch):
         pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
         res = []
         for path in (1, 2, 3):
-            old = dgq.force_path(path)
-            try:
-                res.append(host(dgq.linear_a8w4_acc(dev(torch, xq), pw)))
-            finally:
-                dgq.force_path(old)
+            res.append(host(dgq.linear_a8w4_acc(dev(torch, xq), pw, path=path)))
         assert np.array_equal(res[0], res[1]) and np.array_equal(res[0], res[2])
         assert np.array_equal(res[0].astype(np.int64), xq.astype(np.int64) @ (
             np.repeat(s2.astype(np.int64), g, axis=0) * w4))
@@ -402,11 +394,7 @@ def _acc_case_zp(dgq, torch, M, K, N, g, seed, path=0):
     u4, s2, zp, s1 = _zp_operands(K, N, g, seed)
     xq, _ = workloads.integer_activations(M, K, seed)
     pw = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), g)
-    old = dgq.force_path(path)
-    try:
-        acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw))
-    finally:
-        dgq.force_path(old)
+    acc = host(dgq.linear_a8w4_acc(dev(torch, xq), pw, path=path))
     ws8, bad = oracle.expand_zp(u4, s2, zp, g)
     assert bad == 0
     oacc, wrapped = oracle.gemm_i32(xq, ws8)
@@ -444,24 +432,17 @@ def test_zp_form_with_zero_point_8_equals_signed_nibble_form(dgq, torch):
             xs = xq[:16]
         else:
             xs = xq
-        old = dgq.force_path(path)
-        try:
-            assert np.array_equal(host(dgq.linear_a8w4_acc(dev(torch, xs), a)), host(dgq.linear_a8w4_acc(dev(torch, xs), b)))
-        finally:
-            dgq.force_path(old)
+        assert np.array_equal(host(dgq.linear_a8w4_acc(dev(torch, xs), a, path=path)),
+                              host(dgq.linear_a8w4_acc(dev(torch, xs), b, path=path)))
 
 
 def test_zp_form_is_refused_by_the_forced_streaming_kernel(dgq, torch):
     u4, s2, zp, s1 = _zp_operands(128, 16, 128, 1)
     pw = dgq.pack_weights_zp(dev(torch, u4), dev(torch, s2), dev(torch, zp), dev(torch, s1), 128)
     xq, _ = workloads.integer_activations(20, 128, 1)
-    old = dgq.force_path(3)
-    try:
-        with pytest.raises(dgq.DGQError) as e:
-            dgq.linear_a8w4_acc(dev(torch, xq), pw)
-        assert e.value.status == -2
-    finally:
-        dgq.force_path(old)
+    with pytest.raises(dgq.DGQError) as e:
+        dgq.linear_a8w4_acc(dev(torch, xq), pw, path=3)
+    assert e.value.status == -2
 
 
 @pytest.mark.parametrize("M,K,N,g", [(8, 1024, 256, 128), (64, 1024, 512, 64), (200, 512, 272, 128)])
