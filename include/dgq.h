@@ -208,6 +208,24 @@ DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dgq_linear_a8w4 for callers that can neither allocate device memory nor bring a workspace:
+ * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without the workspace, same kernels, same bits.  Where the problem needs scratch (the
+ * INT32 partial sums of a K split, dgq_linear_workspace_bytes() > 0) it lives in a static device
+ * array of 32 MiB inside the library, which every GPU the library has run on holds until the
+ * process ends; a problem that needs more returns DGQ_ERR_WORKSPACE (nothing is launched).  The
+ * call makes no hipMalloc / hipFree and no allocating library call.  The first call on a device
+ * looks up that device's address of the array (hipGetSymbolAddress with the device current, as
+ * for any launch); make that first call outside graph capture.  All calls on one GPU share the
+ * array: calls that need scratch and may overlap on one GPU (different streams, or graph
+ * branches) race and must be ordered by the caller.  Nothing in the array has to start at zero
+ * (every partial sum is written before it is read).
+ */
+DGQ_API dgq_status dgq_linear_a8w4_noalloc(const int8_t *xq, const float *sx, const void *qweight,
+                                   const void *scales, const float *s1, uint16_t *out,
+                                   int M, int N, int K, int group, void *stream);
+
+/*
  * Test hook: same kernels and main loop as dgq_linear_a8w4 but the epilogue stores the
  * raw INT32 sums X_s8 W_s8 (third line of Eq. 2 before scaling) to acc_out [M][N].
  *   path  0 = the kernel dgq_linear_a8w4 chooses for this M; 1 = the weight-streaming

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "linear_acc_workspace_bytes", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
+    "linear_acc_workspace_bytes", "linear_a8w4_noalloc", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -56,6 +56,8 @@ def _load() -> ctypes.CDLL:
     L.dgq_smooth_scales.argtypes = [vp, i, i, ctypes.c_float, vp, vp, sz, vp]
     L.dgq_smooth_apply.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.dgq_linear_a8w4.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dgq_linear_a8w4_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.dgq_linear_a8w4_noalloc.restype = i
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
     L.dgq_quantize_weights_grid.argtypes = [vp, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
     L.dgq_packed_sizes_zp.argtypes = [i, i, i, psz, psz]
@@ -311,6 +313,18 @@ def linear_a8w4(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch
     fn = lib.dgq_linear_a8w4_zp if pw.zp_form else lib.dgq_linear_a8w4
     _check(fn(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
               M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_linear_a8w4")
+    return out
+
+
+def linear_a8w4_noalloc(xq: torch.Tensor, sx: torch.Tensor, pw: PackedWeight, out: torch.Tensor) -> torch.Tensor:
+    """dgq_linear_a8w4_noalloc: dgq_linear_a8w4 with the library's static scratch; `out` must exist (nothing is
+    allocated here either).  Signed-nibble form only."""
+    _dev(xq, torch.int8, "xq"); _dev(sx, torch.float32, "sx"); _dev(out, torch.float16, "out")
+    M, K = xq.shape
+    if K != pw.K or tuple(out.shape) != (M, pw.N) or pw.zp_form:
+        raise ValueError("shapes or weight form do not match")
+    _check(lib.dgq_linear_a8w4_noalloc(_ptr(xq), _ptr(sx), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out),
+                                       M, pw.N, K, pw.group, _stream()), "dgq_linear_a8w4_noalloc")
     return out
 
 

@@ -1,5 +1,7 @@
 // extern "C" boundary of libdgq.so: argument validation on the host, then one launcher.
 // Every check happens before anything is enqueued.
+#include <atomic>
+#include <mutex>
 #include <cmath>
 #include <cstdio>
 
@@ -8,6 +10,37 @@
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+// Scratch of dgq_linear_a8w4_noalloc: the INT32 partial sums of a K split, for callers that cannot
+// bring a workspace.  Every GPU the library runs on holds its own copy of this array, at its own
+// address, until the process ends.  In host code the NAME below is only a handle for
+// hipGetSymbolAddress; kernels are given the address that call returns for the current device.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];   // device address of `scratch` per GPU, set once
+std::mutex g_scratch_mutex;
+
+hipError_t scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (!p) {
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -337,6 +370,21 @@ dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweigh
                            size_t workspace_bytes, void *stream)
 {
     return linear_fp16(xq, sx, qweight, scales, 0, s1, out, M, N, K, group, workspace, workspace_bytes, stream);
+}
+
+dgq_status dgq_linear_a8w4_noalloc(const int8_t *xq, const float *sx, const void *qweight, const void *scales,
+                                   const float *s1, uint16_t *out, int M, int N, int K, int group, void *stream)
+{
+    if (!xq || !sx || !qweight || !scales || !s1 || !out) return DGQ_ERR_NULL;
+    if (M < 1) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    const size_t need = workspace_needed(pick_path(M, kPathAuto), M, N, K);
+    if (need > kScratchBytes) return DGQ_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (need > 0) {
+        if (dgq_status st = hip_result(scratch_of_current_device(&ws))) return st;
+    }
+    return linear_fp16(xq, sx, qweight, scales, 0, s1, out, M, N, K, group, ws, need, stream);
 }
 
 dgq_status dgq_linear_a8w4_acc(const int8_t *xq, const void *qweight, const void *scales, int32_t *acc_out,

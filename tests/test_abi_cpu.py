@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 33 and len(set(names)) == 33
+    assert len(names) == 34 and len(set(names)) == 34
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -111,6 +111,12 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_rmsnorm_quant_act(good, good, 1, 128, f(-1e-5), good, good, None) == -4
     assert L.dgq_rmsnorm_quant_act(good, None, 1, 128, f(1e-5), good, good, None) == -1
     assert L.dgq_rmsnorm_quant_act(good, good, 1, 24704, f(1e-5), good, good, None) == -2
+    # the entry point that allocates nothing: same checks, and problems beyond its static scratch are refused
+    assert L.dgq_linear_a8w4_noalloc(good, good, good, good, None, good, 1, 16, 128, 128, None) == -1
+    assert L.dgq_linear_a8w4_noalloc(good, good, good, good, good, good, 1, 20, 128, 128, None) == -2
+    assert L.dgq_linear_a8w4_noalloc(good, good, odd, good, good, good, 1, 16, 128, 128, None) == -3
+    assert dgq.linear_workspace_bytes(64, 36864, 131072, 128) > (32 << 20)
+    assert L.dgq_linear_a8w4_noalloc(good, good, good, good, good, good, 64, 36864, 131072, 128, None) == -5
     # quantizer + linear as one call
     n = ctypes.c_size_t(7)
     assert L.dgq_quant_linear_workspace_bytes(4, 4096, 11008, 128, ctypes.byref(n)) == 0 and n.value == 0
