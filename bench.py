@@ -3,11 +3,18 @@
 
 A "step" is one pass of the whole hot path (per-token activation quantization, then the
 fused expand + INT8 GEMM + scale epilogue) over one batch of synthetic input, for every
-(M, layer shape) pair of the chosen workload.  By default each pair is one library call
+(M, layer shape) pair of a workload.  By default each pair is one library call
 (dgq_quant_linear_a8w4), which is a single kernel where the decode kernel can quantize its
-own activations and the two kernels otherwise; --quant separate makes the two calls.  Inputs are resident in HBM before the timed
-region.  Packed weights exist in several copies that the steps rotate through, so that the
-weights of a launch are not left in the 256 MB last-level cache by the previous one.
+own activations and the two kernels otherwise; --quant separate makes the two calls.  Inputs
+are resident in HBM before the timed region.  Packed weights exist in several copies that the
+steps rotate through, so that the weights of a launch are not left in the 256 MB last-level
+cache by the previous one.
+
+The headline (`value`, `ms_per_step`, `roofline`, `cpu_baseline`) is the workload --workload
+names (default: the LLaMA-7B decode linears).  Unless --no-sweep is given, every other
+benchmark configuration (7B prefill, 13B, 65B with both group sizes) is then timed the same
+way with fewer steps and reported under `workloads`, each with one roofline record per regime
+(weight-stream-bound launches against 8 TB/s, matrix-core-bound launches against 5.0 POP/s).
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -15,6 +22,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -25,6 +33,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0        # MI355X dense INT8 MFMA, published
+RIDGE_OPS_PER_BYTE = INT8_PEAK_TOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # 625: below it a launch is bound by HBM
 MALL_BYTES = 256 << 20         # last-level cache; rotate over >= 2x this much weight data
 
 # name -> (model size, list of M, group size)
@@ -35,15 +44,20 @@ WORKLOADS = {
     "llama65b_g128": ("65b", [1, 8, 64, 512, 2048], 128),
     "llama65b_g64": ("65b", [1, 8, 64, 512, 2048], 64),
 }
+SEEDS = {"7b": 1, "13b": 3, "65b": 4}
 
-# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter shows for a 1 GiB copy
-# (FETCH_SIZE reads 0.5 GiB per GiB read: x2.0; WRITE_SIZE x1.0).  Figures and commands are in
-# profiles/; a workload that has not been profiled reports null.
+# HBM bytes per launch of a kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE,
+# KiB per dispatch, mean over the kernel's launches in that workload), each scaled by what the
+# same counter shows for a 1 GiB copy (FETCH_SIZE reads 0.5 GiB per GiB read: x2.0; WRITE_SIZE
+# x1.0).  (workload, kernel) -> (bytes, summary under profiles/ with the figures and commands).
+# A kernel that has not been profiled in a workload reports null.
 TRAFFIC_BYTES = {
-    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"): (2.0 * 14569.5 + 62.5) * 1024,
-    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"): (2.0 * 14182.3 + 175.0) * 1024,
-    ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"): (2.0 * 75912.5 + 34112.0) * 1024,
+    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"):
+        ((2.0 * 14569.5 + 62.5) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"):
+        ((2.0 * 14182.3 + 175.0) * 1024, "profiles/decode_llama7b_linear_decode_kernel.md"),
+    ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"):
+        ((2.0 * 75912.5 + 34112.0) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
 }
 
 
@@ -67,347 +81,385 @@ def algorithmic_bytes(M, K, N, g, in_kernel_quant=False):
     return K * N // 2 + SCALE_BYTES * (K // g) * N + 4 * N + x_bytes + 2 * M * N
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
-    ap.add_argument("--format", default="s4", choices=["s4", "zp"],
-                    help="weight operands: s4 = signed nibbles, S2 <= 15, RTN quantizer (the benchmark configs); "
-                         "zp = unsigned nibbles with per-group zero points, S2 <= 127, two-phase grid search")
-    ap.add_argument("--act", default="dynamic", choices=["dynamic", "static"],
-                    help="activation quantizer: per-token dynamic (the benchmark configs) or one static "
-                         "tensor-wise scale fixed before the timed region (Section 4.1)")
-    ap.add_argument("--quant", default="fused", choices=["fused", "separate"],
-                    help="dynamic quantizer: fused = dgq_quant_linear_a8w4, one call per layer (one kernel where a "
-                         "workgroup of the decode kernel covers all of K, else the two kernels); separate = "
-                         "dgq_quant_act then dgq_linear_a8w4")
-    ap.add_argument("--mlp-block", nargs="?", const="fused", default=None, choices=["fused", "separate"],
-                    help="time the gated MLP as a chain instead of independent layers: RMSNorm + quantizer + gate+up "
-                         "linear (one call; 'separate': dgq_rmsnorm_quant_act then dgq_linear_a8w4), silu*mul fused "
-                         "with the quantizer, down linear")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
-    ap.add_argument("--no-breakdown", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 1 GiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.mlp_block:
-        args.no_cpu_baseline = True      # the oracle leg times independent layers, not this chain
-    if args.act == "static" or args.mlp_block:
-        args.quant = "separate"          # those quantizers are kernels of their own
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (the path is a single-GPU kernel library); "
-                 "--gpus %d is not supported, use --gpus 1" % args.gpus)
+class Bench:
+    """Everything that touches the GPU; one instance per process."""
 
-    import numpy as np
-    import torch
+    def __init__(self, args):
+        import numpy as np
+        import torch
 
-    import paper_2310_04836_amd as dgq
-    import workloads
-
-    global SCALE_BYTES
-    SCALE_BYTES = 2 if args.format == "zp" else 1
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
-    size, Ms, g = WORKLOADS[args.workload]
-    shapes = workloads.LLAMA_SHAPES[size]
-    if args.mlp_block:
-        shapes = {k: shapes[k] for k in ("gate_up", "down")}
-    frac, mult = workloads.OUTLIERS[size]
-    seed = {"7b": 1, "13b": 3, "65b": 4}[size]
+        import paper_2310_04836_amd as dgq
+        import workloads
+        self.np, self.torch, self.dgq, self.wl, self.args = np, torch, dgq, workloads, args
+        assert torch.cuda.is_available(), "bench.py needs a GPU"
+        self.dev = torch.device("cuda:0")
+        self._wcache = {}        # (size, shape, g) -> (packed copy 0, relative quantization error)
+        self._wdev = {}          # (size, shape) -> fp16 weights on the device (shared by the two group sizes)
 
     # ---------------- inputs (untimed) ------------------------------------------------
-    t0 = time.time()
-    layer_bytes = sum(K * N // 2 + (K // g) * N for K, N in shapes.values())
-    ncopies = max(2, -(-2 * MALL_BYTES // layer_bytes))
-    ncopies = -(-ncopies // len(Ms)) * len(Ms)      # a whole number of steps per rotation
-    packed, qerr = {}, {}
-    for name, (K, N) in shapes.items():
-        W = torch.from_numpy(workloads.weights(K, N, seed)).to(dev)
-        if args.format == "zp":
-            w4, zp, s2, s1 = dgq.quantize_weights_grid(W, g)
-            pw, nbad = dgq.pack_weights_zp(w4, s2, zp, s1, g, return_bad=True)
-            assert nbad == 0
-            del zp
-        else:
-            w4, s2, s1 = dgq.quantize_weights_rtn(W, g)
-            pw = dgq.pack_weights(w4, s2, s1, g)
-        # relative error of the quantized weights (context for the quantizer, not a timed quantity)
-        deq = dgq.unpack_weights(pw).float() * s1[None, :]
-        qerr[name] = float(((deq - W.float()) ** 2).sum() / (W.float() ** 2).sum())
-        del deq
-        torch.cuda.synchronize()
-        del W, w4, s2
-        copies = [pw]
-        for _ in range(ncopies - 1):
-            copies.append(dgq.PackedWeight(pw.qweight.clone(), pw.scales.clone(), pw.s1.clone(), K, N, g, pw.zp_form))
-        packed[name] = copies
-    acts, bufs = {}, {}
-    for M in Ms:
+    def _packed(self, size, name, g):
+        torch, dgq, args = self.torch, self.dgq, self.args
+        key = (size, name, g)
+        if key not in self._wcache:
+            K, N = self.wl.LLAMA_SHAPES[size][name]
+            if (size, name) not in self._wdev:
+                self._wdev[(size, name)] = torch.from_numpy(self.wl.weights(K, N, SEEDS[size])).to(self.dev)
+            W = self._wdev[(size, name)]
+            if args.format == "zp":
+                w4, zp, s2, s1 = dgq.quantize_weights_grid(W, g)
+                pw, nbad = dgq.pack_weights_zp(w4, s2, zp, s1, g, return_bad=True)
+                assert nbad == 0
+                del zp
+            else:
+                w4, s2, s1 = dgq.quantize_weights_rtn(W, g)
+                pw = dgq.pack_weights(w4, s2, s1, g)
+            # relative error of the quantized weights (context for the quantizer, not a timed quantity)
+            deq = dgq.unpack_weights(pw).float() * s1[None, :]
+            err = float(((deq - W.float()) ** 2).sum() / (W.float() ** 2).sum())
+            del deq, W, w4, s2
+            torch.cuda.synchronize()
+            self._wcache[key] = (pw, err)
+        return self._wcache[key]
+
+    def drop_weights(self, size):
+        for d in (self._wcache, self._wdev):
+            for k in [k for k in d if k[0] == size]:
+                del d[k]
+        self.torch.cuda.empty_cache()
+
+    def measure(self, workload, steps, warmup, headline):
+        """Times one workload.  Returns the dictionary reported for it."""
+        np, torch, dgq, args, dev = self.np, self.torch, self.dgq, self.args, self.dev
+        size, Ms, g = WORKLOADS[workload]
+        shapes = dict(self.wl.LLAMA_SHAPES[size])
+        if args.mlp_block:
+            shapes = {k: shapes[k] for k in ("gate_up", "down")}
+        frac, mult = self.wl.OUTLIERS[size]
+        seed = SEEDS[size]
+
+        t0 = time.time()
+        layer_bytes = sum(K * N // 2 + (K // g) * N for K, N in shapes.values())
+        ncopies = max(2, -(-2 * MALL_BYTES // layer_bytes))
+        ncopies = -(-ncopies // len(Ms)) * len(Ms)      # a whole number of steps per rotation
+        packed, qerr = {}, {}
         for name, (K, N) in shapes.items():
-            acts[(M, name)] = torch.from_numpy(workloads.activations(M, K, seed + M, frac, mult)).to(dev)
-            wsb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g),
-                      dgq.rmsnorm_quant_linear_workspace_bytes(M, N, K, g))
-            bufs[(M, name)] = (torch.empty((M, K), dtype=torch.int8, device=dev),
-                               torch.empty(M, dtype=torch.float32, device=dev),
-                               torch.empty((M, N), dtype=torch.float16, device=dev),
-                               torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None)
-    torch.cuda.synchronize()
-    log("inputs ready in %.1fs: %s, M=%s, g=%d, %d weight copies of %.1f MB" %
-        (time.time() - t0, size, Ms, g, ncopies, layer_bytes / 1e6))
-
-    static_scale = {k: float(v.float().abs().max().item() / 127.0) for k, v in acts.items()} if args.act == "static" else {}
-
-    # pairs for which the one-call form is a single kernel that quantizes its own activations
-    in_kernel = {(M, name): args.quant == "fused" and dgq.quant_linear_plan(M, N, K, g).startswith("quant_linear")
-                 for M in Ms for name, (K, N) in shapes.items()}
-
-    def one_pair(M, name, copy):
-        xq, sx, out, ws = bufs[(M, name)]
-        if args.quant == "fused":
-            dgq.quant_linear_a8w4(acts[(M, name)], packed[name][copy % ncopies], out, None, ws)
-            return
-        if args.act == "static":
-            dgq.quant_act_static(acts[(M, name)], static_scale[(M, name)], xq, sx)
-        else:
-            dgq.quant_act(acts[(M, name)], xq, sx)
-        dgq.linear_a8w4(xq, sx, packed[name][copy % ncopies], out, ws)
-
-    gamma = torch.ones(shapes["gate_up"][0], dtype=torch.float16, device=dev) if args.mlp_block else None
-
-    def mlp_chain(M, copy):
-        xq, sx, gu, ws = bufs[(M, "gate_up")]
-        if args.mlp_block == "fused":    # RMSNorm, quantizer and gate+up as one call (one kernel for small M)
-            dgq.rmsnorm_quant_linear_a8w4(acts[(M, "gate_up")], gamma, 1e-5, packed["gate_up"][copy % ncopies], gu, None, ws)
-        else:
-            dgq.rmsnorm_quant_act(acts[(M, "gate_up")], gamma, 1e-5, xq, sx)
-            dgq.linear_a8w4(xq, sx, packed["gate_up"][copy % ncopies], gu, ws)
-        hq, hs, out, ws2 = bufs[(M, "down")]
-        dgq.silu_mul_quant_act(gu, hq, hs)
-        dgq.linear_a8w4(hq, hs, packed["down"][copy % ncopies], out, ws2)
-
-    def step_body(i):
-        for mi, M in enumerate(Ms):
-            if args.mlp_block:
-                mlp_chain(M, i * len(Ms) + mi)
-                continue
-            for name in shapes:
-                one_pair(M, name, i * len(Ms) + mi)
-
-    # number of distinct steps before the copy rotation repeats
-    import math
-    period = ncopies // math.gcd(ncopies, len(Ms))
-
-    def make_graph(fn):
-        gr = torch.cuda.CUDAGraph()
-        s = torch.cuda.Stream()
-        s.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(s):
-            fn()                      # warm-up outside capture
-        torch.cuda.current_stream().wait_stream(s)
-        torch.cuda.synchronize()
-        with torch.cuda.graph(gr):
-            fn()
-        return gr
-
-    if args.no_graph:
-        run_step = step_body
-    else:
-        graphs = [make_graph(lambda i=i: step_body(i)) for i in range(period)]
-        run_step = lambda i: graphs[i % period].replay()
-
-    # ---------------- timed region ----------------------------------------------------
-    for i in range(args.warmup):
-        run_step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        run_step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-
-    def pair_bytes(M, name):
-        K, N = shapes[name]
-        if in_kernel[(M, name)]:
-            return algorithmic_bytes(M, K, N, g, True)
-        return algorithmic_bytes(M, K, N, g) + act_quant_bytes(M, K)
-    step_bytes = sum(pair_bytes(M, name) for M in Ms for name in shapes)
-    if args.mlp_block:   # the producer reads gate and up (fp16) and writes int8 + scales; no separate quantizer for down
-        Kd = shapes["down"][0]
-        step_bytes += sum(2 * M * 2 * Kd + M * Kd + 4 * M - act_quant_bytes(M, Kd) for M in Ms)
-    step_ops = sum(2 * M * K * N for M in Ms for K, N in shapes.values())
-    value = step_bytes / (elapsed / args.steps) / 1e9
-    log("step: %.3f ms, %.1f GB/s algorithmic, %.2f TOP/s" % (ms_per_step, value, step_ops / (elapsed / args.steps) / 1e12))
-
-    # ---------------- dominant kernel, HIP events on the launch stream -----------------
-    def time_linear(M, name, reps):
-        """Average duration of the linear kernel alone for (M, shape), weights rotating."""
-        xq, sx, out, ws = bufs[(M, name)]
-        launches = ncopies
-
-        def body():
-            for c in range(launches):
-                if in_kernel[(M, name)]:
-                    dgq.quant_linear_a8w4(acts[(M, name)], packed[name][c], out, None, ws)
-                else:
-                    dgq.linear_a8w4(xq, sx, packed[name][c], out, ws)
-        if args.no_graph:
-            run = body
-        else:
-            gr = make_graph(body)
-            run = gr.replay
-        run()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            run()
-        e1.record()
-        torch.cuda.synchronize()
-        return 1e-3 * e0.elapsed_time(e1) / (reps * launches)   # seconds per launch
-
-    # Every (M, shape) pair alone, same number of launches each, then grouped by the kernel
-    # symbol the library picks: the dominant kernel is the symbol with the largest share of
-    # the step.  Its figures are means over its launches, which is also what a profiler's
-    # per-kernel average over this run shows.
-    reps_pair = 20 if max(Ms) <= 64 else 5
-    pair_sec, groups = {}, {}
-    for M in Ms:
-        for name, (K, N) in shapes.items():
-            pair_sec[(M, name)] = time_linear(M, name, reps_pair)
-            sym = dgq.quant_linear_plan(M, N, K, g) if in_kernel[(M, name)] else dgq.linear_plan(M, N, K, g)
-            if args.format == "zp":      # same plan, the kernels of the zero-point form
-                sym = sym.replace("_kernel<", "_zp_kernel<")
-            groups.setdefault(sym, []).append((M, name))
-    kernel_name = max(groups, key=lambda k: sum(pair_sec[p] for p in groups[k]))
-    dpairs = groups[kernel_name]
-    dsec = sum(pair_sec[p] for p in dpairs) / len(dpairs)
-    dbytes = sum(algorithmic_bytes(M, *shapes[name], g, in_kernel[(M, name)]) for M, name in dpairs) / len(dpairs)
-    dops = sum(2 * M * shapes[name][0] * shapes[name][1] for M, name in dpairs) / len(dpairs)
-    hbm_bound = "linear_tiled" not in kernel_name
-    if hbm_bound:
-        roofline = {"bound": "hbm", "achieved": dbytes / dsec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        roofline = {"bound": "mfma", "achieved": dops / dsec / 1e12, "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
-    roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = TRAFFIC_BYTES.get((args.workload, kernel_name))
-    roofline.update({"kernel": kernel_name,
-                     "launches": ["%s M=%d" % (name, M) for M, name in dpairs],
-                     "avg_us": dsec * 1e6, "algorithmic_bytes_per_launch": dbytes, "ops_per_launch": dops,
-                     "share_of_linear_time": sum(pair_sec[p] for p in dpairs) / sum(pair_sec.values())})
-    log("dominant kernel %s over %d (M, shape) pairs: avg %.2f us, %.1f %s (%.1f%% of peak)" %
-        (kernel_name, len(dpairs), dsec * 1e6, roofline["achieved"], roofline["unit"], 100 * roofline["frac"]))
-
-    # ---------------- per (shape, M) table + fp16 GEMM (A16) baseline -------------------
-    breakdown = []
-    a16_ms = 0.0
-    if not args.no_breakdown:
+            pw, qerr[name] = self._packed(size, name, g)
+            copies = [pw]
+            for _ in range(ncopies - 1):
+                copies.append(dgq.PackedWeight(pw.qweight.clone(), pw.scales.clone(), pw.s1.clone(), K, N, g, pw.zp_form))
+            packed[name] = copies
+        acts, bufs = {}, {}
         for M in Ms:
             for name, (K, N) in shapes.items():
-                sec = pair_sec[(M, name)]
-                xh = acts[(M, name)]
-                wh = torch.empty((K, N), dtype=torch.float16, device=dev).normal_(0, 0.02)
-                torch.matmul(xh, wh)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                reps = 5 if M > 64 else 20
-                e0.record()
-                for _ in range(reps):
-                    torch.matmul(xh, wh)
-                e1.record()
-                torch.cuda.synchronize()
-                fsec = 1e-3 * e0.elapsed_time(e1) / reps
-                del wh
-                a16_ms += fsec * 1e3
-                b = algorithmic_bytes(M, K, N, g, in_kernel[(M, name)])
-                row = {"shape": name, "quantizes_in_kernel": in_kernel[(M, name)], "M": M, "K": K, "N": N, "us": round(sec * 1e6, 2),
-                       "GBps": round(b / sec / 1e9, 1), "hbm_frac": round(b / sec / 1e9 / HBM_PEAK_GBS, 4),
-                       "TOPS": round(2 * M * K * N / sec / 1e12, 2),
-                       "mfma_frac": round(2 * M * K * N / sec / 1e12 / INT8_PEAK_TOPS, 4),
-                       "fp16_gemm_us": round(fsec * 1e6, 2), "speedup_vs_fp16_gemm": round(fsec / sec, 2)}
-                breakdown.append(row)
-                log("  %-8s M=%-5d %9.2f us  %7.1f GB/s (%5.1f%% HBM)  %8.2f TOP/s (%5.1f%% MFMA)  fp16 GEMM %9.2f us  x%.2f" %
-                    (name, M, row["us"], row["GBps"], 100 * row["hbm_frac"], row["TOPS"], 100 * row["mfma_frac"],
-                     row["fp16_gemm_us"], row["speedup_vs_fp16_gemm"]))
+                acts[(M, name)] = torch.from_numpy(self.wl.activations(M, K, seed + M, frac, mult)).to(dev)
+                wsb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g),
+                          dgq.rmsnorm_quant_linear_workspace_bytes(M, N, K, g))
+                bufs[(M, name)] = (torch.empty((M, K), dtype=torch.int8, device=dev),
+                                   torch.empty(M, dtype=torch.float32, device=dev),
+                                   torch.empty((M, N), dtype=torch.float16, device=dev),
+                                   torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None)
+        torch.cuda.synchronize()
+        log("[%s] inputs ready in %.1fs: %s, M=%s, g=%d, %d weight copies of %.1f MB" %
+            (workload, time.time() - t0, size, Ms, g, ncopies, layer_bytes / 1e6))
 
-    # ---------------- measured achievable read bandwidth (plain streaming read) -----------
-    probe = None
-    try:
-        big = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
-        big.zero_()
-        probe = {}
-        for label, nbytes in (("1GiB", 1 << 30), ("dominant_launch", (int(dbytes) // 16) * 16)):
-            ncp = max(1, (1 << 30) // nbytes)
-            reps = 3 if nbytes > (256 << 20) else 10
+        static_scale = ({k: float(v.float().abs().max().item() / 127.0) for k, v in acts.items()}
+                        if args.act == "static" else {})
+        # pairs for which the one-call form is a single kernel that quantizes its own activations
+        in_kernel = {(M, name): args.quant == "fused" and dgq.quant_linear_plan(M, N, K, g).startswith("quant_linear")
+                     for M in Ms for name, (K, N) in shapes.items()}
 
-            def body(nbytes=nbytes, ncp=ncp):
-                for c in range(ncp):
-                    dgq.lib.dgq_probe_read(big.data_ptr() + c * ((nbytes + 255) // 256 * 256) % ((1 << 30) - nbytes + 1) // 256 * 256,
-                                           nbytes, sink.data_ptr(), 256, torch.cuda.current_stream().cuda_stream)
-            gr = make_graph(body)
-            gr.replay()
+        def one_pair(M, name, copy):
+            xq, sx, out, ws = bufs[(M, name)]
+            if args.quant == "fused":
+                dgq.quant_linear_a8w4(acts[(M, name)], packed[name][copy % ncopies], out, None, ws)
+                return
+            if args.act == "static":
+                dgq.quant_act_static(acts[(M, name)], static_scale[(M, name)], xq, sx)
+            else:
+                dgq.quant_act(acts[(M, name)], xq, sx)
+            dgq.linear_a8w4(xq, sx, packed[name][copy % ncopies], out, ws)
+
+        gamma = torch.ones(shapes["gate_up"][0], dtype=torch.float16, device=dev) if args.mlp_block else None
+
+        def mlp_chain(M, copy):
+            xq, sx, gu, ws = bufs[(M, "gate_up")]
+            if args.mlp_block == "fused":    # RMSNorm, quantizer and gate+up as one call (one kernel for small M)
+                dgq.rmsnorm_quant_linear_a8w4(acts[(M, "gate_up")], gamma, 1e-5, packed["gate_up"][copy % ncopies], gu, None, ws)
+            else:
+                dgq.rmsnorm_quant_act(acts[(M, "gate_up")], gamma, 1e-5, xq, sx)
+                dgq.linear_a8w4(xq, sx, packed["gate_up"][copy % ncopies], gu, ws)
+            hq, hs, out, ws2 = bufs[(M, "down")]
+            dgq.silu_mul_quant_act(gu, hq, hs)
+            dgq.linear_a8w4(hq, hs, packed["down"][copy % ncopies], out, ws2)
+
+        def step_body(i):
+            for mi, M in enumerate(Ms):
+                if args.mlp_block:
+                    mlp_chain(M, i * len(Ms) + mi)
+                    continue
+                for name in shapes:
+                    one_pair(M, name, i * len(Ms) + mi)
+
+        # number of distinct steps before the copy rotation repeats
+        period = ncopies // math.gcd(ncopies, len(Ms))
+
+        def make_graph(fn):
+            gr = torch.cuda.CUDAGraph()
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                fn()                      # warm-up outside capture
+            torch.cuda.current_stream().wait_stream(s)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(gr):
+                fn()
+            return gr
+        self.make_graph = make_graph
+
+        if args.no_graph:
+            run_step = step_body
+        else:
+            graphs = [make_graph(lambda i=i: step_body(i)) for i in range(period)]
+            run_step = lambda i: graphs[i % period].replay()
+
+        # ---------------- timed region ----------------------------------------------------
+        for i in range(warmup):
+            run_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            run_step(i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ms_per_step = 1e3 * elapsed / steps
+
+        def pair_bytes(M, name):
+            K, N = shapes[name]
+            if in_kernel[(M, name)]:
+                return algorithmic_bytes(M, K, N, g, True)
+            return algorithmic_bytes(M, K, N, g) + act_quant_bytes(M, K)
+        step_bytes = sum(pair_bytes(M, name) for M in Ms for name in shapes)
+        if args.mlp_block:   # the producer reads gate and up (fp16) and writes int8 + scales; no separate quantizer for down
+            Kd = shapes["down"][0]
+            step_bytes += sum(2 * M * 2 * Kd + M * Kd + 4 * M - act_quant_bytes(M, Kd) for M in Ms)
+        step_ops = sum(2 * M * K * N for M in Ms for K, N in shapes.values())
+        value = step_bytes / (elapsed / steps) / 1e9
+        tops = step_ops / (elapsed / steps) / 1e12
+        log("[%s] step: %.3f ms, %.1f GB/s algorithmic, %.2f TOP/s" % (workload, ms_per_step, value, tops))
+
+        # ---------------- every (M, shape) pair alone, HIP events on the launch stream --------
+        def time_linear(M, name, reps):
+            """Average duration of the linear kernel alone for (M, shape), weights rotating."""
+            xq, sx, out, ws = bufs[(M, name)]
+            if not in_kernel[(M, name)]:
+                dgq.quant_act(acts[(M, name)], xq, sx)
+
+            def body():
+                for c in range(ncopies):
+                    if in_kernel[(M, name)]:
+                        dgq.quant_linear_a8w4(acts[(M, name)], packed[name][c], out, None, ws)
+                    else:
+                        dgq.linear_a8w4(xq, sx, packed[name][c], out, ws)
+            run = body if args.no_graph else make_graph(body).replay
+            run()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(reps):
-                gr.replay()
+                run()
             e1.record()
             torch.cuda.synchronize()
-            sec = 1e-3 * e0.elapsed_time(e1) / (reps * ncp)
-            probe[label] = {"bytes": nbytes, "us": sec * 1e6, "GBps": nbytes / sec / 1e9}
-            log("plain streaming read of %s (%d bytes): %.2f us, %.1f GB/s" % (label, nbytes, sec * 1e6, nbytes / sec / 1e9))
-        del big
-    except Exception as e:  # measurement aid only
-        log("probe_read failed: %r" % (e,))
+            return 1e-3 * e0.elapsed_time(e1) / (reps * ncopies)   # seconds per launch
+
+        pair_sec, pair_sym = {}, {}
+        for M in Ms:
+            for name, (K, N) in shapes.items():
+                pair_sec[(M, name)] = time_linear(M, name, 20 if M <= 64 else 5)
+                sym = dgq.quant_linear_plan(M, N, K, g) if in_kernel[(M, name)] else dgq.linear_plan(M, N, K, g)
+                if args.format == "zp":      # same plan, the kernels of the zero-point form
+                    sym = sym.replace("_kernel<", "_zp_kernel<")
+                pair_sym[(M, name)] = sym
+
+        def pair_b(p):
+            return algorithmic_bytes(p[0], *shapes[p[1]], g, in_kernel[p])
+
+        def pair_o(p):
+            return 2 * p[0] * shapes[p[1]][0] * shapes[p[1]][1]
+
+        def bound_of(p):
+            """What bounds a launch: its arithmetic intensity against the ridge of the two peaks."""
+            return "hbm" if pair_o(p) / pair_b(p) < RIDGE_OPS_PER_BYTE else "mfma"
+
+        def roofline_of(pairs, bound):
+            """Record for the kernel symbol with the largest share of time among `pairs`: means over
+            its launches, which is what a profiler's per-kernel average over this run shows."""
+            groups = {}
+            for p in pairs:
+                groups.setdefault(pair_sym[p], []).append(p)
+            kernel = max(groups, key=lambda k: sum(pair_sec[p] for p in groups[k]))
+            ps = groups[kernel]
+            sec = sum(pair_sec[p] for p in ps) / len(ps)
+            nbytes = sum(pair_b(p) for p in ps) / len(ps)
+            nops = sum(pair_o(p) for p in ps) / len(ps)
+            if bound == "hbm":
+                r = {"bound": "hbm", "achieved": nbytes / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+            else:
+                r = {"bound": "mfma", "achieved": nops / sec / 1e12, "peak": INT8_PEAK_TOPS, "unit": "TOP/s"}
+            r["frac"] = r["achieved"] / r["peak"]
+            traffic = TRAFFIC_BYTES.get((workload, kernel))
+            r["traffic"] = traffic[0] if traffic else None
+            r["traffic_source"] = traffic[1] if traffic else None
+            r.update({"kernel": kernel, "launches": ["%s M=%d" % (name, M) for M, name in ps],
+                      "avg_us": sec * 1e6, "algorithmic_bytes_per_launch": nbytes, "ops_per_launch": nops,
+                      "share_of_linear_time": sum(pair_sec[p] for p in ps) / sum(pair_sec.values())})
+            return r
+
+        all_pairs = list(pair_sec)
+        # the kernel with the largest share of the whole workload, priced against the roofline that
+        # bounds most of its time
+        groups = {}
+        for p in all_pairs:
+            groups.setdefault(pair_sym[p], []).append(p)
+        top = max(groups, key=lambda k: sum(pair_sec[p] for p in groups[k]))
+        t_hbm = sum(pair_sec[p] for p in groups[top] if bound_of(p) == "hbm")
+        top_bound = "hbm" if 2 * t_hbm >= sum(pair_sec[p] for p in groups[top]) else "mfma"
+        roofline = roofline_of(groups[top], top_bound)
+        regimes = {}
+        for b, label in (("hbm", "weight_stream_bound"), ("mfma", "matrix_core_bound")):
+            ps = [p for p in all_pairs if bound_of(p) == b]
+            if ps:
+                regimes[label] = roofline_of(ps, b)
+                log("[%s] %s: %s over %d pair(s): avg %.2f us, %.1f %s (%.1f%% of peak)" %
+                    (workload, label, regimes[label]["kernel"], len(regimes[label]["launches"]), regimes[label]["avg_us"],
+                     regimes[label]["achieved"], regimes[label]["unit"], 100 * regimes[label]["frac"]))
+
+        # ---------------- per (shape, M) table + fp16 GEMM (A16) baseline -------------------
+        breakdown = []
+        a16_ms = 0.0
+        if not args.no_breakdown:
+            for M in Ms:
+                for name, (K, N) in shapes.items():
+                    sec = pair_sec[(M, name)]
+                    xh = acts[(M, name)]
+                    wh = torch.empty((K, N), dtype=torch.float16, device=dev).normal_(0, 0.02)
+                    torch.matmul(xh, wh)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    reps = 5 if M > 64 else 20
+                    e0.record()
+                    for _ in range(reps):
+                        torch.matmul(xh, wh)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    fsec = 1e-3 * e0.elapsed_time(e1) / reps
+                    del wh
+                    a16_ms += fsec * 1e3
+                    b = pair_b((M, name))
+                    row = {"shape": name, "kernel": pair_sym[(M, name)], "bound": bound_of((M, name)),
+                           "quantizes_in_kernel": in_kernel[(M, name)], "M": M, "K": K, "N": N, "us": round(sec * 1e6, 2),
+                           "GBps": round(b / sec / 1e9, 1), "hbm_frac": round(b / sec / 1e9 / HBM_PEAK_GBS, 4),
+                           "TOPS": round(2 * M * K * N / sec / 1e12, 2),
+                           "mfma_frac": round(2 * M * K * N / sec / 1e12 / INT8_PEAK_TOPS, 4),
+                           "fp16_gemm_us": round(fsec * 1e6, 2), "speedup_vs_fp16_gemm": round(fsec / sec, 2)}
+                    breakdown.append(row)
+                    log("  %-8s M=%-5d %9.2f us  %7.1f GB/s (%5.1f%% HBM)  %8.2f TOP/s (%5.1f%% MFMA)  fp16 GEMM %9.2f us  x%.2f" %
+                        (name, M, row["us"], row["GBps"], 100 * row["hbm_frac"], row["TOPS"], 100 * row["mfma_frac"],
+                         row["fp16_gemm_us"], row["speedup_vs_fp16_gemm"]))
+
+        res = {
+            "workload": workload, "value": value, "unit": "GB/s", "ms_per_step": ms_per_step, "steps": steps,
+            "warmup": warmup, "tops": tops,
+            "config": {"workload": workload, "layer_shapes": "llama-" + size, "M": Ms, "group": g,
+                       "layers_per_step": list(shapes), "weight_copies": ncopies,
+                       "activation_quantizer": args.act, "mlp_block": args.mlp_block or False,
+                       "quantizer_call": ("one call with the linear (dgq_quant_linear_a8w4); in-kernel for %d of %d launches"
+                                          % (sum(in_kernel.values()), len(in_kernel))) if args.quant == "fused"
+                                         else "separate kernel before each linear",
+                       "weight_format": ("unsigned nibbles, per-group zero points, S2 <= 127, two-phase grid search"
+                                         if args.format == "zp" else "signed nibbles, S2 <= 15, RTN"),
+                       "launch": "eager" if args.no_graph else "hip_graph"},
+            "roofline": roofline, "regimes": regimes,
+            "a16_fp16_gemm_ms_per_step": a16_ms if breakdown else None,
+            "weight_quantization_rel_sq_error": qerr, "breakdown": breakdown,
+        }
+        if headline:
+            res["measured_read_bandwidth"] = self.probe_read(roofline["algorithmic_bytes_per_launch"])
+            res["measured_mfma_rate"] = self.probe_mfma(bufs[(max(Ms), list(shapes)[0])][0], packed[list(shapes)[0]][0])
+            res["cpu_baseline"] = None if args.no_cpu_baseline else self.cpu_baseline(workload, acts, static_scale)
+        return res
+
+    # ---------------- measured achievable read bandwidth (plain streaming read) -----------
+    def probe_read(self, dbytes):
+        torch, dgq = self.torch, self.dgq
+        try:
+            big = torch.empty(1 << 30, dtype=torch.uint8, device=self.dev)
+            sink = torch.zeros(4096, dtype=torch.int32, device=self.dev)
+            big.zero_()
+            probe = {}
+            for label, nbytes in (("1GiB", 1 << 30), ("dominant_launch", (int(dbytes) // 16) * 16)):
+                ncp = max(1, (1 << 30) // nbytes)
+                reps = 3 if nbytes > (256 << 20) else 10
+
+                def body(nbytes=nbytes, ncp=ncp):
+                    for c in range(ncp):
+                        dgq.lib.dgq_probe_read(big.data_ptr() + c * ((nbytes + 255) // 256 * 256) % ((1 << 30) - nbytes + 1) // 256 * 256,
+                                               nbytes, sink.data_ptr(), 256, torch.cuda.current_stream().cuda_stream)
+                gr = self.make_graph(body)
+                gr.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    gr.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                sec = 1e-3 * e0.elapsed_time(e1) / (reps * ncp)
+                probe[label] = {"bytes": nbytes, "us": sec * 1e6, "GBps": nbytes / sec / 1e9}
+                log("plain streaming read of %s (%d bytes): %.2f us, %.1f GB/s" % (label, nbytes, sec * 1e6, nbytes / sec / 1e9))
+            del big
+            return probe
+        except Exception as e:  # measurement aid only
+            log("probe_read failed: %r" % (e,))
+            return None
 
     # ---------------- measured matrix-core rate on this workload's operand data ------------
-    mfma_probe = None
-    try:
-        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
-        M0 = max(Ms)
-        name0 = list(shapes)[0]
-        K0, N0 = shapes[name0]
-        xq0 = bufs[(M0, name0)][0]                           # X_s8 as the timed steps left it
-        w_s8 = dgq.unpack_weights(packed[name0][0])          # W_s8 of Eq. 2, the B operand's data
-        nrec = 1 << 19                                       # 96-byte records: 64 B of X_s8, 32 B of W_s8
-        xa = xq0.reshape(-1).view(torch.uint8)
-        xa = xa.repeat(-(-nrec * 64 // xa.numel()))[: nrec * 64].view(nrec, 64)
-        wb = w_s8.reshape(-1).view(torch.uint8)[: nrec * 32].view(nrec, 32)
-        real = torch.cat([xa, wb], dim=1).contiguous()
-        mfma_probe = {}
-        for label, buf in (("zero_operands", torch.zeros(1 << 20, dtype=torch.uint8, device=dev)),
-                           ("workload_operands", real)):
-            iters = 20000
-            ops = dgq.probe_mfma(buf, iters, sink)            # warm-up
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(3):
-                dgq.probe_mfma(buf, iters, sink)
-            e1.record()
-            torch.cuda.synchronize()
-            sec = 1e-3 * e0.elapsed_time(e1) / 3
-            mfma_probe[label] = {"TOPS": ops / sec / 1e12, "ms": sec * 1e3}
-            log("MFMA-only loop, %s: %.1f TOP/s" % (label, ops / sec / 1e12))
-        del real, w_s8, xa, wb
-    except Exception as e:  # measurement aid only
-        log("probe_mfma failed: %r" % (e,))
-
-    if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        log("calibration copy of %d bytes done" % src.numel())
+    def probe_mfma(self, xq0, pw0):
+        torch, dgq = self.torch, self.dgq
+        try:
+            sink = torch.zeros(4096, dtype=torch.int32, device=self.dev)
+            w_s8 = dgq.unpack_weights(pw0)                       # W_s8 of Eq. 2, the B operand's data
+            nrec = 1 << 19                                       # 96-byte records: 64 B of X_s8, 32 B of W_s8
+            xa = xq0.reshape(-1).view(torch.uint8)               # X_s8 as the timed steps left it
+            xa = xa.repeat(-(-nrec * 64 // xa.numel()))[: nrec * 64].view(nrec, 64)
+            wb = w_s8.reshape(-1).view(torch.uint8)[: nrec * 32].view(nrec, 32)
+            real = torch.cat([xa, wb], dim=1).contiguous()
+            out = {}
+            for label, buf in (("zero_operands", torch.zeros(1 << 20, dtype=torch.uint8, device=self.dev)),
+                               ("workload_operands", real)):
+                iters = 20000
+                ops = dgq.probe_mfma(buf, iters, sink)            # warm-up
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(3):
+                    dgq.probe_mfma(buf, iters, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                sec = 1e-3 * e0.elapsed_time(e1) / 3
+                out[label] = {"TOPS": ops / sec / 1e12, "ms": sec * 1e3}
+                log("MFMA-only loop, %s: %.1f TOP/s" % (label, ops / sec / 1e12))
+            return out
+        except Exception as e:  # measurement aid only
+            log("probe_mfma failed: %r" % (e,))
+            return None
 
     # ---------------- CPU baseline: the oracle on the same workload ---------------------
-    cpu = None
-    if not args.no_cpu_baseline:
+    def cpu_baseline(self, workload, acts, static_scale):
         import oracle
+        args = self.args
+        size, Ms, g = WORKLOADS[workload]
+        shapes = self.wl.LLAMA_SHAPES[size]
+        seed = SEEDS[size]
         qcache = {}
         t_cpu, n_steps, done_bytes = 0.0, 0, 0
         while t_cpu < 10.0 and n_steps < 400:
@@ -420,7 +472,7 @@ def main():
                     if args.format == "zp":
                         ncol = min(ncol, 512)      # the oracle's (untimed) grid search is slow
                     if (name, ncol) not in qcache:
-                        Wn = workloads.weights(K, N, seed)[:, :ncol]
+                        Wn = self.wl.weights(K, N, seed)[:, :ncol]
                         qcache[(name, ncol)] = (oracle.quantize_weights_grid(Wn, g) if args.format == "zp"
                                                 else oracle.quantize_weights_rtn(Wn, g))
                     x = acts[(M, name)].cpu().numpy()
@@ -445,30 +497,93 @@ def main():
                          (n_steps, "" if (max(Ms) <= 64 and args.format != "zp") else
                           " (output channels of large layers cut to a contiguous slice)", t_cpu)}
         log("cpu oracle: %.3f GB/s on %d threads" % (cpu["value"], cpu["cores"]))
+        return cpu
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS),
+                    help="the workload of the headline figures")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="time the headline workload only (default: every other benchmark configuration too, "
+                         "reported under 'workloads')")
+    ap.add_argument("--sweep-steps", type=int, default=10, help="timed steps of each non-headline workload")
+    ap.add_argument("--format", default="s4", choices=["s4", "zp"],
+                    help="weight operands: s4 = signed nibbles, S2 <= 15, RTN quantizer (the benchmark configs); "
+                         "zp = unsigned nibbles with per-group zero points, S2 <= 127, two-phase grid search")
+    ap.add_argument("--act", default="dynamic", choices=["dynamic", "static"],
+                    help="activation quantizer: per-token dynamic (the benchmark configs) or one static "
+                         "tensor-wise scale fixed before the timed region (Section 4.1)")
+    ap.add_argument("--quant", default="fused", choices=["fused", "separate"],
+                    help="dynamic quantizer: fused = dgq_quant_linear_a8w4, one call per layer (one kernel where a "
+                         "workgroup of the decode kernel covers all of K, else the two kernels); separate = "
+                         "dgq_quant_act then dgq_linear_a8w4")
+    ap.add_argument("--mlp-block", nargs="?", const="fused", default=None, choices=["fused", "separate"],
+                    help="time the gated MLP as a chain instead of independent layers: RMSNorm + quantizer + gate+up "
+                         "linear (one call; 'separate': dgq_rmsnorm_quant_act then dgq_linear_a8w4), silu*mul fused "
+                         "with the quantizer, down linear")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.mlp_block:
+        args.no_cpu_baseline = True      # the oracle leg times independent layers, not this chain
+        args.no_sweep = True
+    if args.act == "static" or args.mlp_block:
+        args.quant = "separate"          # those quantizers are kernels of their own
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the path is a single-GPU kernel library); "
+                 "--gpus %d is not supported, use --gpus 1" % args.gpus)
+
+    global SCALE_BYTES
+    SCALE_BYTES = 2 if args.format == "zp" else 1
+    bench = Bench(args)
+    head = bench.measure(args.workload, args.steps, args.warmup, headline=True)
+
+    if args.calibrate_copy:
+        torch = bench.torch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=bench.dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("calibration copy of %d bytes done" % src.numel())
+        del src, dst
+
+    sweep = []
+    if not args.no_sweep:
+        # the other benchmark configurations, largest model last; weights of a model that is done are freed
+        order = [w for w in ("llama7b_decode", "llama7b_prefill", "llama13b", "llama65b_g128", "llama65b_g64")
+                 if w != args.workload]
+        for i, w in enumerate(order):
+            r = bench.measure(w, args.sweep_steps, 2, headline=False)
+            sweep.append(r)
+            size = WORKLOADS[w][0]
+            if all(WORKLOADS[o][0] != size for o in order[i + 1:]):
+                bench.drop_weights(size)
 
     result = {
         "metric": "A8W4 linear TOPS and weight GB/s (% of roofline) at M=1..2048, LLaMA shapes",
-        "value": value, "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "value": head["value"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": args.workload, "model_shapes": "llama-" + size, "M": Ms, "group": g,
-                   "layers_per_step": list(shapes), "weight_copies": ncopies,
-                   "activation_quantizer": args.act, "mlp_block": args.mlp_block or False,
-                   "quantizer_call": ("one call with the linear (dgq_quant_linear_a8w4); in-kernel for %d of %d launches"
-                                      % (sum(in_kernel.values()), len(in_kernel))) if args.quant == "fused"
-                                     else "separate kernel before each linear",
-                   "weight_format": ("unsigned nibbles, per-group zero points, S2 <= 127, two-phase grid search"
-                                     if args.format == "zp" else "signed nibbles, S2 <= 15, RTN"),
-                   "launch": "eager" if args.no_graph else "hip_graph"},
-        "tops": step_ops / (elapsed / args.steps) / 1e12,
-        "roofline": roofline,
-        "cpu_baseline": cpu,
-        "a16_fp16_gemm_ms_per_step": a16_ms if breakdown else None,
-        "weight_quantization_rel_sq_error": qerr,
-        "measured_read_bandwidth": probe,
-        "measured_mfma_rate": mfma_probe,
-        "breakdown": breakdown,
+        "config": head["config"],
+        "tops": head["tops"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head.get("cpu_baseline"),
+        "regimes": head["regimes"],
+        "workloads": [{k: r[k] for k in ("workload", "value", "unit", "ms_per_step", "steps", "warmup", "tops", "config",
+                                         "roofline", "regimes", "a16_fp16_gemm_ms_per_step", "breakdown")} for r in sweep],
+        "a16_fp16_gemm_ms_per_step": head["a16_fp16_gemm_ms_per_step"],
+        "weight_quantization_rel_sq_error": head["weight_quantization_rel_sq_error"],
+        "measured_read_bandwidth": head.get("measured_read_bandwidth"),
+        "measured_mfma_rate": head.get("measured_mfma_rate"),
+        "breakdown": head["breakdown"],
         "paper_context": "paper reports 3.24x vs A16W4 and 1.12x memory, end to end on one A100-80G (abstract, Section 4.3)",
     }
     print(json.dumps(result), flush=True)
