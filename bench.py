@@ -157,7 +157,7 @@ class Bench:
                 bufs[(M, name)] = (torch.empty((M, K), dtype=torch.int8, device=dev),
                                    torch.empty(M, dtype=torch.float32, device=dev),
                                    torch.empty((M, N), dtype=torch.float16, device=dev),
-                                   torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None)
+                                   torch.zeros(wsb, dtype=torch.uint8, device=dev) if wsb else None)
         torch.cuda.synchronize()
         log("[%s] inputs ready in %.1fs: %s, M=%s, g=%d, %d weight copies of %.1f MB" %
             (workload, time.time() - t0, size, Ms, g, ncopies, layer_bytes / 1e6))

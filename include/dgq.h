@@ -75,10 +75,21 @@ DGQ_API dgq_status dgq_packed_sizes(int K, int N, int group, size_t *qweight_byt
 
 /*
  * Scratch needed by dgq_linear_a8w4 for this problem (host function).  May be 0, in which
- * case `workspace` may be NULL.  Non-zero where several workgroups split K and exchange
- * INT32 partial sums: M <= 16 with very long K, and larger M for shapes with few tiles
- * (at most 8 * M * N * 4 bytes).  dgq_linear_acc_workspace_bytes is the same for the test
- * hooks dgq_linear_a8w4_acc / _zp_acc, which can force a kernel path (see there).
+ * case `workspace` may be NULL.  Non-zero where several workgroups split the K of a tile:
+ * M <= 16 with very long K, and larger M for shapes with few tiles.  It then holds 64 KiB of
+ * arrival counters (one per tile) followed by the INT32 partial sums of every part (about
+ * parts * M * N * 4 bytes, M and N rounded up to whole tiles, parts <= 8).
+ *
+ * WORKSPACE CONTRACT (every call that takes a workspace): the buffer must be ZERO-FILLED
+ * once before its first use (hipMemset after allocating it).  The counters always sit in the
+ * first 64 KiB, whatever the shape and the entry point, and a call leaves them zero again, so
+ * the same buffer serves any sequence of calls it is large enough for without being cleared
+ * in between; the rest of its contents is undefined before and after.  Two calls that may overlap in time must not share a workspace.  (A call that is
+ * torn down while its kernels run, e.g. by a device reset, may leave counters behind: clear
+ * the buffer again.)
+ *
+ * dgq_linear_acc_workspace_bytes is the same for the test hooks dgq_linear_a8w4_acc /
+ * _zp_acc, which can force a kernel path (see there).
  */
 DGQ_API dgq_status dgq_linear_workspace_bytes(int M, int N, int K, int group, size_t *bytes);
 DGQ_API dgq_status dgq_linear_acc_workspace_bytes(int M, int N, int K, int group, int path, size_t *bytes);
@@ -196,11 +207,12 @@ DGQ_API dgq_status dgq_quant_act_static(const uint16_t *x, int M, int K, float s
  *   qweight, scales   in  as written by dgq_pack_weights for the same K, N, group
  *   s1                in  [N] float
  *   out               out [M][N] fp16 (raw bits)
- *   workspace         scratch of at least dgq_linear_workspace_bytes(); contents
- *                     undefined before and after
- * M <= 16 takes a weight-streaming split-K kernel, larger M a tiled MFMA kernel (64-token
- * tiles, with K split over workgroups where that is faster, up to M = 64 and for shapes with
- * few tiles; 128-token tiles otherwise); all give the same INT32 sums.
+ *   workspace         scratch of at least dgq_linear_workspace_bytes(), zero-filled before
+ *                     its first use (see the workspace contract above)
+ * M <= 16 takes a weight-streaming split-K kernel, larger M a tiled MFMA kernel (64- or
+ * 128-token tiles; K split over several workgroups per tile where the tiles alone would
+ * leave compute units idle, the last workgroup to finish a tile adding up the parts); all
+ * give the same INT32 sums.
  */
 DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void *qweight,
                            const void *scales, const float *s1, uint16_t *out,
@@ -212,14 +224,14 @@ DGQ_API dgq_status dgq_linear_a8w4(const int8_t *xq, const float *sx, const void
  * code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments without the workspace, same kernels, same bits.  Where the problem needs scratch (the
  * INT32 partial sums of a K split, dgq_linear_workspace_bytes() > 0) it lives in a static device
- * array of 32 MiB inside the library, which every GPU the library has run on holds until the
+ * array of 40 MiB inside the library, which every GPU the library has run on holds until the
  * process ends; a problem that needs more returns DGQ_ERR_WORKSPACE (nothing is launched).  The
  * call makes no hipMalloc / hipFree and no allocating library call.  The first call on a device
  * looks up that device's address of the array (hipGetSymbolAddress with the device current, as
  * for any launch); make that first call outside graph capture.  All calls on one GPU share the
  * array: calls that need scratch and may overlap on one GPU (different streams, or graph
- * branches) race and must be ordered by the caller.  Nothing in the array has to start at zero
- * (every partial sum is written before it is read).
+ * branches) race and must be ordered by the caller.  The array starts out zero-filled and every
+ * call leaves its arrival counters zero again, which is all the workspace contract asks for.
  */
 DGQ_API dgq_status dgq_linear_a8w4_noalloc(const int8_t *xq, const float *sx, const void *qweight,
                                    const void *scales, const float *s1, uint16_t *out,

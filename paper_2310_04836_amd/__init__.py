@@ -233,9 +233,9 @@ def quant_act(x: torch.Tensor, xq: torch.Tensor = None, sx: torch.Tensor = None)
 
 
 def _workspace(M, N, K, group, device):
-    """Scratch of the size the library asks for (None when it needs none)."""
+    """Zero-filled scratch of the size the library asks for (None when it needs none)."""
     nbytes = linear_workspace_bytes(M, N, K, group)
-    return torch.empty(nbytes, dtype=torch.uint8, device=device) if nbytes else None
+    return torch.zeros(nbytes, dtype=torch.uint8, device=device) if nbytes else None
 
 
 def smooth_scales(X: torch.Tensor, pct: float = 0.005) -> torch.Tensor:
@@ -350,7 +350,7 @@ def quant_linear_a8w4(x: torch.Tensor, pw: PackedWeight, out: torch.Tensor = Non
         out = torch.empty((M, pw.N), dtype=torch.float16, device=x.device)
     if workspace is None:
         nbytes = quant_linear_workspace_bytes(M, pw.N, K, pw.group)
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=x.device) if nbytes else None
+        workspace = torch.zeros(nbytes, dtype=torch.uint8, device=x.device) if nbytes else None
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     fn = lib.dgq_quant_linear_a8w4_zp if pw.zp_form else lib.dgq_quant_linear_a8w4
     _check(fn(_ptr(x), _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out), _ptr(sx_out),
@@ -382,7 +382,7 @@ def rmsnorm_quant_linear_a8w4(x: torch.Tensor, gamma: torch.Tensor, eps: float, 
         out = torch.empty((M, pw.N), dtype=torch.float16, device=x.device)
     if workspace is None:
         nbytes = rmsnorm_quant_linear_workspace_bytes(M, pw.N, K, pw.group)
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=x.device) if nbytes else None
+        workspace = torch.zeros(nbytes, dtype=torch.uint8, device=x.device) if nbytes else None
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     fn = lib.dgq_rmsnorm_quant_linear_a8w4_zp if pw.zp_form else lib.dgq_rmsnorm_quant_linear_a8w4
     _check(fn(_ptr(x), _ptr(gamma), eps, _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out), _ptr(sx_out),
@@ -435,7 +435,7 @@ def linear_a8w4_acc(xq: torch.Tensor, pw: PackedWeight, workspace: torch.Tensor 
     acc = torch.empty((M, pw.N), dtype=torch.int32, device=xq.device)
     if workspace is None:
         nbytes = linear_acc_workspace_bytes(M, pw.N, K, pw.group, path)
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=xq.device) if nbytes else None
+        workspace = torch.zeros(nbytes, dtype=torch.uint8, device=xq.device) if nbytes else None
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     fn = lib.dgq_linear_a8w4_zp_acc if pw.zp_form else lib.dgq_linear_a8w4_acc
     _check(fn(_ptr(xq), _ptr(pw.qweight), _ptr(pw.scales), _ptr(acc), M, pw.N, K, pw.group, path,

@@ -15,7 +15,7 @@ thread_local int g_last_hip_error = 0;
 // bring a workspace.  Every GPU the library runs on holds its own copy of this array, at its own
 // address, until the process ends.  In host code the NAME below is only a handle for
 // hipGetSymbolAddress; kernels are given the address that call returns for the current device.
-constexpr size_t kScratchBytes = (size_t)32 << 20;
+constexpr size_t kScratchBytes = (size_t)40 << 20;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 constexpr int kMaxDevices = 64;
 std::atomic<void *> g_scratch_ptr[kMaxDevices];   // device address of `scratch` per GPU, set once
@@ -128,22 +128,22 @@ dgq_status quant_linear(const uint16_t *x, const uint16_t *gamma, float eps, con
                           s1, out, nullptr, M, N, K, group, zp_form, x, sx_out, gamma, eps};
         return hip_result(dgq::launch_linear_decode(a, nullptr, st));
     }
-    // two launches, xq and sx in the workspace: [xq: M*K][sx: 4*M][what the linear needs]
-    const size_t xq_bytes = round256((size_t)M * K), sx_bytes = round256((size_t)M * sizeof(float));
-    if (!workspace || workspace_bytes < xq_bytes + sx_bytes) return DGQ_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return DGQ_ERR_ALIGN;
-    char *ws = static_cast<char *>(workspace);
-    int8_t *xq = reinterpret_cast<int8_t *>(ws);
-    float *sx = sx_out ? sx_out : reinterpret_cast<float *>(ws + xq_bytes);
-    dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
-                      s1, out, nullptr, M, N, K, group, zp_form, nullptr, nullptr, nullptr, 0.0f};
+    // two launches, xq and sx in the workspace: [what the linear needs, its arrival counters first][xq: M*K][sx: 4*M]
     const int path = pick_path(M, forced);
     if (path == kPathStreamGeneric && zp_form) return DGQ_ERR_SHAPE;
-    if (workspace_bytes < xq_bytes + sx_bytes + workspace_needed(path, M, N, K)) return DGQ_ERR_WORKSPACE;
+    const size_t lin_bytes = round256(workspace_needed(path, M, N, K));
+    const size_t xq_bytes = round256((size_t)M * K), sx_bytes = round256((size_t)M * sizeof(float));
+    if (!workspace || workspace_bytes < lin_bytes + xq_bytes + sx_bytes) return DGQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return DGQ_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace);
+    int8_t *xq = reinterpret_cast<int8_t *>(ws + lin_bytes);
+    float *sx = sx_out ? sx_out : reinterpret_cast<float *>(ws + lin_bytes + xq_bytes);
+    dgq::LinearArgs a{xq, sx, static_cast<const uint4 *>(qweight), static_cast<const uint32_t *>(scales),
+                      s1, out, nullptr, M, N, K, group, zp_form, nullptr, nullptr, nullptr, 0.0f};
     const hipError_t qe = gamma ? dgq::launch_rmsnorm_quant_act(x, gamma, M, K, eps, xq, sx, st)
                                 : dgq::launch_quant_act(x, M, K, xq, sx, st);
     if (dgq_status q = hip_result(qe)) return q;
-    return run_linear(a, kPathAuto, ws + xq_bytes + sx_bytes, workspace_bytes - xq_bytes - sx_bytes, stream);
+    return run_linear(a, kPathAuto, ws, lin_bytes, stream);
 }
 
 }  // namespace
@@ -418,7 +418,7 @@ static dgq_status quant_linear_workspace(int M, int N, int K, int group, bool rm
         *bytes = 0;
     else
         *bytes = round256((size_t)M * K) + round256((size_t)M * sizeof(float)) +
-                 workspace_needed(pick_path(M, forced), M, N, K);
+                 round256(workspace_needed(pick_path(M, forced), M, N, K));
     return DGQ_OK;
 }
 
@@ -499,8 +499,8 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
     }
     default: {
         const dgq::TiledPlan p = dgq::tiled_plan(M, N, K);
-        std::snprintf(buf, buf_bytes, "linear_tiled_kernel<%d, %d, %d, %d, %s>", group, p.nw, p.mi, p.st,
-                      p.ksplit > 1 ? "true" : "false");
+        std::snprintf(buf, buf_bytes, "linear_tiled_%skernel<%d, %d, %d, %d, false>", p.ksplit > 1 ? "splitk_" : "", group,
+                      p.nw, p.mi, p.st);
     }
     }
     return DGQ_OK;

@@ -275,6 +275,11 @@ struct LinearArgs {
     const uint16_t *gamma; // optional, fp16 bits [K]: RMS-normalise x and multiply by gamma first
     float eps;             // added to the mean square
 };
+// A workspace that a K split uses starts with this many bytes of arrival counters (one 32-bit
+// word per tile or workgroup column, at most kSplitCounterBytes / 4 of them), whatever the shape
+// and the entry point: they are zero before a launch and zero again after it, so a buffer that
+// was cleared once serves any sequence of calls.  The partial sums follow.
+constexpr size_t kSplitCounterBytes = 65536;
 // Largest M the weight-streaming kernels take.
 constexpr int kStreamMaxM = 64;
 // Decode kernel (one 16-token tile, activations resident in registers).
@@ -286,6 +291,7 @@ constexpr int kQuantDecodeStageBytes = 49152;
 // With RMSNorm in front the kernel also holds a gamma vector per activation vector: up to four
 // steps per wavefront (K <= 8192, the hidden sizes that feed a block's first linears).
 constexpr int kRmsDecodeMaxStepsPerWave = 4;
+int cu_count();   // compute units of the current device; 256 when there is no device
 struct DecodePlan {
     int spw;     // steps of 128 k per wavefront (template SPW)
     int pf;      // column tiles prefetched ahead (template PF)
@@ -301,8 +307,6 @@ struct StreamPlan {
 StreamPlan stream_plan(int M, int N, int K);
 hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st);
 hipError_t launch_linear_stream(const LinearArgs &a, hipStream_t st);
-// Adds ksplit slices [M][N] of INT32 partial sums and runs the epilogue (or stores the sums).
-hipError_t launch_splitk_finalize(const LinearArgs &a, int ksplit, const int32_t *partial, hipStream_t st);
 struct TiledPlan {
     int nw;      // wavefronts per workgroup, 64 output channels each (template NW)
     int mi;      // 32-token blocks per tile (template MI)

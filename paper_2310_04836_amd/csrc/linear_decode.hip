@@ -15,9 +15,9 @@
 //   - The 16 partial INT32 tiles are added through LDS (double buffered, one barrier per
 //     tile; integer addition is associative, so the split changes no bit).  The first four
 //     wavefronts apply sx[m]*s1[n] (first line of Eq. 2) and store fp16.
-//   - If K is too long for 16 wavefronts x SPW steps, several workgroups split K and write
-//     raw INT32 partial tiles to the workspace; a small second kernel adds them and runs
-//     the epilogue.
+//   - If K is too long for 16 wavefronts x SPW steps, several workgroups split K: each leaves
+//     its INT32 tiles in the workspace and counts itself in; the one that arrives last adds
+//     the others' tiles to its own and runs the epilogue (no waiting, no second kernel).
 //   - FQ variant: the kernel is handed the fp16 activations and runs the per-token quantizer
 //     (Section 3.1, symmetric 8 bits) itself.  A workgroup that is not split over K needs every
 //     token's whole row anyway, so while its first weight loads are in flight its 1024 threads
@@ -42,6 +42,10 @@ struct DecodeGrid {
     int ks_shift;    // log2 of the number of K parts
     int tiles_base;  // every workgroup has this many column tiles ...
     int tiles_rem;   // ... and the first tiles_rem one more
+    // K split only: one counter per group of workgroups that share their column tiles (zero
+    // before the launch and again after it), and (tiles_base + 1) * 256 INT32 per workgroup
+    uint32_t *counters;   // [cols]
+    int32_t *partial;     // [cols][parts][(tiles_base + 1) * 256]
 };
 struct alignas(16) DecodeLds {
     int red[2][kWaves][256];           // partial tiles of the 16 wavefronts, double buffered
@@ -55,13 +59,13 @@ static_assert(sizeof(DecodeLds::red) / 2 + sizeof(DecodeLds::sums) == kQuantDeco
 // rmsnorm_quant_act_kernel does it (fp64 up to the rounding to fp32 and then fp16, the squares
 // added in the same fixed order).
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL, bool ZP, bool FQ, bool RMS = false>
-__device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGrid &grid, int32_t *partial)
+__device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGrid &grid)
 {
     // Everything before the first load is one wavefront executing straight-line scalar code at a
     // few cycles per instruction, so it is kept short: no run-time integer divisions (the host
     // passes quotients and remainders), and the K split is a constant 1 where there is none.
     const int ks_shift = PARTIAL ? grid.ks_shift : 0;   // the K split is a power of two
-    static_assert(!FQ || (!ACC && !PARTIAL), "the quantizing variant writes fp16 only");
+    static_assert(!FQ || (!ACC && !PARTIAL), "the quantizing variant writes fp16 only and sees all of K");
     static_assert(!RMS || FQ, "the normalising variant is a quantizing variant");
     // One block, so that red[1] and sums are contiguous (the FQ variant stages INT8 rows there).
     __shared__ DecodeLds lds;
@@ -96,7 +100,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGri
     const int ep_m = 4 * ((ep_x & 63) >> 4) + (ep_x >> 6);
     float ep_sx = 0.0f, ep_s1[kEarly] = {0.0f, 0.0f, 0.0f};
     auto load_epilogue_operands = [&]() {
-        if (!ACC && !PARTIAL && ep_m < a.M) {
+        if (!ACC && ep_m < a.M) {
             if (!FQ) ep_sx = a.sx[ep_m];
 #pragma unroll
             for (int k = 0; k < kEarly; ++k) {
@@ -373,6 +377,42 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGri
     }
     __syncthreads();
 
+    if constexpr (PARTIAL) {
+        // K split: this workgroup's tiles go to its block of the workspace, then it counts itself
+        // in; the last of the group to arrive adds the other blocks to its tiles and goes on.
+        // Stores and loads of partial tiles are relaxed atomics of device scope (they go through to
+        // the level of the memory system that all compute units share; no cache is written back
+        // or invalidated for them), ordered against the counter by hand: stores complete
+        // (vmcnt(0)) before the barrier behind which the workgroup counts itself in, loads are
+        // issued after the counter's old value has come back.
+        const int parts = 1 << ks_shift;
+        const size_t blk_pairs = (size_t)(grid.tiles_base + 1) * 128;
+        unsigned long long *mine = reinterpret_cast<unsigned long long *>(grid.partial) + ((size_t)wg * parts + kpart) * blk_pairs;
+        unsigned long long *flat = reinterpret_cast<unsigned long long *>(&sums[0][0]);
+        for (int x = threadIdx.x; x < my_tiles * 128; x += kWaves * 64)
+            __hip_atomic_store(&mine[x], flat[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0070);                     // vmcnt(0), lgkmcnt(0): the tiles have reached memory
+        __syncthreads();
+        uint32_t *arrived = reinterpret_cast<uint32_t *>(&red[0][0][0]);
+        if (threadIdx.x == 0)
+            *arrived = __hip_atomic_fetch_add(&grid.counters[wg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*arrived != (uint32_t)(parts - 1)) return;          // somebody else will finish these tiles
+        if (threadIdx.x == 0)                                   // ready for the next launch
+            __hip_atomic_store(&grid.counters[wg], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int p = 0; p < parts; ++p) {
+            if (p == kpart) continue;
+            const unsigned long long *other = reinterpret_cast<const unsigned long long *>(grid.partial) + ((size_t)wg * parts + p) * blk_pairs;
+            for (int x = threadIdx.x; x < my_tiles * 128; x += kWaves * 64) {
+                const unsigned long long o = __hip_atomic_load(&other[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                int *dst = &sums[0][0] + 2 * x;
+                dst[0] += (int)(uint32_t)o;
+                dst[1] += (int)(uint32_t)(o >> 32);
+            }
+        }
+        __syncthreads();
+    }
+
     // Epilogue for all tiles of this workgroup.  Element x of a tile: token 4*((x%64)/16) + x/64,
     // column tile*16 + x%16.
     if (ep_m < a.M) {
@@ -380,9 +420,7 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGri
         for (int ti = threadIdx.x >> 8; ti < my_tiles; ti += 4, ++k) {
             const int sum = sums[ti][ep_x];
             const int n = (wg + ti * wg_stride) * 16 + (ep_x & 15);
-            if (PARTIAL) {
-                partial[((size_t)kpart * a.M + ep_m) * a.N + n] = sum;
-            } else if (ACC) {
+            if (ACC) {
                 a.acc_out[(size_t)ep_m * a.N + n] = sum;
             } else {
                 float s1n;
@@ -398,94 +436,64 @@ __device__ __forceinline__ void decode_body(const LinearArgs &a, const DecodeGri
 }
 
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
-__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, DecodeGrid grid, int32_t *partial)
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, ACC, PARTIAL, false, false>(a, grid, partial);
+    decode_body<SPW, PF, G, ACC, PARTIAL, false, false>(a, grid);
 }
 template <int SPW, int PF, int G, bool ACC, bool PARTIAL>
-__global__ __launch_bounds__(kWaves * 64) void linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid, int32_t *partial)
+__global__ __launch_bounds__(kWaves * 64) void linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, ACC, PARTIAL, true, false>(a, grid, partial);
+    decode_body<SPW, PF, G, ACC, PARTIAL, true, false>(a, grid);
 }
 // fp16 activations in, quantized by the kernel itself (one workgroup sees the whole of K)
 template <int SPW, int PF, int G>
 __global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, false, true>(a, grid, nullptr);
+    decode_body<SPW, PF, G, false, false, false, true>(a, grid);
 }
 template <int SPW, int PF, int G>
 __global__ __launch_bounds__(kWaves * 64) void quant_linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, true, true>(a, grid, nullptr);
+    decode_body<SPW, PF, G, false, false, true, true>(a, grid);
 }
 // the same with RMSNorm in front of the quantizer
 template <int SPW, int PF, int G>
 __global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, false, true, true>(a, grid, nullptr);
+    decode_body<SPW, PF, G, false, false, false, true, true>(a, grid);
 }
 template <int SPW, int PF, int G>
 __global__ __launch_bounds__(kWaves * 64) void rmsnorm_quant_linear_decode_zp_kernel(LinearArgs a, DecodeGrid grid)
 {
-    decode_body<SPW, PF, G, false, false, true, true, true>(a, grid, nullptr);
+    decode_body<SPW, PF, G, false, false, true, true, true>(a, grid);
 }
 
-// Adds the K-split partial tiles and runs the epilogue; four consecutive columns per thread
-// (N is a multiple of 16, so a group of four never crosses a row).
-template <bool ACC>
-__global__ __launch_bounds__(256) void splitk_finalize_kernel(LinearArgs a, int ksplit, const int32_t *partial)
+// Workgroups per K part for N / 16 column tiles.
+int decode_cols(int tiles, int ksplit)
 {
-    const size_t total = (size_t)a.M * a.N;
-    const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (idx >= total) return;
-    v4i sum = v4i{0, 0, 0, 0};
-    for (int p = 0; p < ksplit; ++p) sum += *reinterpret_cast<const v4i *>(&partial[(size_t)p * total + idx]);
-    if (ACC) {
-        *reinterpret_cast<v4i *>(&a.acc_out[idx]) = sum;
-    } else {
-        const int m = (int)(idx / a.N);
-        const int n = (int)(idx % a.N);
-        const float sxm = a.sx[m];
-        const float s1v[4] = {a.s1[n], a.s1[n + 1], a.s1[n + 2], a.s1[n + 3]};  // s1 need not be 16-byte aligned
-        unsigned short h[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float sc = sxm * s1v[i];
-            h[i] = scaled_sum_to_half_bits(sc, sum[i]);
-        }
-        uint2 o;
-        o.x = h[0] | ((uint32_t)h[1] << 16);
-        o.y = h[2] | ((uint32_t)h[3] << 16);
-        *reinterpret_cast<uint2 *>(&a.out[idx]) = o;
-    }
-}
-
-int cu_count()
-{
-    static int n = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-            v = 256;
-        return v;
-    }();
-    return n;
+    int cols = cu_count() / ksplit;
+    if (cols < 1) cols = 1;
+    if (cols * kMaxTilesPerWg < tiles) cols = (tiles + kMaxTilesPerWg - 1) / kMaxTilesPerWg;
+    if (cols > tiles) cols = tiles;
+    return cols;
 }
 
 template <int SPW, int PF, int G>
 hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
 {
     const int tiles = a.N / 16;
-    int cols = cu_count() / ksplit;
-    if (cols < 1) cols = 1;
-    if (cols * kMaxTilesPerWg < tiles) cols = (tiles + kMaxTilesPerWg - 1) / kMaxTilesPerWg;
-    if (cols > tiles) cols = tiles;
+    const int cols = decode_cols(tiles, ksplit);
     dim3 grid(cols * ksplit), block(kWaves * 64);
     int ks_shift = 0;
     while ((1 << ks_shift) < ksplit) ++ks_shift;
     if ((1 << ks_shift) != ksplit) return hipErrorInvalidValue;   // decode_plan only makes powers of two
-    const DecodeGrid dg{cols, ks_shift, tiles / cols, tiles % cols};
-    int32_t *partial = static_cast<int32_t *>(workspace);
+    DecodeGrid dg{cols, ks_shift, tiles / cols, tiles % cols, nullptr, nullptr};
+    if (ksplit > 1) {
+        char *ws = static_cast<char *>(workspace);
+        dg.counters = reinterpret_cast<uint32_t *>(ws);
+        if ((size_t)cols * sizeof(uint32_t) > kSplitCounterBytes) return hipErrorInvalidValue;   // cols <= number of CUs
+        dg.partial = reinterpret_cast<int32_t *>(ws + kSplitCounterBytes);
+    }
     const bool acc = a.acc_out != nullptr;
     if (a.x16) {
         if (ksplit > 1 || acc || (long long)a.M * (a.K + 16) > kQuantDecodeStageBytes) return hipErrorInvalidValue;
@@ -505,20 +513,25 @@ hipError_t launch_spw(const LinearArgs &a, int ksplit, void *workspace, hipStrea
         return hipGetLastError();
     }
     if (ksplit > 1) {
-        if (a.zp)
-            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, dg, partial);
-        else
-            hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, dg, partial);
-        return launch_splitk_finalize(a, ksplit, partial, st);
+        if (a.zp) {
+            if (acc)
+                hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, true, true>), grid, block, 0, st, a, dg);
+            else
+                hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, dg);
+        } else if (acc) {
+            hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, true>), grid, block, 0, st, a, dg);
+        } else {
+            hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, true>), grid, block, 0, st, a, dg);
+        }
     } else if (a.zp) {
         if (acc)
-            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, dg, partial);
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, dg);
         else
-            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, dg, partial);
+            hipLaunchKernelGGL((linear_decode_zp_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, dg);
     } else if (acc) {
-        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, dg, partial);
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, true, false>), grid, block, 0, st, a, dg);
     } else {
-        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, dg, partial);
+        hipLaunchKernelGGL((linear_decode_kernel<SPW, PF, G, false, false>), grid, block, 0, st, a, dg);
     }
     return hipGetLastError();
 }
@@ -539,15 +552,17 @@ hipError_t launch_g(const LinearArgs &a, const DecodePlan &p, void *workspace, h
 
 }  // namespace
 
-hipError_t launch_splitk_finalize(const LinearArgs &a, int ksplit, const int32_t *partial, hipStream_t st)
+// Compute units of the current device (256 if there is none: host-only queries).
+int cu_count()
 {
-    const size_t total = (size_t)a.M * a.N;
-    dim3 fgrid((unsigned)((total / 4 + 255) / 256));
-    if (a.acc_out)
-        hipLaunchKernelGGL(splitk_finalize_kernel<true>, fgrid, dim3(256), 0, st, a, ksplit, partial);
-    else
-        hipLaunchKernelGGL(splitk_finalize_kernel<false>, fgrid, dim3(256), 0, st, a, ksplit, partial);
-    return hipGetLastError();
+    static int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        return v;
+    }();
+    return n;
 }
 
 DecodePlan decode_plan(int K)
@@ -564,8 +579,12 @@ DecodePlan decode_plan(int K)
 
 size_t decode_workspace_bytes(int M, int N, int K)
 {
-    const int s = decode_plan(K).ksplit;
-    return s > 1 ? (size_t)s * M * N * sizeof(int32_t) : 0;
+    (void)M;   // the partial tiles always hold 16 tokens
+    const int ks = decode_plan(K).ksplit;
+    if (ks <= 1) return 0;
+    const int tiles = N / 16;
+    const int cols = decode_cols(tiles, ks);
+    return kSplitCounterBytes + (size_t)cols * ks * (tiles / cols + 1) * 256 * sizeof(int32_t);
 }
 
 hipError_t launch_linear_decode(const LinearArgs &a, void *workspace, hipStream_t st)

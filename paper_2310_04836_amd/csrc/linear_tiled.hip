@@ -6,8 +6,8 @@
 //     stages of 128.  The wavefronts split the output channels (64 each), so every packed
 //     weight is expanded to INT8 exactly once per workgroup.
 //   - Weights never touch LDS: each lane loads 16-byte cells of qweight straight into VGPRs
-//     (a cell = 32 consecutive k of one column) ST - 1 stages ahead of their use (ST = 3, or 6
-//     where the weight stream is the bound), expands them with the group scale (second line
+//     (a cell = 32 consecutive k of one column) ST - 1 = 2 stages ahead of their use, expands
+//     them with the group scale (second line
 //     of Eq. 2) and feeds them as the B operand of v_mfma_i32_32x32x32_i8.
 //   - The INT8 activation tile goes from global memory directly into an ST-stage LDS ring
 //     (global_load_lds_dwordx4, no registers in between), as far ahead.  A row is 128
@@ -16,12 +16,17 @@
 //     16-byte slots of the 256-byte bank line.  Lane (kb, i) reads as the A
 //     operand the same k that the weight cell of lane (kb, j) holds.
 //   - INT32 accumulation over all of K (third line of Eq. 2), then the scale epilogue (first
-//     line of Eq. 2) and one rounding to fp16; or, when several workgroups split K, raw INT32
-//     partial sums for a second kernel that adds them and scales.
+//     line of Eq. 2) and one rounding to fp16.  When several workgroups split the K of one tile,
+//     each leaves its INT32 partial sums in the workspace and counts itself in on the tile's
+//     counter; the workgroup that arrives last adds the others' sums to its own (integer
+//     addition: any order gives the same bits) and runs the epilogue.  Nobody waits for anybody,
+//     so the scheme cannot hang whatever the number of resident workgroups.
 //   - Workgroups are numbered so that each XCD (workgroup id modulo 8) walks a contiguous
 //     range of tiles, ordered in bands of eight column tiles: the 64 workgroups resident on
 //     one XCD cover about 8 x 8 tiles and share their operands in that XCD's L2.
 #include "dgq_device.hpp"
+
+#include <cmath>
 
 namespace dgq {
 namespace {
@@ -88,12 +93,22 @@ __device__ __forceinline__ void arrive(v4u &a, v4u &b, v4u &c, v4u &d, uint32_t 
 
 // NW wavefronts per workgroup, each owning 64 output channels of the (32*MI) x (64*NW) tile;
 // ST stages of operands in flight or in use.  ksplit workgroups share one tile, each walking its
-// own part of K; then (and in the test hook) the raw INT32 sums go to a.acc_out, slice kpart.
+// own part of K (see SplitK below).  ACC: the test hook, raw INT32 sums to a.acc_out.
 // ZP: the scale words hold (S2, ZP) pairs instead of S2 bytes; a compile-time choice, so that the
 // signed-nibble form pays nothing for the general one.
-template <int G, int NW, int MI, int ST, bool ACC, bool ZP>
-__device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int tiles_n, int ksplit)
+// Workspace of a K split: one counter per tile (zero before the launch, zero again after it),
+// then for every tile and part a block of BM x BN INT32 partial sums in register order.
+struct SplitK {
+    int parts;           // workgroups per tile (1: no split, the pointers are unused)
+    uint32_t *counters;  // [tiles]
+    int32_t *partial;    // [tiles][parts][BM * BN]
+};
+
+// SPLIT is a compile-time choice so that the kernels without a K split carry none of its code.
+template <int G, int NW, int MI, int ST, bool ACC, bool ZP, bool SPLIT>
+__device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int tiles_n, const SplitK &sk)
 {
+    const int ksplit = SPLIT ? sk.parts : 1;
     constexpr int kStages = ST;
     constexpr int BM = 32 * MI;
     constexpr int BN = 64 * NW;
@@ -343,11 +358,58 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 #undef DGQ_LOAD_STAGE
 #undef DGQ_LOAD_ITEM
 
+    // ---- K split: the last workgroup of a tile to arrive adds up the parts ----------------------
+    if constexpr (SPLIT) {
+        // Block (tile, part) holds the sums in register order: pair j = (mi*2 + nj)*8 + r/2 of
+        // wavefront w and lane l at 8-byte unit (w*MI*16 + j)*64 + l, so that every store and
+        // load of a wavefront covers 512 bytes of contiguous memory.
+        //
+        // Stores and loads of partial sums are relaxed atomics of device scope: they go through to
+        // (come from) the level of the memory system that all compute units share, and nothing else
+        // in the caches is written back or invalidated for them.  Order between the sums and the
+        // counter is kept by hand: a wavefront waits until its stores have completed (vmcnt(0))
+        // before the barrier behind which the workgroup counts itself in, and the last arriver
+        // issues its loads only after the counter's old value has come back.
+        unsigned long long *blk = reinterpret_cast<unsigned long long *>(sk.partial + ((size_t)tile * ksplit + kpart) * (BM * BN)) +
+                                  wave * (MI * 16) * 64 + lane;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const unsigned long long v = (uint32_t)acc[mi][nj][2 * q] | ((unsigned long long)(uint32_t)acc[mi][nj][2 * q + 1] << 32);
+                    __hip_atomic_store(&blk[((mi * 2 + nj) * 8 + q) * 64], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+        __builtin_amdgcn_s_waitcnt(wait_vm(0, true));   // this wavefront's sums have reached memory
+        __syncthreads();
+        uint32_t *arrived = reinterpret_cast<uint32_t *>(&lds_a[0][0]);
+        if (tid == 0) *arrived = __hip_atomic_fetch_add(&sk.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*arrived != (uint32_t)(ksplit - 1)) return;      // somebody else will finish this tile
+        if (tid == 0) __hip_atomic_store(&sk.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+        for (int p = 0; p < ksplit; ++p) {
+            if (p == kpart) continue;
+            const unsigned long long *ob = reinterpret_cast<const unsigned long long *>(sk.partial + ((size_t)tile * ksplit + p) * (BM * BN)) +
+                                           wave * (MI * 16) * 64 + lane;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const unsigned long long o = __hip_atomic_load(&ob[((mi * 2 + nj) * 8 + q) * 64], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        acc[mi][nj][2 * q] += (int)(uint32_t)o;
+                        acc[mi][nj][2 * q + 1] += (int)(uint32_t)(o >> 32);
+                    }
+        }
+    }
+
     // ---- epilogue ---------------------------------------------------------------------------
     // acc[mi][nj][r] of lane l: token m0 + mi*32 + 8*(r/4) + 4*(l/32) + r%4, column ncol[nj].
     __syncthreads();  // every wavefront is done with the LDS ring
     if (ACC) {
-        int32_t *dst = a.acc_out + (size_t)kpart * a.M * a.N;
+        int32_t *dst = a.acc_out;
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj) {
             const int n = ncol[nj];
@@ -397,71 +459,118 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 }
 
 template <int G, int NW, int MI, int ST, bool ACC>
-__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_kernel(LinearArgs a, int tiles_m, int tiles_n)
 {
-    tiled_body<G, NW, MI, ST, ACC, false>(a, tiles_m, tiles_n, ksplit);
+    tiled_body<G, NW, MI, ST, ACC, false, false>(a, tiles_m, tiles_n, SplitK{1, nullptr, nullptr});
 }
 template <int G, int NW, int MI, int ST, bool ACC>
-__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_zp_kernel(LinearArgs a, int tiles_m, int tiles_n, int ksplit)
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_zp_kernel(LinearArgs a, int tiles_m, int tiles_n)
 {
-    tiled_body<G, NW, MI, ST, ACC, true>(a, tiles_m, tiles_n, ksplit);
+    tiled_body<G, NW, MI, ST, ACC, true, false>(a, tiles_m, tiles_n, SplitK{1, nullptr, nullptr});
+}
+// the same with the K of every tile split over sk.parts workgroups
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_splitk_kernel(LinearArgs a, int tiles_m, int tiles_n, SplitK sk)
+{
+    tiled_body<G, NW, MI, ST, ACC, false, true>(a, tiles_m, tiles_n, sk);
+}
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_splitk_zp_kernel(LinearArgs a, int tiles_m, int tiles_n, SplitK sk)
+{
+    tiled_body<G, NW, MI, ST, ACC, true, true>(a, tiles_m, tiles_n, sk);
 }
 
 }  // namespace
 
+namespace {
+// Predicted duration (us) of one launch: a small model fitted to a sweep of 728 timings over the
+// LLaMA-7B/13B/65B layer shapes at M = 64 ... 2048 (root-mean-square error 12 %).  It is only
+// used to compare a plan with its K split over several workgroups against the unsplit plan.
+//   stage    0.585 us for a 128 x 256 tile alone on a CU, in proportion to the tile's MFMA work;
+//            2.56 x that when two workgroups share the CU (they also share its clock budget);
+//            +0.13 us for 64-token tiles (every weight is expanded for half as many MFMAs)
+//   launch   5.9 us (launch, first loads, epilogue)
+//   split    1.1 us per further part and 64 KiB of tile for the last workgroup's additions, and
+//            0.34 us per MB of partial sums (they go through to memory)
+//   and never faster than the weights, activations and outputs take at 3.9 TB/s
+double predicted_us(int M, int N, int K, const TiledPlan &p, int cus)
+{
+    const int bm = 32 * p.mi, bn = 64 * p.nw;
+    const double tiles = (double)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const double wgs = tiles * p.ksplit;
+    const double slots = (double)cus * (p.nw == 4 ? 2 : 1);
+    const double rounds = ceil(wgs / slots);
+    const double resident = (wgs < slots ? wgs : slots) / cus;
+    const double shared = p.nw == 4 && resident > 1.0 ? resident : 1.0;
+    const double work = p.mi * p.nw / 16.0;
+    const double t_stage = 0.585 * work * (1.0 + 1.563 * (shared - 1.0)) + (p.mi == 2 ? 0.133 : 0.0);
+    const int steps = K / 128;
+    double t = 5.948 + rounds * ((steps + p.ksplit - 1) / p.ksplit) * t_stage;
+    if (p.ksplit > 1)
+        t += 1.125 * (p.ksplit - 1) * (bm * bn * 4 / 65536.0) + 0.337 * (wgs * bm * bn * 4 / 1e6);
+    const double stream = ((double)K * N / 2 + (double)M * K * rounds + 2.0 * M * N) / 3.919e6;
+    return t > stream ? t : stream;
+}
+}  // namespace
+
 TiledPlan tiled_plan(int M, int N, int K)
 {
-    constexpr int kCus = 256;
+    const int cus = cu_count();
     const int steps = K / 128;
     TiledPlan p;
     p.nw = 4, p.mi = 4, p.st = 3, p.ksplit = 1;
     const long long tiles_n = (N + 255) / 256;
     const long long tiles_64 = (long long)((M + 63) / 64) * tiles_n;
-    if (M <= 256 && tiles_64 < 2 * kCus) {
-        // Few 64-token tiles: the weights are read about once and the layer is bound by that
-        // stream and by how many stages one workgroup walks in sequence.  Splitting K over
-        // several workgroups per tile shortens the walk but every part writes and re-reads
-        // M x N INT32 partial sums and a second kernel adds them.  The split (1, 2, 4 or 8 parts,
-        // at least 4 stages each) is the one a small model fitted to measurements predicts to be
-        // fastest: 0.5 us per stage and round of workgroups, 3.5 us for the second kernel, 0.45 us
-        // per MB of partial sums written and read.
-        int best = 1;
-        double best_t = 0.0;
-        for (int ks = 1; ks <= 8; ks *= 2) {
-            if (ks > 1 && steps / ks < 4) break;
-            const double rounds = (double)((tiles_64 * ks + 2 * kCus - 1) / (2 * kCus));
-            double t = 0.5 * ((steps + ks - 1) / ks) * rounds;
-            if (ks > 1) t += 3.5 + 0.45 * (8e-6 * ks * (double)M * (double)N);
-            if (ks == 1 || t < best_t) best = ks, best_t = t;
-        }
-        if (M <= 64 || best > 1) {
-            // six stages keep 5 x 16 KiB of weights in flight per workgroup
-            p.ksplit = best;
-            p.mi = 2;
-            p.st = 6;
-            return p;
-        }
-    }
-    if (tiles_64 <= kCus) {
+    const long long tiles_128 = (long long)((M + 127) / 128) * tiles_n;
+    if (M <= 64 || tiles_64 <= cus) {
         // Even 64-token tiles leave every workgroup a CU of its own: twice as many SIMDs work as
         // with 128-token tiles.  (With more tiles than CUs the smaller tile loses: it expands
         // every weight twice as often.)
         p.mi = 2;
-        return p;
+    } else {
+        // Two workgroups of four wavefronts per CU overlap better than one of eight: the two
+        // wavefronts that share a SIMD then wait at different barriers.  The wide tile (128 x 512,
+        // eight wavefronts) moves a quarter less operand data per MAC, which pays when its grid
+        // fills the CUs as evenly as the narrow one's: in whole rounds, or in one round that
+        // reaches most of them while the narrow tiles also fit one round.
+        const long long wide = (long long)((M + 127) / 128) * ((N + 511) / 512);
+        if ((wide >= cus && wide % cus == 0) || (wide >= 160 && wide <= cus && tiles_128 <= 2 * cus)) p.nw = 8;
     }
-    // Two workgroups of four wavefronts per CU overlap better than one of eight: the two
-    // wavefronts that share a SIMD then wait at different barriers.  The wide tile (128 x 512,
-    // eight wavefronts) moves a quarter less operand data per MAC, which only pays when its grid
-    // fills every CU in whole rounds (one workgroup per CU and round).
-    const long long wide = (long long)((M + 127) / 128) * ((N + 511) / 512);
-    if (wide >= kCus && wide % kCus == 0) p.nw = 8;
-    return p;
+    // K split over several workgroups per tile (the last to arrive adds up the parts): for shapes
+    // whose tiles alone leave CUs idle.  64-token tiles in 2 to 8 parts (at most two workgroups per
+    // CU), 128-token tiles in 2 to 4 parts (every part a CU to itself); at least four stages per
+    // part; taken when the model above predicts more than 3 % gain over the unsplit plan.  The
+    // partial sums of such a plan never exceed 2 * CUs * 64 KiB.
+    double best_t = predicted_us(M, N, K, p, cus);
+    const double bar = 0.97 * best_t;
+    TiledPlan best = p;
+    static const int kParts[] = {2, 3, 4, 6, 8};
+    for (int mi = 2; mi <= 4; mi += 2) {
+        if (mi == 4 && M <= 64) continue;
+        const long long tiles = mi == 2 ? tiles_64 : tiles_128;
+        for (int ks : kParts) {
+            if (steps / ks < 4) break;
+            if (ks > (mi == 2 ? 8 : 4) || tiles * ks > (mi == 4 ? cus : 2 * cus)) break;   // every part resident at once
+            TiledPlan c;
+            c.nw = 4, c.mi = mi, c.st = 3, c.ksplit = ks;
+            const double t = predicted_us(M, N, K, c, cus);
+            if (t < bar && t < best_t) best = c, best_t = t;
+        }
+    }
+    return best;
 }
+
+// Tile shape of a plan (tokens x output channels).
+static inline void plan_tile(const TiledPlan &p, int &bm, int &bn) { bm = 32 * p.mi, bn = 64 * p.nw; }
 
 size_t tiled_workspace_bytes(int M, int N, int K)
 {
-    const int ks = tiled_plan(M, N, K).ksplit;
-    return ks > 1 ? (size_t)ks * M * N * sizeof(int32_t) : 0;
+    const TiledPlan p = tiled_plan(M, N, K);
+    if (p.ksplit <= 1) return 0;
+    int bm, bn;
+    plan_tile(p, bm, bn);
+    const size_t tiles = (size_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    return kSplitCounterBytes + tiles * p.ksplit * bm * bn * sizeof(int32_t);
 }
 
 template <int G, int NW, int MI, int ST>
@@ -473,34 +582,34 @@ static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *worksp
     const long long blocks = ((T + 7) / 8) * 8;
     if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(64 * NW);
+    SplitK sk{ksplit, nullptr, nullptr};
     if (ksplit > 1) {
-        // raw INT32 sums of every part into its slice of the workspace, then one pass that adds
-        // the slices and applies the scales
-        LinearArgs part = a;
-        part.acc_out = static_cast<int32_t *>(workspace);
-        if (a.zp)
-            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
-        else
-            hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, part, tiles_m, tiles_n, ksplit);
-        return launch_splitk_finalize(a, ksplit, part.acc_out, st);
+        char *ws = static_cast<char *>(workspace);
+        sk.counters = reinterpret_cast<uint32_t *>(ws);
+        if ((size_t)tiles_m * tiles_n * sizeof(uint32_t) > kSplitCounterBytes) return hipErrorInvalidValue;   // tiled_plan never splits that many tiles
+        sk.partial = reinterpret_cast<int32_t *>(ws + kSplitCounterBytes);
     }
-    if (a.zp) {
-        if (a.acc_out)
-            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
-        else
-            hipLaunchKernelGGL((linear_tiled_zp_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
-    } else if (a.acc_out) {
-        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+#define DGQ_LAUNCH(KERNEL, ...)                                                                            \
+    do {                                                                                                   \
+        if (a.acc_out)                                                                                     \
+            hipLaunchKernelGGL((KERNEL<G, NW, MI, ST, true>), grid, block, 0, st, a, tiles_m, tiles_n, ##__VA_ARGS__);  \
+        else                                                                                               \
+            hipLaunchKernelGGL((KERNEL<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, ##__VA_ARGS__); \
+    } while (0)
+    if (ksplit > 1) {
+        if (a.zp) DGQ_LAUNCH(linear_tiled_splitk_zp_kernel, sk);
+        else DGQ_LAUNCH(linear_tiled_splitk_kernel, sk);
     } else {
-        hipLaunchKernelGGL((linear_tiled_kernel<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, 1);
+        if (a.zp) DGQ_LAUNCH(linear_tiled_zp_kernel);
+        else DGQ_LAUNCH(linear_tiled_kernel);
     }
+#undef DGQ_LAUNCH
     return hipGetLastError();
 }
 
 template <int G>
 static hipError_t launch_tiled_g(const LinearArgs &a, const TiledPlan &p, void *workspace, hipStream_t st)
 {
-    if (p.mi == 2 && p.st == 6) return launch_tiled_cfg<G, 4, 2, 6>(a, p.ksplit, workspace, st);
     if (p.mi == 2) return launch_tiled_cfg<G, 4, 2, 3>(a, p.ksplit, workspace, st);
     if (p.nw == 8) return launch_tiled_cfg<G, 8, 4, 3>(a, p.ksplit, workspace, st);
     return launch_tiled_cfg<G, 4, 4, 3>(a, p.ksplit, workspace, st);

@@ -115,8 +115,8 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4_noalloc(good, good, good, good, None, good, 1, 16, 128, 128, None) == -1
     assert L.dgq_linear_a8w4_noalloc(good, good, good, good, good, good, 1, 20, 128, 128, None) == -2
     assert L.dgq_linear_a8w4_noalloc(good, good, odd, good, good, good, 1, 16, 128, 128, None) == -3
-    assert dgq.linear_workspace_bytes(64, 36864, 131072, 128) > (32 << 20)
-    assert L.dgq_linear_a8w4_noalloc(good, good, good, good, good, good, 64, 36864, 131072, 128, None) == -5
+    assert dgq.linear_workspace_bytes(1, 1048576, 16384, 128) > (40 << 20)     # K split of the decode kernel over 2048 workgroup columns
+    assert L.dgq_linear_a8w4_noalloc(good, good, good, good, good, good, 1, 1048576, 16384, 128, None) == -5
     # quantizer + linear as one call
     n = ctypes.c_size_t(7)
     assert L.dgq_quant_linear_workspace_bytes(4, 4096, 11008, 128, ctypes.byref(n)) == 0 and n.value == 0
@@ -124,7 +124,7 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_quant_linear_workspace_bytes(16, 4096, 4096, 128, ctypes.byref(n)) == 0
     assert n.value == 16 * 4096 + 256                       # two kernels: xq and sx in the workspace
     assert L.dgq_quant_linear_workspace_bytes(64, 8192, 8192, 128, ctypes.byref(n)) == 0
-    assert n.value == 64 * 8192 + 256 + 4 * 64 * 8192 * 4   # plus the K-split partial sums
+    assert n.value == 64 * 8192 + 256 + 65536 + 32 * 4 * 64 * 256 * 4   # plus counters and K-split partial sums (32 tiles x 4 parts)
     assert L.dgq_quant_linear_workspace_bytes(0, 4096, 4096, 128, ctypes.byref(n)) == -2
     assert L.dgq_quant_linear_a8w4(None, good, good, good, good, None, 1, 16, 128, 128, None, 0, None) == -1
     assert L.dgq_quant_linear_a8w4(good, good, good, good, good, None, 1, 16, 100, 128, None, 0, None) == -2
@@ -162,22 +162,27 @@ def test_linear_plan_names(dgq):
     assert dgq.linear_plan(16, 22016, 4096, 128) == "linear_decode_kernel<2, 2, 128, false, false>"
     assert dgq.linear_plan(1, 4096, 11008, 128) == "linear_decode_kernel<6, 1, 128, false, false>"
     assert dgq.linear_plan(8, 8192, 22016, 64) == "linear_decode_kernel<6, 1, 64, false, true>"
-    # 16 < M <= 64: 64-token tile, six stages, K split over workgroups (partial sums -> "true")
-    assert dgq.linear_plan(64, 8192, 8192, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
-    assert dgq.linear_workspace_bytes(64, 8192, 8192, 128) == 4 * 64 * 8192 * 4
-    assert dgq.linear_plan(17, 44032, 256, 64) == "linear_tiled_kernel<64, 4, 2, 6, false>"
+    # 16 < M <= 64: 64-token tiles; K split over several workgroups per tile where the tiles alone leave CUs idle
+    assert dgq.linear_plan(64, 8192, 8192, 128) == "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"
+    assert dgq.linear_workspace_bytes(64, 8192, 8192, 128) == 65536 + 32 * 4 * 64 * 256 * 4      # counters + 32 tiles x 4 parts
+    assert dgq.linear_plan(17, 44032, 256, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"      # two stages: nothing to split
     assert dgq.linear_workspace_bytes(17, 44032, 256, 64) == 0
-    assert dgq.linear_plan(64, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 2, 6, false>"    # 86 tiles: no split
-    # 64 < M <= 256 with very few tiles splits K as well
-    assert dgq.linear_plan(128, 4096, 11008, 128) == "linear_tiled_kernel<128, 4, 2, 6, true>"
-    assert dgq.linear_workspace_bytes(128, 4096, 11008, 128) == 4 * 128 * 4096 * 4
-    assert dgq.linear_plan(128, 12288, 4096, 128) == "linear_tiled_kernel<128, 4, 2, 3, false>"
-    # fewer 128-token tiles than CUs: 64-token tiles
+    assert dgq.linear_plan(64, 44032, 8192, 128) == "linear_tiled_kernel<128, 4, 2, 3, false>"    # 172 tiles: no split
+    # larger M with few tiles and a long K splits as well, 128-token tiles while every part has a CU to itself
+    assert dgq.linear_plan(128, 4096, 11008, 128) == "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"
+    assert dgq.linear_plan(512, 4096, 11008, 128) == "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"
+    assert dgq.linear_workspace_bytes(512, 4096, 11008, 128) == 65536 + 128 * 2 * 64 * 256 * 4
+    assert dgq.linear_plan(512, 8192, 22016, 128) == "linear_tiled_splitk_kernel<128, 4, 4, 3, false>"
+    assert dgq.linear_workspace_bytes(512, 8192, 22016, 128) == 65536 + 128 * 2 * 128 * 256 * 4
+    assert dgq.linear_plan(1024, 5120, 13824, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"  # 160 tiles x 2 would not fit the CUs
+    # fewer 64-token tiles than CUs: 64-token tiles
     assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"     # 8 x 16 tiles
     assert dgq.linear_plan(512, 12288, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"    # 4 x 48 tiles
     assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"
     assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
+    # 128 x 512 tiles where their grid fills the CUs in whole rounds, or most of them in one round
     assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 16 x 16 wide tiles
+    assert dgq.linear_plan(1024, 12288, 4096, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 8 x 24 wide tiles
 
 
 def test_packed_sizes_zp(dgq):
@@ -193,7 +198,7 @@ def test_path_argument_of_the_test_hooks(dgq):
     assert dgq.lib.dgq_linear_a8w4_zp_acc(good, good, good, good, 65, 16, 128, 128, 3, None, 0, None) == -2
     # the workspace of a forced path is the one that path needs
     assert dgq.linear_acc_workspace_bytes(64, 8192, 8192, 128, 0) == dgq.linear_workspace_bytes(64, 8192, 8192, 128)
-    assert dgq.linear_acc_workspace_bytes(8, 8192, 22016, 128, 1) == 2 * 8 * 8192 * 4
+    assert dgq.linear_acc_workspace_bytes(8, 8192, 22016, 128, 1) == 65536 + 128 * 2 * 5 * 256 * 4   # 128 workgroup columns x 2 parts
     assert dgq.linear_acc_workspace_bytes(64, 8192, 8192, 128, 3) == 0
     with pytest.raises(dgq.DGQError):
         dgq.linear_acc_workspace_bytes(65, 8192, 8192, 128, 1)

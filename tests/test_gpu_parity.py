@@ -181,7 +181,7 @@ def test_acc_bit_exact_decode_kernel(dgq, torch, M, K, N, g):
 def test_decode_workspace_contract(dgq, torch):
     M, K, N, g = 4, 22016, 64, 128
     need = dgq.linear_workspace_bytes(M, N, K, g)
-    assert need == 2 * M * N * 4
+    assert need == 65536 + 4 * 2 * 2 * 256 * 4             # counters; four workgroup columns x two parts x room for two 16 x 16 tiles
     w4, s2, s1 = workloads.integer_weights(K, N, g, 1)
     xq, sx = workloads.integer_activations(M, K, 1)
     pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
@@ -189,10 +189,13 @@ def test_decode_workspace_contract(dgq, torch):
     with pytest.raises(dgq.DGQError) as e:
         dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=small)
     assert e.value.status == -5
-    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")   # contents undefined on entry
-    out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=ws))
+    # zero-filled once; every call leaves the arrival counters zero, so the buffer is reused as it is
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
     oout, _ = oracle.linear_a8w4(xq, sx, w4, s2, s1, g)
-    assert_fp16_close(out, oout)
+    for _ in range(3):
+        out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=ws))
+        assert_fp16_close(out, oout)
+        ws[65536:] = 0xAB                              # only the counters (the first 64 KiB) must stay zero
 
 
 @pytest.mark.parametrize("M,K,N,g", [
@@ -225,7 +228,7 @@ def test_acc_bit_exact_mid_m(dgq, torch, M, K, N, g):
 def test_tiled_split_workspace_contract(dgq, torch):
     M, K, N, g = 64, 4096, 512, 128
     need = dgq.linear_workspace_bytes(M, N, K, g)
-    assert need == 8 * M * N * 4
+    assert need == 65536 + 2 * 4 * 64 * 256 * 4            # counters; two tiles of 64 x 256 in four parts
     w4, s2, s1 = workloads.integer_weights(K, N, g, 2)
     xq, sx = workloads.integer_activations(M, K, 2)
     pw = dgq.pack_weights(dev(torch, w4), dev(torch, s2), dev(torch, s1), g)
@@ -233,10 +236,13 @@ def test_tiled_split_workspace_contract(dgq, torch):
     with pytest.raises(dgq.DGQError) as e:
         dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=small)
     assert e.value.status == -5
-    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")   # contents undefined on entry
-    out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=ws))
+    # zero-filled once; every call leaves the arrival counters zero, so the buffer is reused as it is
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
     oout, _ = oracle.linear_a8w4(xq, sx, w4, s2, s1, g)
-    assert_fp16_close(out, oout)
+    for _ in range(3):
+        out = host(dgq.linear_a8w4(dev(torch, xq), dev(torch, sx), pw, workspace=ws))
+        assert_fp16_close(out, oout)
+        ws[65536:] = 0xAB                              # only the counters (the first 64 KiB) must stay zero
 
 
 def test_both_paths_and_split_factors_agree(dgq, torch):
@@ -769,7 +775,7 @@ def test_graph_replays_equal_eager_results(dgq, torch):
         outsr.append(torch.empty((M, N), dtype=torch.float16, device="cuda"))
         nb = max(dgq.linear_workspace_bytes(M, N, K, g), dgq.quant_linear_workspace_bytes(M, N, K, g),
                  dgq.rmsnorm_quant_linear_workspace_bytes(M, N, K, g), 16)
-        wss.append(torch.empty(nb, dtype=torch.uint8, device="cuda"))
+        wss.append(torch.zeros(nb, dtype=torch.uint8, device="cuda"))
     bufs = [(torch.empty((M, K), dtype=torch.int8, device="cuda"), torch.empty(M, dtype=torch.float32, device="cuda"))
             for M, K, N in cases]
 
