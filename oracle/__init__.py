@@ -41,6 +41,7 @@ def _L():
         _lib.dgq_oracle_gemm_i32.restype = ctypes.c_long
         _lib.dgq_oracle_pack.restype = ctypes.c_long
         _lib.dgq_oracle_threads.restype = ctypes.c_int
+        _lib.dgq_oracle_bmm_s8.restype = ctypes.c_long
         _lib.dgq_oracle_expand_zp.restype = ctypes.c_long
         _lib.dgq_oracle_pack_zp.restype = ctypes.c_long
         _lib.dgq_oracle_quant_act_static.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_float, ctypes.c_void_p]
@@ -117,6 +118,33 @@ def gemm_i32(xq, ws8):
     acc = np.empty((M, N), np.int32)
     wrapped = _L().dgq_oracle_gemm_i32(_p(xq), _p(ws8), M, N, K, _p(acc))
     return acc, int(wrapped)
+
+
+def bmm_s8_acc(a, b):
+    """Batched INT8 product for attention (Section 4.1 "Implementation"): acc[i] = a[i] @ b[i].T in INT32.
+
+    a: int8 [B, M, K], b: int8 [B, N, K] (both with the reduction index last).
+    Returns (acc int32 [B, M, N], n_outputs_that_would_wrap_int32)."""
+    a = _c(a, np.int8)
+    b = _c(b, np.int8)
+    B, M, K = a.shape
+    B2, N, K2 = b.shape
+    assert B == B2 and K == K2
+    acc = np.empty((B, M, N), np.int32)
+    wrapped = _L().dgq_oracle_bmm_s8(_p(a), _p(b), B, M, N, K, _p(acc))
+    return acc, int(wrapped)
+
+
+def bmm_s8(a, b, sa, sb):
+    """out[i][m][n] = fp16((sa[i][m] * sb[i][n]) * acc[i][m][n]): the batched product with the scale epilogue of
+    Eq. 2, the second operand's per-token scale in the place of the channel scale.  Returns (out fp16, acc int32)."""
+    acc, wrapped = bmm_s8_acc(a, b)
+    if wrapped:
+        raise OverflowError("%d INT32 accumulators would wrap" % wrapped)
+    sa = _c(sa, np.float32)
+    sb = _c(sb, np.float32)
+    out = np.stack([epilogue(acc[i], sa[i], sb[i]) for i in range(acc.shape[0])])
+    return out, acc
 
 
 def epilogue(acc, sx, s1):

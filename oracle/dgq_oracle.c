@@ -20,7 +20,8 @@
  * through this file's own formulas (hand-written tiny cases, closed forms,
  * numpy int64 matmul, an fp64 group-wise "segmented GEMM"; for the grid search:
  * exactly representable inputs that it must recover, a brute-force check of the
- * Eq. 4 interval, the min-max special case, error bounds).  The statistical
+ * Eq. 4 interval, the min-max special case, error bounds; for the batched product: a hand-worked
+ * case, numpy int64, one-hot operands, and the already pinned GEMM on a transposed operand).  The statistical
  * accuracy of the RTN and grid-search quantizers against the paper's perplexity
  * tables is parity unpinned (needs the trained models and datasets).
  */
@@ -176,6 +177,39 @@ long dgq_oracle_gemm_i32(const int8_t *xq, const int8_t *ws8, int M, int N, int 
             }
             if ((int64_t)a32 != a64) ++wrapped;
             acc[(size_t)m * N + n] = a32;
+        }
+    }
+    return wrapped;
+}
+
+/*
+ * Batched INT8 x INT8 -> INT32 matrix product for attention (Section 4.1, "Implementation": the
+ * attention products run as INT8 batched matrix multiplications; the paper gives no more than
+ * that).  Both operands have the reduction index contiguous:
+ *     acc[b][m][n] = sum_k A[b][m][k] * B[b][n][k]
+ * (scores: A = Q, B = K; context: A = P, B = V transposed), one unbroken INT32 sum over all of K
+ * with a 64-bit shadow sum; returns the number of outputs that would wrap.  The scale epilogue
+ * is the one of Eq. 2 (dgq_oracle_epilogue per batch) with the two operands' per-token scales.
+ */
+long dgq_oracle_bmm_s8(const int8_t *A, const int8_t *B, int batch, int M, int N, int K, int32_t *acc)
+{
+    long wrapped = 0;
+#pragma omp parallel for schedule(static) reduction(+ : wrapped) collapse(2)
+    for (int b = 0; b < batch; ++b) {
+        for (int m = 0; m < M; ++m) {
+            const int8_t *a = A + ((size_t)b * M + m) * K;
+            for (int n = 0; n < N; ++n) {
+                const int8_t *w = B + ((size_t)b * N + n) * K;
+                int32_t a32 = 0;
+                int64_t a64 = 0;
+                for (int k = 0; k < K; ++k) {
+                    const int p = (int)a[k] * (int)w[k];
+                    a32 = (int32_t)((uint32_t)a32 + (uint32_t)p);
+                    a64 += p;
+                }
+                if ((int64_t)a32 != a64) ++wrapped;
+                acc[((size_t)b * M + m) * N + n] = a32;
+            }
         }
     }
     return wrapped;

@@ -419,3 +419,55 @@ def test_rmsnorm_hand_values_and_numpy_fp64():
     # numpy's pairwise mean and x/sqrt differ from 1/sqrt and a running sum in the last fp64 bits only:
     # after two roundings at most a handful of ties can differ, and on this data none does
     assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+
+
+# ---------------------------------------------------------------- batched INT8 product for attention (Section 4.1)
+def test_bmm_hand_worked_case():
+    """Two batches of a 2 x 3 by 2 x 3 product, sums written out by hand: batch 0 row 0 = (1, -2, 3) against
+    (4, 5, -6) -> 4 - 10 - 18 = -24 and against (-1, 0, 2) -> -1 + 0 + 6 = 5; a swapped operand, a product along
+    the wrong axis or batches mixed up change at least one of the eight numbers."""
+    a = np.array([[[1, -2, 3], [0, 7, -1]], [[127, -127, 1], [2, 2, 2]]], np.int8)
+    b = np.array([[[4, 5, -6], [-1, 0, 2]], [[127, 127, -128], [-3, 4, 5]]], np.int8)
+    acc, wrapped = oracle.bmm_s8_acc(a, b)
+    assert wrapped == 0
+    assert acc.tolist() == [[[-24, 5], [41, -2]], [[-128, -884], [252, 12]]]
+    # scale epilogue: (sa[m] * sb[n]) * acc with power-of-two scales is exact
+    sa = np.array([[0.5, 2.0], [1.0, 0.25]], np.float32)
+    sb = np.array([[1.0, 4.0], [0.125, 2.0]], np.float32)
+    out, _ = oracle.bmm_s8(a, b, sa, sb)
+    assert out.dtype == np.float16
+    assert out.tolist() == [[[-12.0, 10.0], [82.0, -16.0]], [[-16.0, -1768.0], [7.875, 6.0]]]
+
+
+def test_bmm_against_numpy_int64_one_hot_and_the_pinned_gemm():
+    rng = np.random.default_rng(5)
+    B, M, N, K = 3, 17, 29, 200
+    a = rng.integers(-128, 128, (B, M, K), dtype=np.int8)
+    b = rng.integers(-128, 128, (B, N, K), dtype=np.int8)
+    acc, wrapped = oracle.bmm_s8_acc(a, b)
+    assert wrapped == 0
+    assert np.array_equal(acc.astype(np.int64), np.einsum("bmk,bnk->bmn", a.astype(np.int64), b.astype(np.int64)))
+    # each batch is the (separately pinned) GEMM of Eq. 2 on the transposed second operand
+    for i in range(B):
+        g, _ = oracle.gemm_i32(a[i], np.ascontiguousarray(b[i].T))
+        assert np.array_equal(acc[i], g)
+    # swapping the operands transposes the result; permuting the batches permutes it
+    acc_t, _ = oracle.bmm_s8_acc(b, a)
+    assert np.array_equal(acc_t, acc.transpose(0, 2, 1))
+    perm = [2, 0, 1]
+    assert np.array_equal(oracle.bmm_s8_acc(a[perm], b[perm])[0], acc[perm])
+    # one-hot rows of the second operand read out columns of the first
+    e = np.zeros((B, 4, K), np.int8)
+    ks = [3, 77, 199, 0]
+    for j, k in enumerate(ks):
+        e[:, j, k] = 1
+    assert np.array_equal(oracle.bmm_s8_acc(a, e)[0], a[:, :, ks].astype(np.int32))
+
+
+def test_bmm_reports_int32_wrap():
+    K = 140000                                         # 128 * 128 * K > 2^31
+    a = np.full((1, 1, K), -128, np.int8)
+    acc, wrapped = oracle.bmm_s8_acc(a, a)
+    assert wrapped == 1
+    with pytest.raises(OverflowError):
+        oracle.bmm_s8(a, a, np.ones((1, 1), np.float32), np.ones((1, 1), np.float32))
