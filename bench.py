@@ -453,6 +453,49 @@ class Bench:
             log("probe_mfma failed: %r" % (e,))
             return None
 
+    # ---------------- batched INT8 products of attention (Section 4.1 "Implementation") -----
+    def attention_bmm(self):
+        """Scores Q K^T and context P V of one LLaMA-7B layer (32 heads of 128 channels) at prefill (2048 tokens)
+        and decode (one token against 2048 cached ones); an fp16 torch.bmm of the same shape beside each."""
+        torch, dgq = self.torch, self.dgq
+        H, D, S = 32, 128, 2048
+        gen = torch.Generator(device=self.dev)
+        gen.manual_seed(7)
+        out = []
+        for label, M, N, K in (("scores_prefill", S, S, D), ("context_prefill", S, D, S),
+                               ("scores_decode", 1, S, D), ("context_decode", 1, D, S)):
+            a = torch.randint(-127, 128, (H, M, K), dtype=torch.int8, device=self.dev, generator=gen)
+            b = torch.randint(-127, 128, (H, N, K), dtype=torch.int8, device=self.dev, generator=gen)
+            sa = torch.full((H, M), 1e-2, dtype=torch.float32, device=self.dev)
+            sb = torch.full((H, N), 1e-3, dtype=torch.float32, device=self.dev)
+            o = torch.empty((H, M, N), dtype=torch.float16, device=self.dev)
+            ah, bh = a.half(), b.half().transpose(1, 2).contiguous()
+
+            def t(fn, reps):
+                fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return 1e-3 * e0.elapsed_time(e1) / reps
+            gr = self.make_graph(lambda: [dgq.bmm_s8(a, b, sa, sb, o) for _ in range(8)])
+            sec = t(gr.replay, 5) / 8
+            fsec = t(lambda: torch.bmm(ah, bh), 10)
+            nbytes = H * (M * K + N * K + 4 * M + 4 * N + 2 * M * N)
+            ops = 2 * H * M * N * K
+            bound = "hbm" if ops / nbytes < RIDGE_OPS_PER_BYTE else "mfma"
+            row = {"product": label, "batch": H, "M": M, "N": N, "K": K, "bound": bound, "us": round(sec * 1e6, 2),
+                   "GBps": round(nbytes / sec / 1e9, 1), "hbm_frac": round(nbytes / sec / 1e9 / HBM_PEAK_GBS, 4),
+                   "TOPS": round(ops / sec / 1e12, 2), "mfma_frac": round(ops / sec / 1e12 / INT8_PEAK_TOPS, 4),
+                   "fp16_bmm_us": round(fsec * 1e6, 2), "speedup_vs_fp16_bmm": round(fsec / sec, 2)}
+            out.append(row)
+            log("  bmm %-16s %9.2f us  %7.1f GB/s (%5.1f%% HBM)  %8.2f TOP/s  fp16 bmm %9.2f us  x%.2f" %
+                (label, row["us"], row["GBps"], 100 * row["hbm_frac"], row["TOPS"], row["fp16_bmm_us"], row["speedup_vs_fp16_bmm"]))
+        return out
+
     # ---------------- CPU baseline: the oracle on the same workload ---------------------
     def cpu_baseline(self, workload, acts, static_scale):
         import oracle
@@ -526,6 +569,7 @@ def main():
                          "linear (one call; 'separate': dgq_rmsnorm_quant_act then dgq_linear_a8w4), silu*mul fused "
                          "with the quantizer, down linear")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bmm", action="store_true", help="skip the batched INT8 attention products")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -554,6 +598,13 @@ def main():
         log("calibration copy of %d bytes done" % src.numel())
         del src, dst
 
+    bmm = None
+    if not args.no_bmm and not args.mlp_block:
+        try:
+            bmm = bench.attention_bmm()
+        except Exception as e:      # a side measurement must not take the headline down
+            log("attention_bmm failed: %r" % (e,))
+
     sweep = []
     if not args.no_sweep:
         # the other benchmark configurations, largest model last; weights of a model that is done are freed
@@ -579,6 +630,7 @@ def main():
         "regimes": head["regimes"],
         "workloads": [{k: r[k] for k in ("workload", "value", "unit", "ms_per_step", "steps", "warmup", "tops", "config",
                                          "roofline", "regimes", "a16_fp16_gemm_ms_per_step", "breakdown")} for r in sweep],
+        "attention_bmm": bmm,
         "a16_fp16_gemm_ms_per_step": head["a16_fp16_gemm_ms_per_step"],
         "weight_quantization_rel_sq_error": head["weight_quantization_rel_sq_error"],
         "measured_read_bandwidth": head.get("measured_read_bandwidth"),

@@ -368,6 +368,27 @@ DGQ_API dgq_status dgq_rmsnorm_quant_linear_a8w4_zp(const uint16_t *x, const uin
                                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Batched INT8 matrix product for attention.  Section 4.1 ("Implementation") runs the attention
+ * products as INT8 batched matrix multiplications and says no more; taken here as: both operands
+ * INT8 with the reduction index contiguous, one INT32 sum over all of K, and the scale epilogue of
+ * Eq. 2 (first and third line) with the second operand's per-token scale in the place of the
+ * channel scale, rounded once to fp16:
+ *   out[i][m][n] = fp16( (sa[i][m] * sb[i][n]) * (float) sum_k a[i][m][k] * b[i][n][k] )
+ * (attention scores: a = Q, b = K; context: a = P, b = V transposed).
+ *   a    in  [batch][M][K] int8;   b  in  [batch][N][K] int8
+ *   sa   in  [batch][M] float, sb in [batch][N] float; either may be NULL (= all ones); a static
+ *        tensor-wise scale is an array filled with that scale
+ *   out  out [batch][M][N] fp16 (raw bits)
+ * Shape rules: 1 <= batch <= 65535, M, N >= 1 (any values; 16-byte stores are used when N % 8 == 0),
+ * K % 16 == 0, 16 <= K <= 65536 (INT32 sums cannot wrap).  No workspace.
+ * dgq_bmm_s8_acc is the test hook that stores the raw INT32 sums [batch][M][N].
+ */
+DGQ_API dgq_status dgq_bmm_s8(const int8_t *a, const int8_t *b, const float *sa, const float *sb, uint16_t *out,
+                      int batch, int M, int N, int K, void *stream);
+DGQ_API dgq_status dgq_bmm_s8_acc(const int8_t *a, const int8_t *b, int32_t *acc_out, int batch, int M, int N, int K,
+                          void *stream);
+
+/*
  * Measurement aid (host function, nothing launched): writes into buf (at least 96 bytes)
  * the name, with template arguments, of the GEMM kernel that dgq_linear_a8w4 would launch
  * for this problem, e.g. "linear_decode_kernel<2, 2, 128, false, false>".  Profiler output can be matched to it.

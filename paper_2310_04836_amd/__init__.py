@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "linear_acc_workspace_bytes", "linear_a8w4_noalloc", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
+    "linear_acc_workspace_bytes", "linear_a8w4_noalloc", "bmm_s8", "bmm_s8_acc", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -65,6 +65,10 @@ def _load() -> ctypes.CDLL:
     L.dgq_unpack_weights_zp.argtypes = [vp, vp, i, i, i, vp, vp]
     L.dgq_linear_a8w4_zp.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dgq_linear_a8w4_zp_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+    L.dgq_bmm_s8.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.dgq_bmm_s8.restype = i
+    L.dgq_bmm_s8_acc.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    L.dgq_bmm_s8_acc.restype = i
     L.dgq_probe_read.argtypes = [vp, sz, vp, i, vp]
     L.dgq_probe_mfma.argtypes = [vp, sz, i, vp, i, vp]
     L.dgq_linear_plan.argtypes = [i, i, i, i, ctypes.c_char_p, sz]
@@ -388,6 +392,37 @@ def rmsnorm_quant_linear_a8w4(x: torch.Tensor, gamma: torch.Tensor, eps: float, 
     _check(fn(_ptr(x), _ptr(gamma), eps, _ptr(pw.qweight), _ptr(pw.scales), _ptr(pw.s1), _ptr(out), _ptr(sx_out),
               M, pw.N, K, pw.group, _ptr(workspace), wsb, _stream()), "dgq_rmsnorm_quant_linear_a8w4")
     return out
+
+
+def bmm_s8(a: torch.Tensor, b: torch.Tensor, sa: torch.Tensor = None, sb: torch.Tensor = None,
+           out: torch.Tensor = None) -> torch.Tensor:
+    """dgq_bmm_s8: fp16 [B,M,N] = (sa x sb) * (a @ b^T) per batch; a int8 [B,M,K], b int8 [B,N,K], scales float32."""
+    _dev(a, torch.int8, "a"); _dev(b, torch.int8, "b")
+    B, M, K = a.shape
+    B2, N, K2 = b.shape
+    if B != B2 or K != K2:
+        raise ValueError("a is %s but b is %s" % (tuple(a.shape), tuple(b.shape)))
+    for t, n, name in ((sa, M, "sa"), (sb, N, "sb")):
+        if t is not None:
+            _dev(t, torch.float32, name)
+            if tuple(t.shape) != (B, n):
+                raise ValueError("%s must be [batch, %d]" % (name, n))
+    if out is None:
+        out = torch.empty((B, M, N), dtype=torch.float16, device=a.device)
+    _check(lib.dgq_bmm_s8(_ptr(a), _ptr(b), _ptr(sa), _ptr(sb), _ptr(out), B, M, N, K, _stream()), "dgq_bmm_s8")
+    return out
+
+
+def bmm_s8_acc(a: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
+    """dgq_bmm_s8_acc: raw INT32 sums [B,M,N] of the same kernel (test hook)."""
+    _dev(a, torch.int8, "a"); _dev(b, torch.int8, "b")
+    B, M, K = a.shape
+    B2, N, K2 = b.shape
+    if B != B2 or K != K2:
+        raise ValueError("a is %s but b is %s" % (tuple(a.shape), tuple(b.shape)))
+    acc = torch.empty((B, M, N), dtype=torch.int32, device=a.device)
+    _check(lib.dgq_bmm_s8_acc(_ptr(a), _ptr(b), _ptr(acc), B, M, N, K, _stream()), "dgq_bmm_s8_acc")
+    return acc
 
 
 def quant_linear_plan(M: int, N: int, K: int, group: int) -> str:

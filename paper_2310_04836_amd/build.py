@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libdgq.so")
 
-SOURCES = ["api.hip", "quant_act.hip", "weights.hip", "quantize_grid.hip", "smooth.hip", "linear_decode.hip", "linear_stream.hip", "linear_tiled.hip", "probe.hip"]
+SOURCES = ["api.hip", "quant_act.hip", "weights.hip", "quantize_grid.hip", "smooth.hip", "linear_decode.hip", "linear_stream.hip", "linear_tiled.hip", "bmm.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -506,6 +506,33 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
     return DGQ_OK;
 }
 
+static dgq_status bmm_check(const void *a, const void *b, int batch, int M, int N, int K)
+{
+    if (!a || !b) return DGQ_ERR_NULL;
+    // INT32 sums cannot wrap: 128 * 128 * K < 2^31; the batch is a grid dimension
+    if (batch < 1 || batch > 65535 || M < 1 || N < 1 || K < 16 || K > 65536 || (K % 16) != 0) return DGQ_ERR_SHAPE;
+    if ((long long)M > (1LL << 24) || (long long)N > (1LL << 24)) return DGQ_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(b)) return DGQ_ERR_ALIGN;
+    return DGQ_OK;
+}
+
+dgq_status dgq_bmm_s8(const int8_t *a, const int8_t *b, const float *sa, const float *sb, uint16_t *out, int batch,
+                      int M, int N, int K, void *stream)
+{
+    if (!out) return DGQ_ERR_NULL;
+    if (dgq_status st = bmm_check(a, b, batch, M, N, K)) return st;
+    if (!aligned16(out) || (reinterpret_cast<uintptr_t>(sa) & 3u) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_bmm_s8(a, b, sa, sb, out, nullptr, batch, M, N, K, static_cast<hipStream_t>(stream)));
+}
+
+dgq_status dgq_bmm_s8_acc(const int8_t *a, const int8_t *b, int32_t *acc_out, int batch, int M, int N, int K, void *stream)
+{
+    if (!acc_out) return DGQ_ERR_NULL;
+    if (dgq_status st = bmm_check(a, b, batch, M, N, K)) return st;
+    if (!aligned16(acc_out)) return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_bmm_s8(a, b, nullptr, nullptr, nullptr, acc_out, batch, M, N, K, static_cast<hipStream_t>(stream)));
+}
+
 dgq_status dgq_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, void *stream)
 {
     if (!src || !sink) return DGQ_ERR_NULL;

@@ -317,6 +317,9 @@ TiledPlan tiled_plan(int M, int N, int K);
 size_t tiled_workspace_bytes(int M, int N, int K);
 hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st);
 
+hipError_t launch_bmm_s8(const int8_t *A, const int8_t *B, const float *sa, const float *sb, uint16_t *out, int32_t *acc_out,
+                         int batch, int M, int N, int K, hipStream_t st);
+
 hipError_t launch_probe_read(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t st);
 hipError_t launch_probe_mfma(const void *operands, size_t bytes, int iters, uint32_t *sink, int workgroups, hipStream_t st);
 

@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 34 and len(set(names)) == 34
+    assert len(names) == 36 and len(set(names)) == 36
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -117,6 +117,15 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_linear_a8w4_noalloc(good, good, odd, good, good, good, 1, 16, 128, 128, None) == -3
     assert dgq.linear_workspace_bytes(1, 1048576, 16384, 128) > (40 << 20)     # K split of the decode kernel over 2048 workgroup columns
     assert L.dgq_linear_a8w4_noalloc(good, good, good, good, good, good, 1, 1048576, 16384, 128, None) == -5
+    # batched INT8 product
+    assert L.dgq_bmm_s8(good, None, None, None, good, 1, 8, 8, 128, None) == -1
+    assert L.dgq_bmm_s8(good, good, None, None, good, 1, 8, 8, 120, None) == -2       # K % 16
+    assert L.dgq_bmm_s8(good, good, None, None, good, 0, 8, 8, 128, None) == -2
+    assert L.dgq_bmm_s8(good, good, None, None, good, 70000, 8, 8, 128, None) == -2
+    assert L.dgq_bmm_s8(good, good, None, None, good, 1, 8, 8, 65536 + 16, None) == -2
+    assert L.dgq_bmm_s8(good, odd, None, None, good, 1, 8, 8, 128, None) == -3
+    assert L.dgq_bmm_s8(good, good, 0x10002, None, good, 1, 8, 8, 128, None) == -3
+    assert L.dgq_bmm_s8_acc(good, good, None, 1, 8, 8, 128, None) == -1
     # quantizer + linear as one call
     n = ctypes.c_size_t(7)
     assert L.dgq_quant_linear_workspace_bytes(4, 4096, 11008, 128, ctypes.byref(n)) == 0 and n.value == 0
