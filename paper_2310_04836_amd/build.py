@@ -9,13 +9,14 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-OBJ = os.path.join(PKG, "_build")
-LIB = os.path.join(PKG, "libdgq.so")
+OBJ = os.environ.get("DGQ_BUILD_DIR") or os.path.join(PKG, "_build")
+# DGQ_LIBRARY: load (and build into) another file than the in-tree library
+LIB = os.environ.get("DGQ_LIBRARY") or os.path.join(PKG, "libdgq.so")
 
 SOURCES = ["api.hip", "quant_act.hip", "weights.hip", "quantize_grid.hip", "smooth.hip", "linear_decode.hip", "linear_stream.hip", "linear_tiled.hip", "bmm.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = [
+FLAGS = os.environ.get("DGQ_EXTRA_FLAGS", "").split() + [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

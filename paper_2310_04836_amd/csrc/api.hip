@@ -474,7 +474,8 @@ dgq_status dgq_quant_linear_plan(int M, int N, int K, int group, char *buf, size
     if (dgq_status st = check_shape(N, K, group)) return st;
     if (quantizes_in_kernel(M, K, kPathAuto)) {
         const dgq::DecodePlan p = dgq::decode_plan(K);
-        std::snprintf(buf, buf_bytes, "quant_linear_decode_kernel<%d, %d, %d>", p.spw, p.pf, group);
+        std::snprintf(buf, buf_bytes, "quant_linear_decode_%skernel<%d, %d, %d>", dgq::decode_streams_weights(N, K) ? "nt_" : "",
+                      p.spw, p.pf, group);
         return DGQ_OK;
     }
     return dgq_linear_plan(M, N, K, group, buf, buf_bytes);
@@ -488,8 +489,12 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
     switch (pick_path(M, kPathAuto)) {
     case kPathStream: {
         const dgq::DecodePlan p = dgq::decode_plan(K);
-        std::snprintf(buf, buf_bytes, "linear_decode_kernel<%d, %d, %d, false, %s>", p.spw, p.pf, group,
-                      p.ksplit > 1 ? "true" : "false");
+        if (dgq::decode_streams_weights(N, K))
+            std::snprintf(buf, buf_bytes, "linear_decode_nt_kernel<%d, %d, %d, %s>", p.spw, p.pf, group,
+                          p.ksplit > 1 ? "true" : "false");
+        else
+            std::snprintf(buf, buf_bytes, "linear_decode_kernel<%d, %d, %d, false, %s>", p.spw, p.pf, group,
+                          p.ksplit > 1 ? "true" : "false");
         break;
     }
     case kPathStreamGeneric: {

@@ -298,6 +298,7 @@ struct DecodePlan {
     int ksplit;  // workgroups sharing one column tile's K
 };
 DecodePlan decode_plan(int K);
+bool decode_streams_weights(int N, int K);   // large layer: the decode kernel reads its weights with streaming loads
 size_t decode_workspace_bytes(int M, int N, int K);
 struct StreamPlan {
     int mtiles;  // 16-token tiles (template MT)

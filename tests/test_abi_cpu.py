@@ -162,7 +162,8 @@ def test_quant_linear_plan_names(dgq):
     assert dgq.quant_linear_plan(5, 8192, 8192, 64) == "quant_linear_decode_kernel<4, 1, 64>"
     assert dgq.quant_linear_plan(6, 8192, 8192, 64) == "linear_decode_kernel<4, 1, 64, false, false>"   # 6 * 8208 bytes
     assert dgq.quant_linear_plan(16, 4096, 4096, 128) == "linear_decode_kernel<2, 2, 128, false, false>"
-    assert dgq.quant_linear_plan(2, 8192, 22016, 128) == "linear_decode_kernel<6, 1, 128, false, true>"  # K split
+    assert dgq.quant_linear_plan(2, 8192, 22016, 128) == "linear_decode_nt_kernel<6, 1, 128, true>"  # K split; 90 MB of weights: streaming loads
+    assert dgq.quant_linear_plan(1, 24576, 8192, 128) == "quant_linear_decode_nt_kernel<4, 1, 128>"
     assert dgq.quant_linear_plan(17, 4096, 4096, 128) == dgq.linear_plan(17, 4096, 4096, 128)
     assert dgq.quant_linear_workspace_bytes(4, 12288, 4096, 128) == 0
 
@@ -170,7 +171,8 @@ def test_quant_linear_plan_names(dgq):
 def test_linear_plan_names(dgq):
     assert dgq.linear_plan(16, 22016, 4096, 128) == "linear_decode_kernel<2, 2, 128, false, false>"
     assert dgq.linear_plan(1, 4096, 11008, 128) == "linear_decode_kernel<6, 1, 128, false, false>"
-    assert dgq.linear_plan(8, 8192, 22016, 64) == "linear_decode_kernel<6, 1, 64, false, true>"
+    assert dgq.linear_plan(8, 8192, 22016, 64) == "linear_decode_nt_kernel<6, 1, 64, true>"      # 64 MB of weights and more: streaming loads
+    assert dgq.linear_plan(8, 512, 22016, 64) == "linear_decode_kernel<6, 1, 64, false, true>"
     # 16 < M <= 64: 64-token tiles; K split over several workgroups per tile where the tiles alone leave CUs idle
     assert dgq.linear_plan(64, 8192, 8192, 128) == "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"
     assert dgq.linear_workspace_bytes(64, 8192, 8192, 128) == 65536 + 32 * 4 * 64 * 256 * 4      # counters + 32 tiles x 4 parts
