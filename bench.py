@@ -11,10 +11,12 @@ steps rotate through, so that the weights of a launch are not left in the 256 MB
 cache by the previous one.
 
 The headline (`value`, `ms_per_step`, `roofline`, `cpu_baseline`) is the workload --workload
-names (default: the LLaMA-7B decode linears).  Unless --no-sweep is given, every other
-benchmark configuration (7B prefill, 13B, 65B with both group sizes) is then timed the same
-way with fewer steps and reported under `workloads`, each with one roofline record per regime
-(weight-stream-bound launches against 8 TB/s, matrix-core-bound launches against 5.0 POP/s).
+names (default: the LLaMA-65B single-layer sweep, M in {1, 8, 64, 512, 2048}, the one benchmark
+configuration that spans both the weight-stream-bound and the matrix-core-bound regime).  Unless
+--no-sweep is given, every other benchmark configuration (7B decode, 7B prefill, 13B, 65B with
+group size 64) is then timed the same way with fewer steps and reported under `workloads`.  Every
+workload carries one roofline record per regime (weight-stream-bound launches against 8 TB/s,
+matrix-core-bound launches against 5.0 POP/s).
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -515,7 +517,9 @@ class Bench:
                     if args.format == "zp":
                         ncol = min(ncol, 512)      # the oracle's (untimed) grid search is slow
                     if (name, ncol) not in qcache:
-                        Wn = self.wl.weights(K, N, seed)[:, :ncol]
+                        # the same synthetic weights the GPU leg quantized (kept on the device): no second draw
+                        Wd = self._wdev.get((size, name))
+                        Wn = (Wd[:, :ncol].cpu().numpy() if Wd is not None else self.wl.weights(K, N, seed)[:, :ncol])
                         qcache[(name, ncol)] = (oracle.quantize_weights_grid(Wn, g) if args.format == "zp"
                                                 else oracle.quantize_weights_rtn(Wn, g))
                     x = acts[(M, name)].cpu().numpy()
@@ -548,8 +552,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS),
-                    help="the workload of the headline figures")
+    ap.add_argument("--workload", default="llama65b_g128", choices=sorted(WORKLOADS),
+                    help="the workload of the headline figures (default: the LLaMA-65B sweep, the one benchmark "
+                         "configuration that spans the metric's whole range of M = 1 ... 2048)")
     ap.add_argument("--no-sweep", action="store_true",
                     help="time the headline workload only (default: every other benchmark configuration too, "
                          "reported under 'workloads')")

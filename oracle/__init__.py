@@ -47,6 +47,10 @@ def _L():
         _lib.dgq_oracle_quant_act_static.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_float, ctypes.c_void_p]
         _lib.dgq_oracle_smooth_scales.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
         _lib.dgq_oracle_rmsnorm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+        _lib.dgq_oracle_quantize_grid_act.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                      ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                                                      ctypes.c_void_p, ctypes.c_void_p]
         _lib.dgq_oracle_quantize_grid.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                   ctypes.c_int, ctypes.c_float, ctypes.c_void_p,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -250,6 +254,31 @@ def quantize_weights_grid(W, group: int, n_alpha: int = 51, step: float = 0.01):
     s2 = np.empty((K // group, N), np.uint8)
     s1 = np.empty(N, np.float32)
     _L().dgq_oracle_quantize_grid(_p(Wf), K, N, group, n_alpha, ctypes.c_float(step), _p(u4), _p(zp), _p(s2), _p(s1))
+    return u4, zp, s2, s1
+
+
+def dequant_act(x):
+    """X^ of Eq. 3: the per-token INT8 quantization of x, dequantized (fp32 product sx * xq)."""
+    xq, sx = quant_act(x)
+    return (sx[:, None] * xq.astype(np.float32)).astype(np.float32)
+
+
+def quantize_weights_grid_act(W, X, group: int, n_alpha: int = 51, step: float = 0.01, Xh=None):
+    """Two-phase grid search with the activation-weighted objectives of Section 3.3 (Eq. 3; objective of Eq. 5) on
+    calibration activations X [M, K]; Xh defaults to dequant_act(X).
+
+    Returns (u4 uint8 [K,N], zp uint8 [K/group,N], s2 uint8 [K/group,N], s1 float32 [N])."""
+    Wf, Xf = _c(W, np.float32), _c(X, np.float32)
+    Xhf = dequant_act(X) if Xh is None else _c(Xh, np.float32)
+    K, N = Wf.shape
+    M = Xf.shape[0]
+    assert K % group == 0 and n_alpha >= 1 and Xf.shape == (M, K) and Xhf.shape == (M, K)
+    u4 = np.empty((K, N), np.uint8)
+    zp = np.empty((K // group, N), np.uint8)
+    s2 = np.empty((K // group, N), np.uint8)
+    s1 = np.empty(N, np.float32)
+    _L().dgq_oracle_quantize_grid_act(_p(Wf), _p(Xf), _p(Xhf), M, K, N, group, n_alpha, ctypes.c_float(step),
+                                      _p(u4), _p(zp), _p(s2), _p(s1))
     return u4, zp, s2, s1
 
 

@@ -471,6 +471,133 @@ void dgq_oracle_quantize_grid(const float *W, int K, int N, int g, int n_alpha, 
 }
 
 /*
+ * Two-phase grid search with the activation-weighted objectives of Section 3.3 (Eq. 3 for
+ * phase 1, the objective printed with Eq. 5 for phase 2), on calibration activations X [M][K]
+ * and their dequantized form Xh [M][K] (the per-token INT8 quantization of X times its scale):
+ *
+ *   phase 1, group j of column n:   err = sum_m ( X_j[m,:] w_j  -  Xh_j[m,:] Q(w_j) )^2
+ *   phase 2, column n:              err = sum_m ( X[m,:] w      -  Xh[m,:]  Q(w)   )^2
+ *
+ * where X_j, w_j are the K-slice of group j.  Everything else (alpha grid, scale and zero point
+ * of a candidate, S2, the Eq. 4 clip, first minimum wins, zero groups and columns) is as in
+ * dgq_oracle_quantize_grid.  fp32; each of the two products of a token is summed on its own in
+ * increasing k, then subtracted; the squares are added in increasing m.
+ */
+static float weighted_err(const float *Xh, int M, int K, int k0, int k1, const float *xw, const float *wq)
+{
+    float err = 0.0f;
+    for (int m = 0; m < M; ++m) {
+        float t = 0.0f;
+        for (int k = k0; k < k1; ++k) t = t + Xh[(size_t)m * K + k] * wq[k - k0];
+        const float d = xw[m] - t;
+        err = err + d * d;
+    }
+    return err;
+}
+
+void dgq_oracle_quantize_grid_act(const float *W, const float *X, const float *Xh, int M, int K, int N, int g,
+                                  int n_alpha, float step, uint8_t *u4, uint8_t *zp, uint8_t *s2, float *s1)
+{
+    const int ng = K / g;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int n = 0; n < N; ++n) {
+        float *Sp = (float *)malloc(sizeof(float) * (size_t)ng);
+        float *xw = (float *)malloc(sizeof(float) * (size_t)M);     /* X w of the slice in hand, per token */
+        float *wq = (float *)malloc(sizeof(float) * (size_t)K);     /* dequantized candidate */
+        /* ---- phase 1 ---- */
+        for (int j = 0; j < ng; ++j) {
+            const int k0 = j * g, k1 = (j + 1) * g;
+            float lo = 0.0f, hi = 0.0f;
+            for (int k = k0; k < k1; ++k) {
+                const float w = W[(size_t)k * N + n];
+                if (w < lo) lo = w;
+                if (w > hi) hi = w;
+            }
+            float best_err = 0.0f, best_s = 0.0f;
+            int best_zp = 0, have = 0;
+            if (hi - lo > 0.0f) {
+                for (int m = 0; m < M; ++m) {
+                    float t = 0.0f;
+                    for (int k = k0; k < k1; ++k) t = t + X[(size_t)m * K + k] * W[(size_t)k * N + n];
+                    xw[m] = t;
+                }
+                for (int i = 0; i < n_alpha; ++i) {
+                    const float alpha = 1.0f - (float)i * step;
+                    const float s = (alpha * (hi - lo)) / 15.0f;
+                    const float z = clampf(rintf(-(alpha * lo) / s), 0.0f, 15.0f);
+                    for (int k = k0; k < k1; ++k) {
+                        const float u = clampf(rintf(W[(size_t)k * N + n] / s) + z, 0.0f, 15.0f);
+                        wq[k - k0] = (u - z) * s;
+                    }
+                    const float err = weighted_err(Xh, M, K, k0, k1, xw, wq);
+                    if (!have || err < best_err) {
+                        have = 1;
+                        best_err = err;
+                        best_s = s;
+                        best_zp = (int)z;
+                    }
+                }
+            }
+            Sp[j] = best_s;
+            zp[(size_t)j * N + n] = (uint8_t)best_zp;
+        }
+        /* ---- phase 2 ---- */
+        float smax = 0.0f;
+        for (int j = 0; j < ng; ++j)
+            if (Sp[j] > smax) smax = Sp[j];
+        if (!(smax > 0.0f)) {
+            s1[n] = 1.0f;
+            for (int j = 0; j < ng; ++j) s2[(size_t)j * N + n] = 1, zp[(size_t)j * N + n] = 0;
+            for (int k = 0; k < K; ++k) u4[(size_t)k * N + n] = 0;
+            free(Sp), free(xw), free(wq);
+            continue;
+        }
+        for (int m = 0; m < M; ++m) {
+            float t = 0.0f;
+            for (int k = 0; k < K; ++k) t = t + X[(size_t)m * K + k] * W[(size_t)k * N + n];
+            xw[m] = t;
+        }
+        float best_err = 0.0f, best_s1 = 0.0f;
+        int have = 0;
+        for (int i = 0; i < n_alpha; ++i) {
+            const float alpha = 1.0f - (float)i * step;
+            const float c1 = (alpha * smax) / 15.0f;
+            for (int j = 0; j < ng; ++j) {
+                const float q2 = clampf(rintf(Sp[j] / c1), 1.0f, 127.0f);
+                const float S = c1 * q2;
+                const int z = zp[(size_t)j * N + n];
+                int lo4, hi4;
+                dgq_oracle_clip_interval((int)q2, z, &lo4, &hi4);
+                for (int k = j * g; k < (j + 1) * g; ++k) {
+                    const float u = clampf(rintf(W[(size_t)k * N + n] / S) + (float)z, (float)lo4, (float)hi4);
+                    wq[k] = (u - (float)z) * S;
+                }
+            }
+            const float err = weighted_err(Xh, M, K, 0, K, xw, wq);
+            if (!have || err < best_err) {
+                have = 1;
+                best_err = err;
+                best_s1 = c1;
+            }
+        }
+        s1[n] = best_s1;
+        for (int j = 0; j < ng; ++j) {
+            const float q2 = clampf(rintf(Sp[j] / best_s1), 1.0f, 127.0f);
+            const float S = best_s1 * q2;
+            const int z = zp[(size_t)j * N + n];
+            int lo4, hi4;
+            dgq_oracle_clip_interval((int)q2, z, &lo4, &hi4);
+            s2[(size_t)j * N + n] = (uint8_t)q2;
+            for (int k = j * g; k < (j + 1) * g; ++k) {
+                const float u = clampf(rintf(W[(size_t)k * N + n] / S) + (float)z, (float)lo4, (float)hi4);
+                u4[(size_t)k * N + n] = (uint8_t)u;
+            }
+        }
+        free(Sp), free(xw), free(wq);
+    }
+}
+
+/*
  * Device format for the general operands, written from the layout text alone.
  *   qweight: as in dgq_oracle_pack, the stored nibble being W_u4 itself.
  *   scales_zp: two bytes per (group, column), the group scale S2 then the zero point, at

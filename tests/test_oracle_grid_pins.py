@@ -286,3 +286,57 @@ def test_smooth_apply_hand_values():
 
 def test_smooth_scales_without_activations_is_the_identity():
     assert (oracle.smooth_scales(np.zeros((2, 256), np.float32)) == 1).all()
+
+
+# ---------------------------------------------------------------- Eq. 3 with calibration activations
+def test_activation_weighted_search_with_identity_activations_is_the_weight_only_search():
+    """X = X^ = I makes ||X W - X^ Q(W)||^2 the weight-only objective term by term (the other products are
+    exact zeros), so the result must equal the already pinned weight-only search bit for bit."""
+    rng = np.random.default_rng(31)
+    K, N, g = 64, 24, 16
+    W = rng.normal(0, 0.02, (K, N)).astype(np.float32)
+    W[:, 3] = 0
+    W[16:32, 5] = 0
+    I = np.eye(K, dtype=np.float32)
+    a = oracle.quantize_weights_grid_act(W, I, g, n_alpha=21, step=0.025, Xh=I)
+    b = oracle.quantize_weights_grid(W, g, n_alpha=21, step=0.025)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_activation_weighted_search_hand_worked_flip():
+    """One group of two weights (1.0, 0.1), alpha in {1, 0.5}, one calibration token that only excites channel 1.
+    Weight-only: alpha = 1 keeps 1.0 exact (s = 1/15, u = (15, 2), error 0.0011 on the small weight) and wins.
+    With the activations only the small weight counts: alpha = 0.5 gives s = 1/30, u = (15, 3): 3/30 = 0.1 exactly,
+    error 0, and wins phase 1 (S' = 1/30).  Phase 2 at alpha = 1: s1 = S'/15 = 1/450, S2 = 15, the Eq. 4 clip of
+    S2 = 15, ZP = 0 is [0, 8], so u = (8, 3), error 0 again."""
+    W = np.array([[1.0], [0.1]], np.float32)
+    X = np.array([[0.0, 1.0]], np.float32)
+    u4, zp, s2, s1 = oracle.quantize_weights_grid_act(W, X, 2, n_alpha=2, step=0.5, Xh=X)
+    assert u4[:, 0].tolist() == [8, 3] and zp[0, 0] == 0 and s2[0, 0] == 15
+    assert abs(s1[0] * 450 - 1) < 1e-6
+    wu, wz, ws2, ws1 = oracle.quantize_weights_grid(W, 2, n_alpha=2, step=0.5)
+    assert abs(ws1[0] * 225 - 1) < 1e-6 and wu[:, 0].tolist() == [8, 2]     # the weight-only search keeps alpha = 1
+
+
+def test_activation_weighted_search_recovers_representable_weights_and_lowers_the_output_error():
+    rng = np.random.default_rng(32)
+    # weights that are exactly s1 * S2 * (u - ZP) (the construction of the weight-only pin): with X^ = X the
+    # error zero is reachable at alpha = 1 in both phases and nothing else can beat it, whatever X is
+    W, u4, zp, s2, s1 = _constructed(5)
+    K, N = W.shape
+    g, M = 64, 40
+    X = rng.normal(0, 1, (M, K)).astype(np.float32)
+    X[:, rng.choice(K, 4, replace=False)] *= 20
+    gu, gz, gs2, gs1 = oracle.quantize_weights_grid_act(W, X, g, n_alpha=11, step=0.05, Xh=X)
+    assert np.array_equal(gz, zp) and np.array_equal(gs2, s2) and np.array_equal(gs1, s1) and np.array_equal(gu, u4)
+    # on Gaussian weights the activation-weighted search gives a smaller output error than the weight-only one
+    Xh = oracle.dequant_act(X)
+    Wg = rng.normal(0, 0.02, (K, N)).astype(np.float32)
+    ref = X.astype(np.float64) @ Wg.astype(np.float64)
+
+    def out_err(res):
+        a4, az, a2, a1 = res
+        d = a1[None, :].astype(np.float64) * np.repeat(a2, g, 0) * (a4.astype(np.float64) - np.repeat(az, g, 0))
+        return np.linalg.norm(Xh.astype(np.float64) @ d - ref)
+    assert out_err(oracle.quantize_weights_grid_act(Wg, X, g)) < out_err(oracle.quantize_weights_grid(Wg, g))
