@@ -298,6 +298,27 @@ DGQ_API dgq_status dgq_quantize_weights_grid(const uint16_t *W, int K, int N, in
                                      uint8_t *w_u4, uint8_t *zp, uint8_t *s2, float *s1,
                                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same two-phase search with the activation-weighted objectives the paper states (Eq. 3 for
+ * phase 1, the objective printed with Eq. 5 for phase 2), on calibration activations:
+ *   phase 1, group j of column n:  err = sum_m ( X_j[m,:] w_j - Xh_j[m,:] Q(w_j) )^2
+ *   phase 2, column n:             err = sum_m ( X[m,:] w     - Xh[m,:]  Q(w)   )^2
+ * with Xh[m][k] = sx[m] * xq[m][k], the dequantized per-token INT8 form of X (xq, sx as written by
+ * dgq_quant_act(X)).  Candidates, alpha grid, clip and tie rule as in dgq_quantize_weights_grid;
+ * fp32, each product of a token summed on its own in increasing k, the squares in increasing m.
+ *   W   in  [K][N] fp16;   X in [M][K] fp16, 1 <= M <= 4096 calibration tokens
+ *   xq  in  [M][K] int8;   sx in [M] float
+ *   outputs as for dgq_quantize_weights_grid
+ *   workspace  at least dgq_quantize_weights_grid_act_workspace_bytes() (4 bytes times
+ *              (K/group)*N + M*K + (K/group)*M*N + M*N)
+ * Offline and written for clarity, not speed: the work grows with n_alpha * M * K * N.
+ */
+DGQ_API dgq_status dgq_quantize_weights_grid_act_workspace_bytes(int M, int K, int N, int group, size_t *bytes);
+DGQ_API dgq_status dgq_quantize_weights_grid_act(const uint16_t *W, const uint16_t *X, const int8_t *xq, const float *sx,
+                                         int M, int K, int N, int group, int n_alpha, float step,
+                                         uint8_t *w_u4, uint8_t *zp, uint8_t *s2, float *s1,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test hook: W_s8[K][N] = S2 * (W_u4 - ZP) from the packed form. */
 DGQ_API dgq_status dgq_unpack_weights_zp(const void *qweight, const void *scales_zp, int K, int N, int group,
                                  int8_t *w_s8, void *stream);

@@ -17,7 +17,7 @@ from . import build as _build
 __all__ = [
     "DGQError", "lib", "layout_version", "packed_sizes", "linear_workspace_bytes", "pack_weights",
     "unpack_weights", "quantize_weights_rtn", "quant_act", "linear_a8w4", "linear_a8w4_acc",
-    "linear_acc_workspace_bytes", "linear_a8w4_noalloc", "bmm_s8", "bmm_s8_acc", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
+    "linear_acc_workspace_bytes", "linear_a8w4_noalloc", "bmm_s8", "bmm_s8_acc", "linear_plan", "probe_read", "probe_mfma", "packed_sizes_zp", "pack_weights_zp", "quantize_weights_grid", "quantize_weights_grid_act", "quant_act_static", "smooth_scales", "smooth_apply", "silu_mul_quant_act", "rmsnorm_quant_act", "PackedWeight", "STREAM_MAX_M",
 ]
 
 STREAM_MAX_M = 64
@@ -60,6 +60,10 @@ def _load() -> ctypes.CDLL:
     L.dgq_linear_a8w4_noalloc.restype = i
     L.dgq_linear_a8w4_acc.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
     L.dgq_quantize_weights_grid.argtypes = [vp, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
+    L.dgq_quantize_weights_grid_act.argtypes = [vp, vp, vp, vp, i, i, i, i, i, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp]
+    L.dgq_quantize_weights_grid_act.restype = i
+    L.dgq_quantize_weights_grid_act_workspace_bytes.argtypes = [i, i, i, i, psz]
+    L.dgq_quantize_weights_grid_act_workspace_bytes.restype = i
     L.dgq_packed_sizes_zp.argtypes = [i, i, i, psz, psz]
     L.dgq_pack_weights_zp.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, vp]
     L.dgq_unpack_weights_zp.argtypes = [vp, vp, i, i, i, vp, vp]
@@ -221,6 +225,29 @@ def quantize_weights_grid(W: torch.Tensor, group: int, n_alpha: int = 51, step: 
     ws = torch.empty((K // group) * N, dtype=torch.float32, device=W.device)
     _check(lib.dgq_quantize_weights_grid(_ptr(W), K, N, group, n_alpha, step, _ptr(u4), _ptr(zp), _ptr(s2), _ptr(s1),
                                          _ptr(ws), ws.numel() * 4, _stream()), "dgq_quantize_weights_grid")
+    return u4, zp, s2, s1
+
+
+def quantize_weights_grid_act(W: torch.Tensor, X: torch.Tensor, group: int, n_alpha: int = 51, step: float = 0.01):
+    """dgq_quantize_weights_grid_act: the two-phase grid search with the activation-weighted objectives of Section 3.3
+    on calibration activations X fp16 [M,K] (quantized here with dgq_quant_act).  Returns (u4, zp, s2, s1)."""
+    _dev(W, torch.float16, "W"); _dev(X, torch.float16, "X")
+    K, N = W.shape
+    M = X.shape[0]
+    if X.shape[1] != K:
+        raise ValueError("X has K=%d but W has K=%d" % (X.shape[1], K))
+    xq, sx = quant_act(X)
+    u4 = torch.empty((K, N), dtype=torch.uint8, device=W.device)
+    zp = torch.empty((K // group, N), dtype=torch.uint8, device=W.device)
+    s2 = torch.empty((K // group, N), dtype=torch.uint8, device=W.device)
+    s1 = torch.empty(N, dtype=torch.float32, device=W.device)
+    nb = ctypes.c_size_t()
+    _check(lib.dgq_quantize_weights_grid_act_workspace_bytes(M, K, N, group, ctypes.byref(nb)),
+           "dgq_quantize_weights_grid_act_workspace_bytes")
+    ws = torch.empty(nb.value, dtype=torch.uint8, device=W.device)
+    _check(lib.dgq_quantize_weights_grid_act(_ptr(W), _ptr(X), _ptr(xq), _ptr(sx), M, K, N, group, n_alpha, step,
+                                             _ptr(u4), _ptr(zp), _ptr(s2), _ptr(s1), _ptr(ws), nb.value, _stream()),
+           "dgq_quantize_weights_grid_act")
     return u4, zp, s2, s1
 
 

@@ -274,6 +274,31 @@ dgq_status dgq_quantize_weights_grid(const uint16_t *W, int K, int N, int group,
                                                 static_cast<float *>(workspace), static_cast<hipStream_t>(stream)));
 }
 
+dgq_status dgq_quantize_weights_grid_act_workspace_bytes(int M, int K, int N, int group, size_t *bytes)
+{
+    if (!bytes) return DGQ_ERR_NULL;
+    if (M < 1 || M > 4096) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    *bytes = dgq::quantize_grid_act_workspace_bytes(M, K, N, group);
+    return DGQ_OK;
+}
+
+dgq_status dgq_quantize_weights_grid_act(const uint16_t *W, const uint16_t *X, const int8_t *xq, const float *sx, int M,
+                                         int K, int N, int group, int n_alpha, float step, uint8_t *w_u4, uint8_t *zp,
+                                         uint8_t *s2, float *s1, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!W || !X || !xq || !sx || !w_u4 || !zp || !s2 || !s1 || !workspace) return DGQ_ERR_NULL;
+    if (M < 1 || M > 4096) return DGQ_ERR_SHAPE;
+    if (dgq_status st = check_shape(N, K, group)) return st;
+    if (n_alpha < 1 || n_alpha > 1024 || !(step >= 0.0f) || !((float)(n_alpha - 1) * step < 1.0f)) return DGQ_ERR_RANGE;
+    if (workspace_bytes < dgq::quantize_grid_act_workspace_bytes(M, K, N, group)) return DGQ_ERR_WORKSPACE;
+    if (!aligned16(W) || !aligned16(X) || !aligned16(xq) || !aligned16(w_u4) || !aligned16(zp) || !aligned16(s2) ||
+        !aligned16(s1) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(sx) & 3u))
+        return DGQ_ERR_ALIGN;
+    return hip_result(dgq::launch_quantize_grid_act(W, X, xq, sx, M, K, N, group, n_alpha, step, w_u4, zp, s2, s1,
+                                                    static_cast<float *>(workspace), static_cast<hipStream_t>(stream)));
+}
+
 dgq_status dgq_quant_act(const uint16_t *x, int M, int K, int8_t *xq, float *sx, void *stream)
 {
     if (!x || !xq || !sx) return DGQ_ERR_NULL;

@@ -252,6 +252,10 @@ hipError_t launch_quantize_rtn(const uint16_t *W, int K, int N, int group, int8_
                                float *s1, hipStream_t st);
 hipError_t launch_quantize_grid(const uint16_t *W, int K, int N, int group, int n_alpha, float step, uint8_t *u4,
                                 uint8_t *zp, uint8_t *s2, float *s1, float *sprime, hipStream_t st);
+size_t quantize_grid_act_workspace_bytes(int M, int K, int N, int group);
+hipError_t launch_quantize_grid_act(const uint16_t *W, const uint16_t *X, const int8_t *xq, const float *sx, int M, int K,
+                                    int N, int group, int n_alpha, float step, uint8_t *u4, uint8_t *zp, uint8_t *s2,
+                                    float *s1, float *workspace, hipStream_t st);
 hipError_t launch_pack(const int8_t *w4, const uint8_t *s2, int K, int N, int group, void *qweight,
                        void *scales, int32_t *bad_count, hipStream_t st);
 hipError_t launch_unpack(const void *qweight, const void *scales, int zp_form, int K, int N, int group,

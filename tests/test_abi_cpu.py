@@ -22,7 +22,7 @@ def _declared():
 
 def test_header_symbols_are_exported(dgq):
     names = _declared()
-    assert len(names) == 36 and len(set(names)) == 36
+    assert len(names) == 38 and len(set(names)) == 38
     for n in names:
         assert hasattr(dgq.lib, n), n
 
@@ -96,6 +96,10 @@ def test_argument_checks_come_before_any_launch(dgq):
     assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.02), good, good, good, good, good, 1 << 20, None) == -4
     assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.01), good, good, good, good, good, 63, None) == -5
     assert L.dgq_quantize_weights_grid(good, 128, 16, 128, 51, f(0.01), good, good, good, good, None, 64, None) == -1
+    assert L.dgq_quantize_weights_grid_act(good, good, good, good, 8, 128, 16, 128, 51, f(0.01), good, good, good, good, good, 100, None) == -5
+    assert L.dgq_quantize_weights_grid_act(good, None, good, good, 8, 128, 16, 128, 51, f(0.01), good, good, good, good, good, 1 << 20, None) == -1
+    assert L.dgq_quantize_weights_grid_act(good, good, good, good, 0, 128, 16, 128, 51, f(0.01), good, good, good, good, good, 1 << 20, None) == -2
+    assert L.dgq_quantize_weights_grid_act(good, good, good, good, 8, 128, 16, 128, 0, f(0.01), good, good, good, good, good, 1 << 20, None) == -4
     assert L.dgq_quant_act_static(good, 1, 128, f(0.0), good, good, None) == -4
     assert L.dgq_quant_act_static(good, 1, 128, f(-1.0), good, good, None) == -4
     assert L.dgq_quant_act_static(good, 1, 100, f(0.1), good, good, None) == -2

@@ -487,6 +487,27 @@ def test_grid_search_quantizer_bit_exact(dgq, torch, K, N, g, n_alpha, step):
     assert bad == 0                                # the clip of Eq. 4 keeps every product inside INT8
 
 
+@pytest.mark.parametrize("M,K,N,g,n_alpha,step", [(8, 256, 64, 128, 51, 0.01), (33, 512, 80, 64, 21, 0.025),
+                                                  (70, 384, 272, 128, 11, 0.05), (1, 128, 16, 128, 1, 0.0)])
+def test_activation_weighted_grid_search_bit_exact(dgq, torch, M, K, N, g, n_alpha, step):
+    """The two-phase search under the output-error objectives of Section 3.3 (Eq. 3, objective of Eq. 5) on
+    calibration activations with outlier channels; token counts off the 32-token register block."""
+    W = workloads.weights(K, N, K + N + M)
+    W[:, 3] = 0
+    W[g:2 * g, 5] = 0
+    W[:, 7] = np.abs(W[:, 7])
+    W[::37, 9] *= 8
+    X = workloads.activations(M, K, 3 * M + K)
+    u4, zp, s2, s1 = dgq.quantize_weights_grid_act(dev(torch, W), dev(torch, X), g, n_alpha, step)
+    ou, oz, os2, os1 = oracle.quantize_weights_grid_act(W, X, g, n_alpha, step)
+    assert np.array_equal(host(zp), oz)
+    assert np.array_equal(host(s1), os1)
+    assert np.array_equal(host(s2), os2)
+    assert np.array_equal(host(u4), ou)
+    pw, bad = dgq.pack_weights_zp(u4, s2, zp, s1, g, return_bad=True)
+    assert bad == 0
+
+
 @pytest.mark.parametrize("M,K", [(1, 128), (7, 1024), (300, 4096), (64, 11008)])
 def test_quant_act_static_bit_exact(dgq, torch, M, K):
     x = workloads.activations(M, K, M + K)
@@ -550,6 +571,17 @@ def test_offline_pipeline_lowers_the_output_error(dgq, torch):
     xq2, sx2 = dgq.quant_act(Xs)
     e_smooth = err(dgq.linear_a8w4(xq2, sx2, dgq.pack_weights_zp(u4, s2, zp, s1, g)))
     assert e_grid < 0.95 * e_rtn and e_smooth < 0.95 * e_rtn and e_smooth < 1.05 * e_grid
+    # the search that weighs the error by calibration activations (the first 64 tokens: the same outlier channels)
+    # does better on the tokens it has not seen than the weight-only search, which cannot see those channels
+    def err_held_out(o):
+        return float(np.linalg.norm(host(o).astype(np.float64)[64:] - ref[64:]) / np.linalg.norm(ref[64:]))
+    u4, zp, s2, s1 = dgq.quantize_weights_grid(Wd, g)
+    e_grid_h = err_held_out(dgq.linear_a8w4(xq, sx, dgq.pack_weights_zp(u4, s2, zp, s1, g)))
+    u4, zp, s2, s1 = dgq.quantize_weights_grid_act(Wd, X[:64].contiguous(), g)
+    e_act_h = err_held_out(dgq.linear_a8w4(xq, sx, dgq.pack_weights_zp(u4, s2, zp, s1, g)))
+    print("relative output error: rtn %.4f grid %.4f smooth+grid %.4f; held-out tokens: grid %.4f activation-weighted grid %.4f"
+          % (e_rtn, e_grid, e_smooth, e_grid_h, e_act_h))
+    assert e_act_h < e_grid_h
     assert e_rtn < 0.2                                  # and all of them are sane
 
 
