@@ -54,12 +54,76 @@ SEEDS = {"7b": 1, "13b": 3, "65b": 4}
 # x1.0).  (workload, kernel) -> (bytes, summary under profiles/ with the figures and commands).
 # A kernel that has not been profiled in a workload reports null.
 TRAFFIC_BYTES = {
-    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"):
-        ((2.0 * 14569.5 + 62.5) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
-    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"):
-        ((2.0 * 14182.3 + 175.0) * 1024, "profiles/decode_llama7b_linear_decode_kernel.md"),
+    ("llama65b_g128", "quant_linear_decode_nt_kernel<4, 1, 128>"):
+        ((2.0 * 74498.5 + 1.0 * 67.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "quant_linear_decode_kernel<4, 1, 128>"):
+        ((2.0 * 17544.8 + 1.0 * 16.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_decode_nt_kernel<6, 1, 128, true>"):
+        ((2.0 * 51209.1 + 1.0 * 1108.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_decode_nt_kernel<4, 1, 128, false>"):
+        ((2.0 * 75197.1 + 1.0 * 536.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_decode_kernel<4, 1, 128, false, false>"):
+        ((2.0 * 17897.2 + 1.0 * 128.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"):
+        ((2.0 * 44237.0 + 1.0 * 12636.3) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_tiled_kernel<128, 4, 2, 3, false>"):
+        ((2.0 * 77879.0 + 1.0 * 6244.4) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_tiled_kernel<128, 8, 4, 3, false>"):
+        ((2.0 * 166956.6 + 1.0 * 47104.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_tiled_kernel<128, 4, 4, 3, false>"):
+        ((2.0 * 399104.4 + 1.0 * 110080.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g128", "linear_tiled_splitk_kernel<128, 4, 4, 3, false>"):
+        ((2.0 * 119926.3 + 1.0 * 40972.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+    ("llama65b_g64", "quant_linear_decode_nt_kernel<4, 1, 64>"):
+        ((2.0 * 75932.0 + 1.0 * 67.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "quant_linear_decode_kernel<4, 1, 64>"):
+        ((2.0 * 18321.0 + 1.0 * 16.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_decode_nt_kernel<6, 1, 64, true>"):
+        ((2.0 * 52031.5 + 1.0 * 1108.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_decode_nt_kernel<4, 1, 64, false>"):
+        ((2.0 * 76618.6 + 1.0 * 536.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_decode_kernel<4, 1, 64, false, false>"):
+        ((2.0 * 18667.9 + 1.0 * 128.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_tiled_splitk_kernel<64, 4, 2, 3, false>"):
+        ((2.0 * 44798.1 + 1.0 * 12636.3) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_tiled_kernel<64, 4, 2, 3, false>"):
+        ((2.0 * 79006.5 + 1.0 * 6244.4) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_tiled_kernel<64, 8, 4, 3, false>"):
+        ((2.0 * 169038.1 + 1.0 * 47104.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_tiled_kernel<64, 4, 4, 3, false>"):
+        ((2.0 * 403530.9 + 1.0 * 110080.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama65b_g64", "linear_tiled_splitk_kernel<64, 4, 4, 3, false>"):
+        ((2.0 * 121271.1 + 1.0 * 40972.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+    ("llama13b", "quant_linear_decode_kernel<3, 2, 128>"):
+        ((2.0 * 14901.4 + 1.0 * 20.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+    ("llama13b", "quant_linear_decode_nt_kernel<3, 2, 128>"):
+        ((2.0 * 36249.1 + 1.0 * 54.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+    ("llama13b", "linear_decode_kernel<4, 1, 128, false, true>"):
+        ((2.0 * 19916.8 + 1.0 * 737.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+    ("llama13b", "linear_decode_kernel<3, 2, 128, false, false>"):
+        ((2.0 * 14441.6 + 1.0 * 320.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+    ("llama13b", "linear_decode_nt_kernel<3, 2, 128, false>"):
+        ((2.0 * 37577.5 + 1.0 * 864.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+    ("llama13b", "linear_tiled_kernel<128, 8, 4, 3, false>"):
+        ((2.0 * 64050.5 + 1.0 * 30720.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+    ("llama13b", "linear_tiled_kernel<128, 4, 4, 3, false>"):
+        ((2.0 * 84556.6 + 1.0 * 25258.7) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"):
-        ((2.0 * 75912.5 + 34112.0) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+        ((2.0 * 70745.5 + 1.0 * 37717.3) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+    ("llama7b_prefill", "linear_tiled_kernel<128, 4, 2, 3, false>"):
+        ((2.0 * 31853.1 + 1.0 * 6826.7) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+    ("llama7b_prefill", "linear_tiled_kernel<128, 8, 4, 3, false>"):
+        ((2.0 * 50418.8 + 1.0 * 23296.0) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+    ("llama7b_prefill", "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"):
+        ((2.0 * 54540.3 + 1.0 * 20492.0) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+    ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"):
+        ((2.0 * 14550.8 + 1.0 * 62.5) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+    ("llama7b_decode", "quant_linear_decode_kernel<6, 1, 128>"):
+        ((2.0 * 12291.4 + 1.0 * 20.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+    ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"):
+        ((2.0 * 14209.5 + 1.0 * 400.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+    ("llama7b_decode", "linear_decode_kernel<6, 1, 128, false, false>"):
+        ((2.0 * 11932.2 + 1.0 * 128.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
 }
 
 
@@ -326,14 +390,29 @@ class Bench:
         t_hbm = sum(pair_sec[p] for p in groups[top] if bound_of(p) == "hbm")
         top_bound = "hbm" if 2 * t_hbm >= sum(pair_sec[p] for p in groups[top]) else "mfma"
         roofline = roofline_of(groups[top], top_bound)
+        # The two regimes of the layer, by the token counts they are defined on: M <= 16 (decode: bound by
+        # the weight stream, priced against the HBM peak) and M >= 1024 (prefill: bound by the matrix
+        # cores); what lies between is priced by its arithmetic intensity.  Each record is that of the
+        # kernel symbol with the largest share of the regime's time, plus the aggregate over all the
+        # regime's launches (sum of bytes or ops over sum of time).
         regimes = {}
-        for b, label in (("hbm", "weight_stream_bound"), ("mfma", "matrix_core_bound")):
-            ps = [p for p in all_pairs if bound_of(p) == b]
-            if ps:
-                regimes[label] = roofline_of(ps, b)
-                log("[%s] %s: %s over %d pair(s): avg %.2f us, %.1f %s (%.1f%% of peak)" %
-                    (workload, label, regimes[label]["kernel"], len(regimes[label]["launches"]), regimes[label]["avg_us"],
-                     regimes[label]["achieved"], regimes[label]["unit"], 100 * regimes[label]["frac"]))
+        for label, b, ps in (("weight_stream_bound", "hbm", [p for p in all_pairs if p[0] <= 16]),
+                             ("intermediate", None, [p for p in all_pairs if 16 < p[0] < 1024]),
+                             ("matrix_core_bound", "mfma", [p for p in all_pairs if p[0] >= 1024])):
+            if not ps:
+                continue
+            t = sum(pair_sec[p] for p in ps)
+            if b is None:
+                b = "hbm" if 2 * sum(pair_sec[p] for p in ps if bound_of(p) == "hbm") >= t else "mfma"
+            rec = roofline_of(ps, b)
+            agg = sum(pair_b(p) for p in ps) / t / 1e9 if b == "hbm" else sum(pair_o(p) for p in ps) / t / 1e12
+            rec["all_launches"] = {"M": sorted({p[0] for p in ps}), "launches": len(ps), "time_us": t * 1e6, "achieved": agg,
+                                   "frac": agg / (HBM_PEAK_GBS if b == "hbm" else INT8_PEAK_TOPS),
+                                   "kernels": sorted({pair_sym[p] for p in ps})}
+            regimes[label] = rec
+            log("[%s] %s (M in %s): %s over %d launch(es): avg %.2f us, %.1f %s (%.1f%% of peak); all %d launches %.1f%%" %
+                (workload, label, rec["all_launches"]["M"], rec["kernel"], len(rec["launches"]), rec["avg_us"],
+                 rec["achieved"], rec["unit"], 100 * rec["frac"], len(ps), 100 * rec["all_launches"]["frac"]))
 
         # ---------------- per (shape, M) table + fp16 GEMM (A16) baseline -------------------
         breakdown = []
