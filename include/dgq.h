@@ -162,8 +162,8 @@ DGQ_API dgq_status dgq_smooth_scales(const uint16_t *X, int M, int K, float pct,
 /*
  * Moves the smoothing scale from the activations into the weights (Section 3.4):
  *   Wout[j][n] = fp16(k_j * W[j][n])   if W is not NULL ([K][N] fp16)
- *   Xout[m][j] = fp16(X[m][j] / k_j)   if X is not NULL ([M][K] fp16, M <= 65535)
- * fp32 arithmetic, one rounding to fp16; K <= 65535.  In a model the division is folded into the
+ *   Xout[m][j] = fp16(X[m][j] / k_j)   if X is not NULL ([M][K] fp16)
+ * fp32 arithmetic, one rounding to fp16; K <= 131072.  In a model the division is folded into the
  * producer of X; the entry point exists so that the identity (X/k)(kW) = XW can be exercised.
  */
 DGQ_API dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k, int M, int K, int N,

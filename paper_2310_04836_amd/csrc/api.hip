@@ -354,7 +354,7 @@ dgq_status dgq_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k
                             uint16_t *Wout, uint16_t *Xout, void *stream)
 {
     if (!k || (!W && !X) || (W && !Wout) || (X && !Xout)) return DGQ_ERR_NULL;
-    if (K < 1 || K > 65535 || (W && N < 1) || (X && (M < 1 || M > 65535))) return DGQ_ERR_SHAPE;
+    if (K < 1 || K > 131072 || (W && N < 1) || (X && M < 1)) return DGQ_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(Wout) |
          reinterpret_cast<uintptr_t>(Xout)) & 1u)
         return DGQ_ERR_ALIGN;

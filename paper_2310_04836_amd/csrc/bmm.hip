@@ -15,6 +15,8 @@
 //     probability matrix read), not by the matrix cores, so nothing more elaborate is needed.
 //   - Ragged M, N: rows past the end repeat the last row and are never stored.  K is a multiple
 //     of 16; units past the end of K are zeros.
+//   - M <= 16 (decode: one query token per head) takes another kernel, dot products on the vector
+//     units, described where it stands.
 #include "dgq_device.hpp"
 
 namespace dgq {
@@ -164,11 +166,81 @@ __global__ __launch_bounds__(256, DB ? 2 : 3) void bmm_s8_kernel(const int8_t *_
     }
 }
 
+// Few rows of A (one query token per head at decode): the product is a handful of dot products per
+// row of B and is bound by reading B once, so no matrix instruction is needed.  A group of LPR lanes
+// (a power of two, at least K / 16 and at most 64) owns one row n of B: a lane takes 16-byte pieces
+// l, l + LPR, ... of it and of every row of A (v_dot4_i32_i8), the group adds its lanes' sums with
+// lane exchanges, and its first lane writes the MT results.  A 256-thread workgroup covers 256 / LPR
+// rows of B of one batch.
+template <int MT, bool ACC>
+__global__ __launch_bounds__(256) void bmm_s8_rows_kernel(const int8_t *__restrict__ A, const int8_t *__restrict__ B,
+                                                         const float *__restrict__ sa, const float *__restrict__ sb,
+                                                         uint16_t *__restrict__ out, int32_t *__restrict__ acc_out, int M,
+                                                         int N, int K, int lpr_log2)
+{
+    const int lpr = 1 << lpr_log2;
+    const int l = threadIdx.x & (lpr - 1);
+    const int n = blockIdx.x * (256 >> lpr_log2) + (threadIdx.x >> lpr_log2);
+    const size_t batch = blockIdx.y;
+    const int pieces = K >> 4;
+    const int8_t *Ab = A + batch * (size_t)M * K;
+    const int8_t *Bn = B + (batch * (size_t)N + (n < N ? n : N - 1)) * K;   // rows past the end repeat the last one
+    int acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc[m] = 0;
+    for (int p = l; p < pieces; p += lpr) {
+        const v4i b = *reinterpret_cast<const v4i *>(Bn + (size_t)p * 16);
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            if (m < M) {
+                const v4i a = *reinterpret_cast<const v4i *>(Ab + (size_t)m * K + (size_t)p * 16);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[m] = __builtin_amdgcn_sdot4(a[q], b[q], acc[m], false);
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+        for (int d = lpr >> 1; d > 0; d >>= 1) acc[m] += __shfl_xor(acc[m], d, 64);
+    if (l != 0 || n >= N) return;
+    const float sbn = ACC ? 0.0f : (sb ? sb[batch * N + n] : 1.0f);
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        if (m >= M) break;
+        const size_t o = (batch * (size_t)M + m) * N + n;
+        if (ACC)
+            acc_out[o] = acc[m];
+        else
+            out[o] = scaled_sum_to_half_bits((sa ? sa[batch * M + m] : 1.0f) * sbn, acc[m]);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_bmm_s8(const int8_t *A, const int8_t *B, const float *sa, const float *sb, uint16_t *out, int32_t *acc_out,
                          int batch, int M, int N, int K, hipStream_t st)
 {
+    if (M <= 16) {
+        int lpr_log2 = 0;
+        while (lpr_log2 < 6 && (16 << lpr_log2) < K) ++lpr_log2;
+        const int rows = 256 >> lpr_log2;
+        const dim3 g((N + rows - 1) / rows, batch), b(256);
+#define DGQ_ROWS(MT)                                                                                                  \
+    do {                                                                                                              \
+        if (acc_out)                                                                                                  \
+            hipLaunchKernelGGL((bmm_s8_rows_kernel<MT, true>), g, b, 0, st, A, B, sa, sb, out, acc_out, M, N, K, lpr_log2); \
+        else                                                                                                          \
+            hipLaunchKernelGGL((bmm_s8_rows_kernel<MT, false>), g, b, 0, st, A, B, sa, sb, out, acc_out, M, N, K, lpr_log2); \
+    } while (0)
+        if (M == 1)
+            DGQ_ROWS(1);
+        else if (M <= 4)
+            DGQ_ROWS(4);
+        else
+            DGQ_ROWS(16);
+#undef DGQ_ROWS
+        return hipGetLastError();
+    }
     const dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, batch), block(256);
     if (K > BK) {
         if (acc_out)

@@ -64,24 +64,27 @@ __global__ __launch_bounds__(256) void smooth_weights_kernel(const uint16_t *__r
                                                              int K, int N, uint16_t *__restrict__ Wout)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
-    const int j = blockIdx.y;
     if (n >= N) return;
-    const size_t i = (size_t)j * N + n;
-    float p = k[j] * ld_h(W + i);
-    // keep the product and the rounding to fp16 two operations: fused into one mixed-precision
-    // multiply-add with a +0 addend, a product of -0 would come out as +0
-    asm volatile("" : "+v"(p));
-    Wout[i] = __builtin_bit_cast(unsigned short, (_Float16)p);
+    for (int j = blockIdx.y; j < K; j += gridDim.y) {   // (a grid has at most 65535 rows of blocks)
+        const size_t i = (size_t)j * N + n;
+        float p = k[j] * ld_h(W + i);
+        // keep the product and the rounding to fp16 two operations: fused into one mixed-precision
+        // multiply-add with a +0 addend, a product of -0 would come out as +0
+        asm volatile("" : "+v"(p));
+        Wout[i] = __builtin_bit_cast(unsigned short, (_Float16)p);
+    }
 }
 
 __global__ __launch_bounds__(256) void smooth_acts_kernel(const uint16_t *__restrict__ X, const float *__restrict__ k,
                                                           int M, int K, uint16_t *__restrict__ Xout)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
-    const int m = blockIdx.y;
     if (j >= K) return;
-    const size_t i = (size_t)m * K + j;
-    Xout[i] = __builtin_bit_cast(unsigned short, (_Float16)(ld_h(X + i) / k[j]));
+    const float kj = k[j];
+    for (int m = blockIdx.y; m < M; m += gridDim.y) {
+        const size_t i = (size_t)m * K + j;
+        Xout[i] = __builtin_bit_cast(unsigned short, (_Float16)(ld_h(X + i) / kj));
+    }
 }
 
 }  // namespace
@@ -96,8 +99,8 @@ hipError_t launch_smooth_scales(const uint16_t *X, int M, int K, int r, float *k
 hipError_t launch_smooth_apply(const uint16_t *W, const uint16_t *X, const float *k, int M, int K, int N,
                                uint16_t *Wout, uint16_t *Xout, hipStream_t st)
 {
-    if (W) hipLaunchKernelGGL(smooth_weights_kernel, dim3((N + 255) / 256, K), dim3(256), 0, st, W, k, K, N, Wout);
-    if (X) hipLaunchKernelGGL(smooth_acts_kernel, dim3((K + 255) / 256, M), dim3(256), 0, st, X, k, M, K, Xout);
+    if (W) hipLaunchKernelGGL(smooth_weights_kernel, dim3((N + 255) / 256, K < 65535 ? K : 65535), dim3(256), 0, st, W, k, K, N, Wout);
+    if (X) hipLaunchKernelGGL(smooth_acts_kernel, dim3((K + 255) / 256, M < 65535 ? M : 65535), dim3(256), 0, st, X, k, M, K, Xout);
     return hipGetLastError();
 }
 

@@ -44,6 +44,10 @@ def _operands(B, M, N, K, seed):
 @pytest.mark.parametrize("B,M,N,K", [
     (1, 1, 1, 16), (2, 8, 8, 128), (3, 130, 257, 144), (1, 300, 100, 1040), (2, 128, 128, 128), (1, 129, 127, 2064),
     (4, 1, 2048, 128), (2, 77, 128, 4096), (1, 5, 1003, 48), (5, 256, 384, 256),
+    # at most 16 rows of A: the dot-product kernel (1, 2-4 and 5-16 rows; K / 16 a power of two and not; one lane
+    # group per row of B up to a whole wavefront with several pieces per lane; ragged N)
+    (32, 1, 128, 2048), (3, 1, 7, 16), (2, 2, 300, 32), (2, 4, 65, 80), (1, 16, 1000, 1024), (2, 9, 33, 4112),
+    (1, 16, 5, 65536), (40, 3, 16, 128), (2, 17, 40, 128),
 ])
 def test_bmm_bit_exact_and_epilogue(dgq, torch, B, M, N, K):
     a, b, sa, sb = _operands(B, M, N, K, seed=M + N + K)

@@ -531,7 +531,8 @@ def test_static_activation_scale_through_the_linear(dgq, torch):
     assert_fp16_close(out, oout)
 
 
-@pytest.mark.parametrize("M,K,N,pct", [(64, 4096, 64, 0.005), (7, 11008, 16, 0.005), (300, 1024, 48, 0.02), (2, 128, 16, 1.0)])
+@pytest.mark.parametrize("M,K,N,pct", [(64, 4096, 64, 0.005), (7, 11008, 16, 0.005), (300, 1024, 48, 0.02), (2, 128, 16, 1.0),
+                                       (3, 66048, 16, 0.005)])      # more input channels than a grid has rows of blocks
 def test_smoothing_bit_exact(dgq, torch, M, K, N, pct):
     x = workloads.activations(M, K, M + K)                       # 1 % of the channels are outliers
     W = workloads.weights(K, N, M + K)
@@ -541,6 +542,15 @@ def test_smoothing_bit_exact(dgq, torch, M, K, N, pct):
     Wo, Xo = dgq.smooth_apply(dev(torch, W), dev(torch, x), k)
     oW, oX = oracle.smooth_apply(W, x, ok)
     assert np.array_equal(host(Wo).view(np.uint16), oW.view(np.uint16))
+    assert np.array_equal(host(Xo).view(np.uint16), oX.view(np.uint16))
+
+
+def test_smooth_apply_with_more_tokens_than_a_grid_has_rows(dgq, torch):
+    M, K = 70000, 128
+    x = workloads.activations(M, K, 5)
+    k = (1.0 + np.arange(K, dtype=np.float32) / 16).astype(np.float32)
+    _, Xo = dgq.smooth_apply(None, dev(torch, x), dev(torch, k))
+    _, oX = oracle.smooth_apply(np.zeros((K, 16), np.float16), x, k)
     assert np.array_equal(host(Xo).view(np.uint16), oX.view(np.uint16))
 
 
