@@ -35,6 +35,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0        # MI355X dense INT8 MFMA, published
+FP16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 MFMA, published (prices the A16 baseline GEMM)
 RIDGE_OPS_PER_BYTE = INT8_PEAK_TOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # 625: below it a launch is bound by HBM
 MALL_BYTES = 256 << 20         # last-level cache; rotate over >= 2x this much weight data
 
@@ -441,7 +442,8 @@ class Bench:
                            "GBps": round(b / sec / 1e9, 1), "hbm_frac": round(b / sec / 1e9 / HBM_PEAK_GBS, 4),
                            "TOPS": round(2 * M * K * N / sec / 1e12, 2),
                            "mfma_frac": round(2 * M * K * N / sec / 1e12 / INT8_PEAK_TOPS, 4),
-                           "fp16_gemm_us": round(fsec * 1e6, 2), "speedup_vs_fp16_gemm": round(fsec / sec, 2)}
+                           "fp16_gemm_us": round(fsec * 1e6, 2), "speedup_vs_fp16_gemm": round(fsec / sec, 2),
+                           "fp16_gemm_mfma_frac": round(2 * M * K * N / fsec / 1e12 / FP16_PEAK_TFLOPS, 4)}
                     breakdown.append(row)
                     log("  %-8s M=%-5d %9.2f us  %7.1f GB/s (%5.1f%% HBM)  %8.2f TOP/s (%5.1f%% MFMA)  fp16 GEMM %9.2f us  x%.2f" %
                         (name, M, row["us"], row["GBps"], 100 * row["hbm_frac"], row["TOPS"], 100 * row["mfma_frac"],
