@@ -527,11 +527,8 @@ dgq_status dgq_linear_plan(int M, int N, int K, int group, char *buf, size_t buf
         std::snprintf(buf, buf_bytes, "linear_stream_kernel<%d, %d, %d, %d, false>", p.mtiles, group, p.waves, p.depth);
         break;
     }
-    default: {
-        const dgq::TiledPlan p = dgq::tiled_plan(M, N, K);
-        std::snprintf(buf, buf_bytes, "linear_tiled_%skernel<%d, %d, %d, %d, false>", p.ksplit > 1 ? "splitk_" : "", group,
-                      p.nw, p.mi, p.st);
-    }
+    default:
+        dgq::tiled_plan_name(M, N, K, group, buf, buf_bytes);
     }
     return DGQ_OK;
 }

@@ -278,6 +278,10 @@ struct LinearArgs {
     float *sx_out;         // optional: the token scales it derived, [M]
     const uint16_t *gamma; // optional, fp16 bits [K]: RMS-normalise x and multiply by gamma first
     float eps;             // added to the mean square
+    // Only for the tiled kernels that compute a range of output channels of a wider layer (the
+    // pointers above then start at the range's first channel, N is its width): elements between the
+    // starts of two token rows of out / acc_out.
+    int ldo;
 };
 // A workspace that a K split uses starts with this many bytes of arrival counters (one 32-bit
 // word per tile or workgroup column, at most kSplitCounterBytes / 4 of them), whatever the shape
@@ -319,6 +323,16 @@ struct TiledPlan {
     int ksplit;  // workgroups that share one tile, each taking a part of K
 };
 TiledPlan tiled_plan(int M, int N, int K);
+// A layer whose tiles fill the CUs in two or more whole rounds plus a remainder is run as two
+// launches: the first n_first output channels (whole rounds of 128 x 512 tiles when nw_first is 8,
+// of 128 x 256 tiles when it is 4) and the rest as a problem of its own.  n_first = 0: one launch.
+struct TiledTail {
+    int n_first;
+    int nw_first;
+};
+TiledTail tiled_tail(int M, int N, int K);
+// Name of the kernel(s) launch_linear_tiled would launch, as a profiler shows them (without the namespace).
+void tiled_plan_name(int M, int N, int K, int group, char *buf, size_t buf_bytes);
 size_t tiled_workspace_bytes(int M, int N, int K);
 hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st);
 

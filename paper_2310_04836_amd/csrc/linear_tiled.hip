@@ -27,6 +27,7 @@
 #include "dgq_device.hpp"
 
 #include <cmath>
+#include <cstdio>
 
 namespace dgq {
 namespace {
@@ -105,10 +106,13 @@ struct SplitK {
 };
 
 // SPLIT is a compile-time choice so that the kernels without a K split carry none of its code.
-template <int G, int NW, int MI, int ST, bool ACC, bool ZP, bool SPLIT>
+// COLS: the launch covers a range of the output channels of a wider layer (rows of the output are
+// a.ldo elements apart instead of a.N).
+template <int G, int NW, int MI, int ST, bool ACC, bool ZP, bool SPLIT, bool COLS = false>
 __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int tiles_n, const SplitK &sk)
 {
     const int ksplit = SPLIT ? sk.parts : 1;
+    const int ldo = COLS ? a.ldo : a.N;
     constexpr int kStages = ST;
     constexpr int BM = 32 * MI;
     constexpr int BN = 64 * NW;
@@ -419,7 +423,7 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = m0 + mi * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
-                    if (m < a.M) dst[(size_t)m * a.N + n] = acc[mi][nj][r];
+                    if (m < a.M) dst[(size_t)m * ldo + n] = acc[mi][nj][r];
                 }
         }
         return;
@@ -453,7 +457,7 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
             const int m = m0 + mi * 32 + row;
             const int n = nw0 + (lane & 7) * 8;
             const uint4 v = *reinterpret_cast<const uint4 *>(&lds_t[row * 64 + (lane & 7) * 8]);
-            if (m < a.M && n < a.N) *reinterpret_cast<uint4 *>(&a.out[(size_t)m * a.N + n]) = v;
+            if (m < a.M && n < a.N) *reinterpret_cast<uint4 *>(&a.out[(size_t)m * ldo + n]) = v;
         }
     }
 }
@@ -467,6 +471,17 @@ template <int G, int NW, int MI, int ST, bool ACC>
 __global__ __launch_bounds__(64 * NW, 2) void linear_tiled_zp_kernel(LinearArgs a, int tiles_m, int tiles_n)
 {
     tiled_body<G, NW, MI, ST, ACC, true, false>(a, tiles_m, tiles_n, SplitK{1, nullptr, nullptr});
+}
+// the same for a range of the output channels of a wider layer
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_cols_kernel(LinearArgs a, int tiles_m, int tiles_n)
+{
+    tiled_body<G, NW, MI, ST, ACC, false, false, true>(a, tiles_m, tiles_n, SplitK{1, nullptr, nullptr});
+}
+template <int G, int NW, int MI, int ST, bool ACC>
+__global__ __launch_bounds__(64 * NW, 2) void linear_tiled_cols_zp_kernel(LinearArgs a, int tiles_m, int tiles_n)
+{
+    tiled_body<G, NW, MI, ST, ACC, true, false, true>(a, tiles_m, tiles_n, SplitK{1, nullptr, nullptr});
 }
 // the same with the K of every tile split over sk.parts workgroups
 template <int G, int NW, int MI, int ST, bool ACC>
@@ -513,10 +528,9 @@ double predicted_us(int M, int N, int K, const TiledPlan &p, int cus)
 }
 }  // namespace
 
-TiledPlan tiled_plan(int M, int N, int K)
+// The plan without a K split.
+static TiledPlan tiled_base_plan(int M, int N, int cus)
 {
-    const int cus = cu_count();
-    const int steps = K / 128;
     TiledPlan p;
     p.nw = 4, p.mi = 4, p.st = 3, p.ksplit = 1;
     const long long tiles_n = (N + 255) / 256;
@@ -536,6 +550,17 @@ TiledPlan tiled_plan(int M, int N, int K)
         const long long wide = (long long)((M + 127) / 128) * ((N + 511) / 512);
         if ((wide >= cus && wide % cus == 0) || (wide >= 160 && wide <= cus && tiles_128 <= 2 * cus)) p.nw = 8;
     }
+    return p;
+}
+
+TiledPlan tiled_plan(int M, int N, int K)
+{
+    const int cus = cu_count();
+    const int steps = K / 128;
+    const TiledPlan p = tiled_base_plan(M, N, cus);
+    const long long tiles_n = (N + 255) / 256;
+    const long long tiles_64 = (long long)((M + 63) / 64) * tiles_n;
+    const long long tiles_128 = (long long)((M + 127) / 128) * tiles_n;
     // K split over several workgroups per tile (the last to arrive adds up the parts): for shapes
     // whose tiles alone leave CUs idle.  64-token tiles in 2 to 8 parts (at most two workgroups per
     // CU), 128-token tiles in 2 to 4 parts (every part a CU to itself); at least four stages per
@@ -560,11 +585,35 @@ TiledPlan tiled_plan(int M, int N, int K)
     return best;
 }
 
+// Whole rounds first, the remainder as a launch of its own.  A grid of 5.4 rounds of resident
+// workgroups ends with a round that runs on a fraction of the CUs.  Cut at a channel where a round
+// ends (the resident 128 x 512 tiles cover all token tiles of CUs / token-tiles column tiles), the
+// first part runs in whole rounds of the wide tile and the rest is a narrower layer that gets the
+// tile shape that suits it.  The gain is small, because the hardware already spreads a partial
+// round over the CUs one workgroup each: in the benchmark (graph replay, weights never cached)
+// LLaMA-65B gate+up at M = 2048 (5.4 rounds) 576 -> 565 us, LLaMA-7B gate+up (2.7 rounds)
+// 161.2 -> 158.8 us.  One round plus a remainder gains nothing and is left alone.
+TiledTail tiled_tail(int M, int N, int K)
+{
+    (void)K;
+    TiledTail t{0, 0};
+    const int cus = cu_count();
+    const int tiles_m = (M + 127) / 128;
+    if (M <= 64 || tiles_m > cus || cus % tiles_m != 0) return t;
+    const long long per_round = (long long)(cus / tiles_m) * 512;   // output channels one round of 128 x 512 tiles covers
+    const long long rounds = N / per_round;
+    if (rounds < 2 || N % per_round == 0) return t;
+    t.n_first = (int)(rounds * per_round);
+    t.nw_first = 8;
+    return t;
+}
+
 // Tile shape of a plan (tokens x output channels).
 static inline void plan_tile(const TiledPlan &p, int &bm, int &bn) { bm = 32 * p.mi, bn = 64 * p.nw; }
 
 size_t tiled_workspace_bytes(int M, int N, int K)
 {
+    if (tiled_tail(M, N, K).n_first) return 0;   // both launches run without a K split
     const TiledPlan p = tiled_plan(M, N, K);
     if (p.ksplit <= 1) return 0;
     int bm, bn;
@@ -574,7 +623,7 @@ size_t tiled_workspace_bytes(int M, int N, int K)
 }
 
 template <int G, int NW, int MI, int ST>
-static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st)
+static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *workspace, hipStream_t st, bool cols = false)
 {
     const int tiles_m = (a.M + 32 * MI - 1) / (32 * MI);
     const int tiles_n = (a.N + 64 * NW - 1) / (64 * NW);
@@ -596,7 +645,11 @@ static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *worksp
         else                                                                                               \
             hipLaunchKernelGGL((KERNEL<G, NW, MI, ST, false>), grid, block, 0, st, a, tiles_m, tiles_n, ##__VA_ARGS__); \
     } while (0)
-    if (ksplit > 1) {
+    if (cols) {
+        if (ksplit > 1) return hipErrorInvalidValue;
+        if (a.zp) DGQ_LAUNCH(linear_tiled_cols_zp_kernel);
+        else DGQ_LAUNCH(linear_tiled_cols_kernel);
+    } else if (ksplit > 1) {
         if (a.zp) DGQ_LAUNCH(linear_tiled_splitk_zp_kernel, sk);
         else DGQ_LAUNCH(linear_tiled_splitk_kernel, sk);
     } else {
@@ -608,17 +661,60 @@ static hipError_t launch_tiled_cfg(const LinearArgs &a, int ksplit, void *worksp
 }
 
 template <int G>
-static hipError_t launch_tiled_g(const LinearArgs &a, const TiledPlan &p, void *workspace, hipStream_t st)
+static hipError_t launch_tiled_g(const LinearArgs &a, const TiledPlan &p, void *workspace, hipStream_t st, bool cols = false)
 {
-    if (p.mi == 2) return launch_tiled_cfg<G, 4, 2, 3>(a, p.ksplit, workspace, st);
-    if (p.nw == 8) return launch_tiled_cfg<G, 8, 4, 3>(a, p.ksplit, workspace, st);
-    return launch_tiled_cfg<G, 4, 4, 3>(a, p.ksplit, workspace, st);
+    if (p.mi == 2) return launch_tiled_cfg<G, 4, 2, 3>(a, p.ksplit, workspace, st, cols);
+    if (p.nw == 8) return launch_tiled_cfg<G, 8, 4, 3>(a, p.ksplit, workspace, st, cols);
+    return launch_tiled_cfg<G, 4, 4, 3>(a, p.ksplit, workspace, st, cols);
 }
+
+// The second of the two launches of a layer cut by tiled_tail: its plan, without a K split.
+static TiledPlan tail_plan(int M, int n_rest) { return tiled_base_plan(M, n_rest, cu_count()); }
 
 hipError_t launch_linear_tiled(const LinearArgs &a, void *workspace, hipStream_t st)
 {
-    const TiledPlan p = tiled_plan(a.M, a.N, a.K);
-    return a.group == 128 ? launch_tiled_g<128>(a, p, workspace, st) : launch_tiled_g<64>(a, p, workspace, st);
+    const TiledTail t = tiled_tail(a.M, a.N, a.K);
+    if (!t.n_first) {
+        const TiledPlan p = tiled_plan(a.M, a.N, a.K);
+        return a.group == 128 ? launch_tiled_g<128>(a, p, workspace, st) : launch_tiled_g<64>(a, p, workspace, st);
+    }
+    // first part: channels [0, n_first) in whole rounds
+    LinearArgs first = a;
+    first.N = t.n_first;
+    first.ldo = a.N;
+    TiledPlan pf;
+    pf.nw = t.nw_first, pf.mi = 4, pf.st = 3, pf.ksplit = 1;
+    hipError_t e = a.group == 128 ? launch_tiled_g<128>(first, pf, nullptr, st, true) : launch_tiled_g<64>(first, pf, nullptr, st, true);
+    if (e != hipSuccess) return e;
+    // the rest: the packed arrays are ordered by blocks of 16 channels, so a range that starts at a
+    // multiple of 16 is a contiguous part of each of them
+    LinearArgs rest = a;
+    const int steps = a.K / 128;
+    const int per_word = a.zp ? 2 : 4;   // groups per 32-bit scale word
+    const int words = (a.K / a.group + per_word - 1) / per_word;
+    rest.N = a.N - t.n_first;
+    rest.ldo = a.N;
+    rest.qweight = reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(a.qweight) + (size_t)(t.n_first / 16) * steps * 1024);
+    rest.scales = reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(a.scales) + (size_t)(t.n_first / 16) * words * 64);
+    if (a.s1) rest.s1 = a.s1 + t.n_first;
+    if (a.out) rest.out = a.out + t.n_first;
+    if (a.acc_out) rest.acc_out = a.acc_out + t.n_first;
+    const TiledPlan pr = tail_plan(a.M, rest.N);
+    return a.group == 128 ? launch_tiled_g<128>(rest, pr, nullptr, st, true) : launch_tiled_g<64>(rest, pr, nullptr, st, true);
+}
+
+void tiled_plan_name(int M, int N, int K, int group, char *buf, size_t buf_bytes)
+{
+    const TiledTail t = tiled_tail(M, N, K);
+    if (!t.n_first) {
+        const TiledPlan p = tiled_plan(M, N, K);
+        std::snprintf(buf, buf_bytes, "linear_tiled_%skernel<%d, %d, %d, %d, false>", p.ksplit > 1 ? "splitk_" : "", group, p.nw,
+                      p.mi, p.st);
+        return;
+    }
+    const TiledPlan pr = tail_plan(M, N - t.n_first);
+    std::snprintf(buf, buf_bytes, "linear_tiled_cols_kernel<%d, %d, 4, 3, false> + linear_tiled_cols_kernel<%d, %d, %d, %d, false>",
+                  group, t.nw_first, group, pr.nw, pr.mi, pr.st);
 }
 
 }  // namespace dgq

@@ -194,10 +194,19 @@ def test_linear_plan_names(dgq):
     assert dgq.linear_plan(512, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 2, 3, false>"     # 8 x 16 tiles
     assert dgq.linear_plan(512, 12288, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"    # 4 x 48 tiles
     assert dgq.linear_plan(2048, 4096, 4096, 64) == "linear_tiled_kernel<64, 4, 4, 3, false>"
-    assert dgq.linear_plan(2048, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
+    assert dgq.linear_plan(1024, 22016, 4096, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"
     # 128 x 512 tiles where their grid fills the CUs in whole rounds, or most of them in one round
     assert dgq.linear_plan(2048, 8192, 22016, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 16 x 16 wide tiles
     assert dgq.linear_plan(1024, 12288, 4096, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # 8 x 24 wide tiles
+    # two or more whole rounds of 128 x 512 tiles plus a remainder: the whole rounds and the rest as two launches
+    # (256 CUs, 16 token tiles: a round covers 16 column tiles = 8192 channels)
+    assert dgq.linear_plan(2048, 44032, 8192, 128) == ("linear_tiled_cols_kernel<128, 8, 4, 3, false> + "
+                                                       "linear_tiled_cols_kernel<128, 4, 4, 3, false>")   # 40960 + 3072
+    assert dgq.linear_plan(2048, 22016, 4096, 64) == ("linear_tiled_cols_kernel<64, 8, 4, 3, false> + "
+                                                      "linear_tiled_cols_kernel<64, 8, 4, 3, false>")     # 16384 + 5632
+    assert dgq.linear_workspace_bytes(2048, 44032, 8192, 128) == 0
+    assert dgq.linear_plan(2048, 24576, 8192, 128) == "linear_tiled_kernel<128, 8, 4, 3, false>"   # three whole rounds
+    assert dgq.linear_plan(512, 44032, 8192, 128) == "linear_tiled_kernel<128, 4, 4, 3, false>"    # one round and a third: left alone
 
 
 def test_packed_sizes_zp(dgq):

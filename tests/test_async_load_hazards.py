@@ -117,7 +117,8 @@ def tiled_asm(tmp_path_factory):
 
 def test_no_register_is_touched_while_an_async_load_into_it_is_in_flight(tiled_asm):
     # signed-nibble and zero-point forms, without and with the K of a tile split over workgroups
-    for name in ("linear_tiled_kernel", "linear_tiled_zp_kernel", "linear_tiled_splitk_kernel", "linear_tiled_splitk_zp_kernel"):
+    for name in ("linear_tiled_kernel", "linear_tiled_zp_kernel", "linear_tiled_cols_kernel", "linear_tiled_cols_zp_kernel",
+                 "linear_tiled_splitk_kernel", "linear_tiled_splitk_zp_kernel"):
         kernels, problems = check_asm(tiled_asm, name)
         assert kernels == 12, (name, kernels)      # two group sizes x three tile shapes x {fp16, INT32 test hook}
         assert not problems, "\n".join(problems[:10])

@@ -204,6 +204,10 @@ def test_decode_workspace_contract(dgq, torch):
     (4000, 256, 4096 + 16, 64),      # 32 x 17 narrow tiles, ragged M and N
     (4000, 256, 4096 - 48, 64),      # 32 x 8 = 256 wide tiles: the eight-wavefront 128 x 512 variant, ragged M and N
     (2000, 384, 8192 - 64, 128),     # 16 x 16 wide tiles
+    # two whole rounds of 128 x 512 tiles and more, plus a remainder: two launches, the second on a column range
+    (4000, 256, 2 * 4096 + 16, 64),          # 32 token tiles: a round is 8 column tiles; a remainder of 16 channels
+    (1024, 384, 2 * 16384 + 272, 128),       # 8 token tiles: a round is 32 column tiles
+    (2048, 256, 3 * 8192 + 4096 - 48, 128),  # 16 token tiles, three rounds, ragged remainder with wide tiles of its own
 ])
 def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
     _acc_case(dgq, torch, M, K, N, g, seed=M * 5 + N, path=2)
@@ -420,6 +424,7 @@ def test_acc_bit_exact_zp_decode_kernel(dgq, torch, M, K, N, g):
     (17, 128, 16, 128), (64, 4096, 512, 128), (40, 2048, 272, 64), (33, 384, 1040, 128),     # 64-token tiles, split K
     (130, 384, 320, 64), (300, 640, 1040, 128),                                              # 64-token tiles
     (4000, 256, 4096 + 16, 64), (2000, 384, 8192 - 64, 128),                                 # 128-token tiles, both widths
+    (4000, 256, 2 * 4096 + 16, 64), (2048, 128, 2 * 8192 + 528, 128),                        # whole rounds + remainder: two launches
 ])
 def test_acc_bit_exact_zp_tiled_kernel(dgq, torch, M, K, N, g):
     _acc_case_zp(dgq, torch, M, K, N, g, seed=M + N, path=0 if M > 16 else 2)
