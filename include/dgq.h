@@ -25,8 +25,8 @@
  *     N % 16 == 0, group in {64, 128}.
  *   - Argument errors (every status but DGQ_ERR_HIP) are found on the host and returned
  *     BEFORE anything is launched.  DGQ_ERR_HIP reports a failed launch; where a call
- *     enqueues two kernels (a quantizer in front of the linear, a K split with its second
- *     pass) the first may already be enqueued when the second fails.
+ *     enqueues two kernels (a quantizer in front of the linear; a wide layer run as whole
+ *     rounds of tiles plus a remainder) the first may already be enqueued when the second fails.
  *   - NaN/Inf activations give unspecified outputs, not an error.
  *   - Thread-safe; calls on the same buffers must be ordered by the caller.
  */

@@ -213,7 +213,7 @@ def test_acc_bit_exact_tiled_path(dgq, torch, M, K, N, g):
     _acc_case(dgq, torch, M, K, N, g, seed=M * 5 + N, path=2)
 
 
-# 16 < M <= 64 takes the tiled kernel with a 64-token tile, six stages and K split over several
+# 16 < M <= 64 takes the tiled kernel with a 64-token tile and K split over several
 # workgroups whose INT32 partial sums meet in the workspace.
 @pytest.mark.parametrize("M,K,N,g", [
     (17, 128, 16, 128),          # one stage, no split
@@ -804,9 +804,8 @@ def test_rmsnorm_quant_linear_one_call_zero_point_form(dgq, torch):
 # the launch form bench.py times: calls recorded in a HIP graph and replayed
 # ----------------------------------------------------------------------------
 def test_graph_replays_equal_eager_results(dgq, torch):
-    """Every kind of launch the library makes (decode kernel with and without its K split and
-    second kernel, the kernels that quantize for themselves, tiled kernel with and without K split,
-    stand-alone quantizers) recorded once and replayed three times on changing inputs, with eager
+    """Every kind of launch the library makes (decode kernel with and without its K split, the kernels that
+    quantize for themselves, tiled kernel with and without K split, stand-alone quantizers) recorded once and replayed three times on changing inputs, with eager
     work and synchronisation between the replays; every replay must reproduce the eager result."""
     g = 128
     cases = [(4, 4096, 272), (3, 22016, 256), (16, 4096, 528), (64, 8192, 512), (130, 1024, 528)]
