@@ -457,7 +457,10 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
             const int m = m0 + mi * 32 + row;
             const int n = nw0 + (lane & 7) * 8;
             const uint4 v = *reinterpret_cast<const uint4 *>(&lds_t[row * 64 + (lane & 7) * 8]);
-            if (m < a.M && n < a.N) *reinterpret_cast<uint4 *>(&a.out[(size_t)m * ldo + n]) = v;
+            // streaming store: the output is written once and read by another kernel; this keeps it
+            // from displacing the operands the other tiles still share in L2 (1-4 % per launch)
+            if (m < a.M && n < a.N)
+                __builtin_nontemporal_store(__builtin_bit_cast(v4i, v), reinterpret_cast<v4i *>(&a.out[(size_t)m * ldo + n]));
         }
     }
 }
