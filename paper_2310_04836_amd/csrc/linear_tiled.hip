@@ -180,6 +180,24 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
         goff[q] = (uint32_t)(m - m0) * a.K + (((lane & 7) ^ ((r >> 1) & 7)) << 4);
     }
 
+    // ---- epilogue operands, requested now -----------------------------------------------------
+    // One token scale per thread (threads past the tile's tokens repeat a valid one) and the
+    // channel scales of this lane's two columns.  Asked for here, in front of the first stage, they
+    // cost three registers through the main loop; asked for after it they add a memory latency to
+    // every tile, which shows where a workgroup has its CU to itself (64-token tiles: 1-5 % per
+    // launch).  The 128-token tiles use all 256 registers a wavefront can have at two per SIMD and
+    // gain nothing measurable, so they keep asking late.  These are the oldest vector loads, so the
+    // first wait of the prologue covers them.
+    constexpr bool kEarlyScales = !ACC && MI == 2;
+    uint32_t ep_sx = 0, ep_s1[2] = {0, 0};
+    if constexpr (kEarlyScales) {
+        int mrow = m0 + (tid < BM ? tid : 0);
+        if (mrow >= a.M) mrow = a.M - 1;
+        ep_sx = load_b32_async(a.sx, (uint32_t)mrow * 4u);
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj) ep_s1[nj] = load_b32_async(a.s1, (uint32_t)(ncol[nj] < a.N ? ncol[nj] : a.N - 1) * 4u);
+    }
+
     // LDS byte address of this wavefront's first piece in stage buffer 0
     const uint32_t lds_base = (uint32_t)(size_t)(lptr_t)&lds_a[0][0] + wave * PPW * 1024;
 
@@ -293,6 +311,7 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
     __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 2) * kLoadsPerStage, false));  // the first stage has landed
     __syncthreads();
     DGQ_ARRIVE(0);
+    if constexpr (kEarlyScales) asm volatile("" : "+v"(ep_sx), "+v"(ep_s1[0]), "+v"(ep_s1[1]));
     DGQ_SCALES(0, p0, 0);
 #pragma unroll
     for (int c = 0; c < 4; ++c) DGQ_PREP(0, c, 0, 0);
@@ -434,10 +453,16 @@ __device__ __forceinline__ void tiled_body(const LinearArgs &a, int tiles_m, int
     // stores 16 contiguous bytes and eight lanes cover a whole 128-byte line of the output.
     float *lds_sx = reinterpret_cast<float *>(&lds_a[0][0]);
     unsigned short *lds_t = reinterpret_cast<unsigned short *>(&lds_a[0][0] + 1024 + wave * 4096);
-    if (tid < BM) lds_sx[tid] = (m0 + tid < a.M) ? a.sx[m0 + tid] : 0.0f;
+    if (tid < BM) {
+        if constexpr (kEarlyScales) lds_sx[tid] = (m0 + tid < a.M) ? __builtin_bit_cast(float, ep_sx) : 0.0f;
+        else lds_sx[tid] = (m0 + tid < a.M) ? a.sx[m0 + tid] : 0.0f;
+    }
     float s1n[2];
 #pragma unroll
-    for (int nj = 0; nj < 2; ++nj) s1n[nj] = ncol[nj] < a.N ? a.s1[ncol[nj]] : 0.0f;
+    for (int nj = 0; nj < 2; ++nj) {
+        if constexpr (kEarlyScales) s1n[nj] = ncol[nj] < a.N ? __builtin_bit_cast(float, ep_s1[nj]) : 0.0f;
+        else s1n[nj] = ncol[nj] < a.N ? a.s1[ncol[nj]] : 0.0f;
+    }
     __syncthreads();
     const int nw0 = n0 + wave * 64;
 #pragma unroll
