@@ -56,85 +56,85 @@ SEEDS = {"7b": 1, "13b": 3, "65b": 4}
 # A kernel that has not been profiled in a workload reports null.
 TRAFFIC_BYTES = {
     ("llama65b_g128", "quant_linear_decode_nt_kernel<4, 1, 128>"):
-        ((2.0 * 74617.8 + 1.0 * 67.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 74627.8 + 1.0 * 67.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "quant_linear_decode_kernel<4, 1, 128>"):
-        ((2.0 * 17575.6 + 1.0 * 16.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 17564.8 + 1.0 * 16.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_decode_nt_kernel<6, 1, 128, true>"):
-        ((2.0 * 51208.3 + 1.0 * 1108.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 51213.8 + 1.0 * 1108.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_decode_nt_kernel<4, 1, 128, false>"):
-        ((2.0 * 75172.7 + 1.0 * 536.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 75168.7 + 1.0 * 536.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_decode_kernel<4, 1, 128, false, false>"):
-        ((2.0 * 17895.6 + 1.0 * 128.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 17902.9 + 1.0 * 128.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"):
-        ((2.0 * 44236.2 + 1.0 * 12636.3) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 44235.9 + 1.0 * 12636.3) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_kernel<128, 4, 2, 3, false>"):
-        ((2.0 * 66636.1 + 1.0 * 6848.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 66635.1 + 1.0 * 6848.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_kernel<128, 8, 4, 3, false>"):
-        ((2.0 * 166951.5 + 1.0 * 47111.7) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 166951.5 + 1.0 * 47116.2) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_kernel<128, 4, 4, 3, false>"):
-        ((2.0 * 198402.8 + 1.0 * 44032.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 198468.2 + 1.0 * 44032.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_splitk_kernel<128, 4, 4, 3, false>"):
-        ((2.0 * 119927.2 + 1.0 * 40972.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 119927.1 + 1.0 * 40972.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_cols_kernel<128, 8, 4, 3, false>"):
-        ((2.0 * 415201.1 + 1.0 * 163858.2) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
+        ((2.0 * 415201.2 + 1.0 * 163853.4) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g128", "linear_tiled_cols_kernel<128, 4, 4, 3, false>"):
         ((2.0 * 47744.0 + 1.0 * 12288.0) * 1024, "profiles/llama65b_g128_linear_tiled_kernel.md"),
     ("llama65b_g64", "quant_linear_decode_nt_kernel<4, 1, 64>"):
-        ((2.0 * 76067.8 + 1.0 * 67.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 76086.8 + 1.0 * 67.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "quant_linear_decode_kernel<4, 1, 64>"):
-        ((2.0 * 18345.1 + 1.0 * 16.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 18360.1 + 1.0 * 16.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_decode_nt_kernel<6, 1, 64, true>"):
-        ((2.0 * 51955.2 + 1.0 * 1108.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 51947.3 + 1.0 * 1108.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_decode_nt_kernel<4, 1, 64, false>"):
         ((2.0 * 76614.3 + 1.0 * 536.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_decode_kernel<4, 1, 64, false, false>"):
         ((2.0 * 18639.2 + 1.0 * 128.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_splitk_kernel<64, 4, 2, 3, false>"):
-        ((2.0 * 44798.1 + 1.0 * 12636.3) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 44797.9 + 1.0 * 12636.3) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_kernel<64, 4, 2, 3, false>"):
-        ((2.0 * 67581.1 + 1.0 * 6848.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 67580.6 + 1.0 * 6848.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_kernel<64, 8, 4, 3, false>"):
-        ((2.0 * 169031.5 + 1.0 * 47112.3) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 169036.1 + 1.0 * 47121.7) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_kernel<64, 4, 4, 3, false>"):
-        ((2.0 * 200498.6 + 1.0 * 44032.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 200485.5 + 1.0 * 44032.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_splitk_kernel<64, 4, 4, 3, false>"):
-        ((2.0 * 121265.6 + 1.0 * 40972.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 121269.6 + 1.0 * 40972.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_cols_kernel<64, 8, 4, 3, false>"):
-        ((2.0 * 420320.1 + 1.0 * 163858.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 420323.1 + 1.0 * 163855.7) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama65b_g64", "linear_tiled_cols_kernel<64, 4, 4, 3, false>"):
-        ((2.0 * 48224.5 + 1.0 * 12288.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
+        ((2.0 * 48221.5 + 1.0 * 12288.0) * 1024, "profiles/llama65b_g64_linear_tiled_kernel.md"),
     ("llama13b", "quant_linear_decode_kernel<3, 2, 128>"):
-        ((2.0 * 14895.2 + 1.0 * 20.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 14883.3 + 1.0 * 20.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama13b", "quant_linear_decode_nt_kernel<3, 2, 128>"):
-        ((2.0 * 35879.1 + 1.0 * 54.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 35876.1 + 1.0 * 54.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama13b", "linear_decode_kernel<4, 1, 128, false, true>"):
-        ((2.0 * 19938.8 + 1.0 * 737.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 19918.6 + 1.0 * 737.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama13b", "linear_decode_kernel<3, 2, 128, false, false>"):
-        ((2.0 * 14457.4 + 1.0 * 320.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 14458.9 + 1.0 * 320.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama13b", "linear_decode_nt_kernel<3, 2, 128, false>"):
-        ((2.0 * 37261.3 + 1.0 * 864.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 37251.1 + 1.0 * 864.0) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama13b", "linear_tiled_kernel<128, 8, 4, 3, false>"):
-        ((2.0 * 64045.3 + 1.0 * 30732.4) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 64045.3 + 1.0 * 30737.3) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama13b", "linear_tiled_kernel<128, 4, 4, 3, false>"):
-        ((2.0 * 84117.6 + 1.0 * 25258.7) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
+        ((2.0 * 84124.0 + 1.0 * 25258.7) * 1024, "profiles/llama13b_linear_tiled_kernel.md"),
     ("llama7b_prefill", "linear_tiled_kernel<128, 4, 4, 3, false>"):
-        ((2.0 * 53417.1 + 1.0 * 27648.1) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+        ((2.0 * 53425.8 + 1.0 * 27648.1) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
     ("llama7b_prefill", "linear_tiled_kernel<128, 4, 2, 3, false>"):
-        ((2.0 * 31853.0 + 1.0 * 6826.7) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+        ((2.0 * 31852.5 + 1.0 * 6826.7) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
     ("llama7b_prefill", "linear_tiled_kernel<128, 8, 4, 3, false>"):
-        ((2.0 * 50418.7 + 1.0 * 23299.1) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+        ((2.0 * 50418.7 + 1.0 * 23300.8) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
     ("llama7b_prefill", "linear_tiled_splitk_kernel<128, 4, 2, 3, false>"):
-        ((2.0 * 54536.8 + 1.0 * 20492.0) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+        ((2.0 * 54535.8 + 1.0 * 20492.0) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
     ("llama7b_prefill", "linear_tiled_cols_kernel<128, 8, 4, 3, false>"):
-        ((2.0 * 61385.3 + 1.0 * 44049.9) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
+        ((2.0 * 61385.3 + 1.0 * 44061.4) * 1024, "profiles/prefill_llama7b_linear_tiled_kernel.md"),
     ("llama7b_decode", "quant_linear_decode_kernel<2, 2, 128>"):
-        ((2.0 * 14558.6 + 1.0 * 62.5) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+        ((2.0 * 14564.1 + 1.0 * 62.5) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
     ("llama7b_decode", "quant_linear_decode_kernel<6, 1, 128>"):
-        ((2.0 * 12219.9 + 1.0 * 20.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+        ((2.0 * 12220.9 + 1.0 * 20.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
     ("llama7b_decode", "linear_decode_kernel<2, 2, 128, false, false>"):
-        ((2.0 * 14195.3 + 1.0 * 400.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+        ((2.0 * 14193.6 + 1.0 * 400.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
     ("llama7b_decode", "linear_decode_kernel<6, 1, 128, false, false>"):
-        ((2.0 * 11930.5 + 1.0 * 128.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
+        ((2.0 * 11930.4 + 1.0 * 128.0) * 1024, "profiles/decode_llama7b_quant_linear_decode_kernel.md"),
 }
 
 
